@@ -1,0 +1,163 @@
+"""CPU oracle for the k-NN-graph path -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes access to oracle/knn_oracle.c (plain C, fp64 accumulation).  Only
+tests, the smoke check and the benchmark's CPU-baseline leg may import this
+package; the GPU library and its Python binding never do, and this package
+imports nothing from them.
+"""
+import ctypes
+import numpy as np
+
+from .build import build as _build
+
+L2SQ, IP_UNIT, COSINE = 0, 1, 2
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(_build())
+        c_i32, c_i64, c_f32, c_f64, c_u64 = (ctypes.c_int32, ctypes.c_int64, ctypes.c_float,
+                                             ctypes.c_double, ctypes.c_uint64)
+        P = ctypes.c_void_p
+        L.oracle_distance.restype = c_f32
+        L.oracle_distance.argtypes = [P, P, c_i32, c_i32]
+        L.oracle_num_threads.restype = ctypes.c_int
+        L.oracle_brute_knn.restype = ctypes.c_int
+        L.oracle_brute_knn.argtypes = [P, c_i64, c_i32, c_i32, c_i32, P, c_i64, P, P]
+        L.oracle_graph_recall.restype = c_f64
+        L.oracle_graph_recall.argtypes = [P, P, c_i32, P, P, c_i32, c_i64, c_i32, c_i32]
+        L.oracle_check_graph.restype = c_i64
+        L.oracle_check_graph.argtypes = [P, c_i64, c_i32, c_i32, P, P, c_i32, c_f64, P]
+        L.oracle_nn_descent.restype = ctypes.c_int
+        L.oracle_nn_descent.argtypes = [P, c_i64, c_i32, c_i32, c_i32, c_i32, c_f64, c_f64,
+                                        c_i32, c_i32, c_u64, P, P, P]
+        _lib = L
+    return _lib
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def distance(a, b, metric=L2SQ) -> np.float32:
+    a, b = _f32(a), _f32(b)
+    assert a.ndim == 1 and a.shape == b.shape
+    return np.float32(lib().oracle_distance(_p(a), _p(b), a.shape[0], metric))
+
+
+def brute_knn(points, k, metric=L2SQ, query_rows=None):
+    """Exact k-NN rows for all points (or for query_rows).  -> (ids i32, dists f32)."""
+    x = _f32(points)
+    n, d = x.shape
+    q = None if query_rows is None else _i32(query_rows)
+    nq = n if q is None else q.shape[0]
+    ids = np.empty((nq, k), dtype=np.int32)
+    dists = np.empty((nq, k), dtype=np.float32)
+    rc = lib().oracle_brute_knn(_p(x), n, d, k, metric, _p(q), nq, _p(ids), _p(dists))
+    if rc != 0:
+        raise ValueError(f"oracle_brute_knn: bad arguments (rc={rc})")
+    return ids, dists
+
+
+def graph_recall(test_ids, test_dists, ref_ids, ref_dists, at_k, mode=0) -> float:
+    ti = None if test_ids is None else _i32(test_ids)
+    td = None if test_dists is None else _f32(test_dists)
+    ri = None if ref_ids is None else _i32(ref_ids)
+    rd = None if ref_dists is None else _f32(ref_dists)
+    shape_t = (ti if ti is not None else td).shape
+    shape_r = (ri if ri is not None else rd).shape
+    assert shape_t[0] == shape_r[0]
+    r = lib().oracle_graph_recall(_p(ti), _p(td), shape_t[1], _p(ri), _p(rd), shape_r[1],
+                                  shape_t[0], at_k, mode)
+    if r < 0:
+        raise ValueError("oracle_graph_recall: bad arguments")
+    return float(r)
+
+
+VIOLATION_NAMES = ("id_range", "self_loop", "duplicate_id", "not_ascending",
+                   "distance_mismatch", "bad_distance")
+
+
+def check_graph(points, ids, dists, metric=L2SQ, rel_tol=1e-5, rows=None):
+    """Row invariants of a graph; `rows` = source point of each graph row (default 0..n-1).
+
+    Returns a dict name -> violation count.
+    """
+    x = _f32(points)
+    ids, dists = _i32(ids), _f32(dists)
+    n, d = x.shape
+    if rows is not None:
+        # graph rows belong to a subset of the points: check each against its own source
+        rows = np.asarray(rows, dtype=np.int64)
+        out = dict.fromkeys(VIOLATION_NAMES, 0)
+        for q, r in enumerate(rows):
+            sub = _check_one(x, int(r), ids[q], dists[q], metric, rel_tol)
+            for kname, v in sub.items():
+                out[kname] += v
+        return out
+    assert ids.shape[0] == n
+    viol = np.zeros(6, dtype=np.int64)
+    rc = lib().oracle_check_graph(_p(x), n, d, metric, _p(ids), _p(dists), ids.shape[1],
+                                  rel_tol, _p(viol))
+    if rc < 0:
+        raise ValueError("oracle_check_graph: bad arguments")
+    return dict(zip(VIOLATION_NAMES, (int(v) for v in viol)))
+
+
+def _check_one(x, r, ids_row, dists_row, metric, rel_tol):
+    n = x.shape[0]
+    out = dict.fromkeys(VIOLATION_NAMES, 0)
+    seen = set()
+    for a, (i, l) in enumerate(zip(ids_row.tolist(), dists_row.tolist())):
+        if not (l >= 0.0) or l == float("inf"):
+            out["bad_distance"] += 1
+        if i < 0 or i >= n:
+            out["id_range"] += 1
+            continue
+        if i == r:
+            out["self_loop"] += 1
+        if i in seen:
+            out["duplicate_id"] += 1
+        seen.add(i)
+        if a > 0:
+            pl, pi = float(dists_row[a - 1]), int(ids_row[a - 1])
+            if not (pl < l or (pl == l and pi < i)):
+                out["not_ascending"] += 1
+        s = float(distance(x[r], x[i], metric))
+        if abs(l - s) > rel_tol * s + 1e-30:
+            out["distance_mismatch"] += 1
+    return out
+
+
+def nn_descent(points, k, metric=L2SQ, k_build=None, rho=0.5, delta=1e-4, max_iters=100,
+               cand_cap=0, seed=0):
+    """CPU reference NN-Descent.  -> (ids, dists, stats dict)."""
+    x = _f32(points)
+    n, d = x.shape
+    K = k if k_build is None else k_build
+    ids = np.empty((n, k), dtype=np.int32)
+    dists = np.empty((n, k), dtype=np.float32)
+    stats = np.zeros(3 + max(max_iters, 1), dtype=np.int64)
+    rc = lib().oracle_nn_descent(_p(x), n, d, k, metric, K, rho, delta, max_iters, cand_cap,
+                                 seed, _p(ids), _p(dists), _p(stats))
+    if rc != 0:
+        raise ValueError(f"oracle_nn_descent failed (rc={rc})")
+    it = int(stats[0])
+    return ids, dists, {"iterations": it, "distance_evals": int(stats[1]),
+                        "dropped": int(stats[2]), "updates": stats[3:3 + it].tolist()}

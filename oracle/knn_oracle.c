@@ -1,0 +1,528 @@
+/*
+ * knn_oracle.c -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow CPU statement of what the k-NN-graph path computes.  It exists
+ * so that the tests, the smoke check and the CPU-baseline leg of the benchmark
+ * have something independent to compare the GPU library against.  Nothing in
+ * the product path may include, link or call this file, and this file includes
+ * nothing from the GPU sources.
+ *
+ * Contents (paper passages each one follows are named at the function):
+ *   oracle_distance      sigma(p1,p2): the distance recipes            (Sec. 2.1)
+ *   oracle_brute_knn     the exact k-NN graph by brute force           (Sec. 2.1)
+ *   oracle_graph_recall  recall of one graph against another           (Sec. 2.1, 5.3.1, 5.4.3)
+ *   oracle_check_graph   row invariants of a k-NN graph                (Sec. 2.1)
+ *   oracle_nn_descent    NN-Descent with candidate lists and a
+ *                        single-owner merge, step by step              (Sec. 3.1, 3.1.1)
+ *
+ * Pin status: every function is pinned by tests that do not go through this
+ * file (closed forms, exhaustive enumeration in numpy on tiny inputs, integer
+ * data where all arithmetic is exact, the K = n-1 special case).  What stays
+ * "parity unpinned" is agreement with the outputs of the paper's own
+ * implementation: the paper prints no worked example or per-dataset numbers
+ * for this path.
+ *
+ * Arithmetic: inputs are fp32; every distance is accumulated in IEEE double,
+ * coordinates taken in index order t = 0..d-1 with an explicit fma and no
+ * reassociation, then rounded once to fp32.  Build with -ffp-contract=off.
+ * All orderings are lexicographic on (fp32 distance, id).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_L2SQ = 0, ORACLE_IP_UNIT = 1, ORACLE_COSINE = 2 };
+
+/* ------------------------------------------------------------------------ */
+/* sigma: non-negative, smaller = more similar (Sec. 2.1).                   */
+/*   L2SQ    : sum_t (a_t - b_t)^2                                           */
+/*   IP_UNIT : max(0, 1 - <a,b>)       rows are unit length by contract      */
+/*   COSINE  : max(0, 1 - <a,b>/(|a||b|)); a zero vector is at distance 1    */
+/* ------------------------------------------------------------------------ */
+float oracle_distance(const float *a, const float *b, int32_t d, int32_t metric)
+{
+    double acc = 0.0;
+    if (metric == ORACLE_L2SQ) {
+        for (int32_t t = 0; t < d; ++t) {
+            double df = (double)a[t] - (double)b[t];
+            acc = fma(df, df, acc);
+        }
+        return (float)acc;
+    }
+    for (int32_t t = 0; t < d; ++t)
+        acc = fma((double)a[t], (double)b[t], acc);
+    if (metric == ORACLE_IP_UNIT) {
+        double r = 1.0 - acc;
+        if (r < 0.0) r = 0.0;
+        return (float)r;
+    }
+    /* ORACLE_COSINE */
+    double na = 0.0, nb = 0.0;
+    for (int32_t t = 0; t < d; ++t) na = fma((double)a[t], (double)a[t], na);
+    for (int32_t t = 0; t < d; ++t) nb = fma((double)b[t], (double)b[t], nb);
+    if (na == 0.0 || nb == 0.0) return 1.0f;
+    double r = 1.0 - acc / sqrt(na * nb);
+    if (r < 0.0) r = 0.0;
+    return (float)r;
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* (dist, id) lexicographic "less than" */
+static int key_less(float da, int32_t ia, float db, int32_t ib)
+{
+    return (da < db) || (da == db && ia < ib);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Exact k-NN graph (Sec. 2.1: "the exact kNNG computed by brute force";     */
+/* exactly k neighbours per source point).  For query row r (= query_rows[q] */
+/* or q when query_rows is NULL) every j != r is scored with sigma and the k */
+/* smallest under (fp32 dist, id) are written in ascending order.            */
+/* The only parallelism is one query row per OpenMP iteration.               */
+/* Returns 0, or -1 on bad arguments.                                        */
+/* ------------------------------------------------------------------------ */
+int oracle_brute_knn(const float *points, int64_t n, int32_t d, int32_t k, int32_t metric,
+                     const int32_t *query_rows, int64_t nq,
+                     int32_t *ids_out, float *dists_out)
+{
+    if (!points || !ids_out || !dists_out || n < 2 || d < 1 || k < 1 || k > n - 1 ||
+        metric < 0 || metric > 2 || nq < 0)
+        return -1;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t q = 0; q < nq; ++q) {
+        int64_t r = query_rows ? (int64_t)query_rows[q] : q;
+        const float *x = points + r * (int64_t)d;
+        int32_t *oi = ids_out + q * (int64_t)k;
+        float *od = dists_out + q * (int64_t)k;
+        int32_t cnt = 0;
+        for (int64_t j = 0; j < n; ++j) {
+            if (j == r) continue;
+            float l = oracle_distance(x, points + j * (int64_t)d, d, metric);
+            if (cnt == k && !key_less(l, (int32_t)j, od[k - 1], oi[k - 1])) continue;
+            int32_t p = (cnt < k) ? cnt : k - 1;   /* slot that is free or dropped */
+            while (p > 0 && key_less(l, (int32_t)j, od[p - 1], oi[p - 1])) {
+                od[p] = od[p - 1];
+                oi[p] = oi[p - 1];
+                --p;
+            }
+            od[p] = l;
+            oi[p] = (int32_t)j;
+            if (cnt < k) ++cnt;
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Recall of a test graph against a reference graph, over the nearest at_k   */
+/* entries of each (Sec. 5.3.1: take the nearest 32 of a k >= 32 graph).     */
+/*   mode 0 (Sec. 2.1): fraction of test neighbours whose id also appears in */
+/*           the reference row.                                              */
+/*   mode 1 (Sec. 5.4.3): the reference row's at_k-th distance is a          */
+/*           threshold; fraction of test neighbours at distance <= it.       */
+/* Rows of both graphs are ascending.  Returns the recall, or -1.0 on bad    */
+/* arguments.                                                                */
+/* ------------------------------------------------------------------------ */
+double oracle_graph_recall(const int32_t *test_ids, const float *test_dists, int32_t k_test,
+                           const int32_t *ref_ids, const float *ref_dists, int32_t k_ref,
+                           int64_t n, int32_t at_k, int32_t mode)
+{
+    if (n < 1 || at_k < 1 || at_k > k_test || at_k > k_ref || mode < 0 || mode > 1) return -1.0;
+    if (mode == 0 && (!test_ids || !ref_ids)) return -1.0;
+    if (mode == 1 && (!test_dists || !ref_dists)) return -1.0;
+    int64_t hits = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (mode == 0) {
+            const int32_t *t = test_ids + i * (int64_t)k_test;
+            const int32_t *r = ref_ids + i * (int64_t)k_ref;
+            for (int32_t a = 0; a < at_k; ++a)
+                for (int32_t b = 0; b < at_k; ++b)
+                    if (t[a] == r[b]) { ++hits; break; }
+        } else {
+            const float *t = test_dists + i * (int64_t)k_test;
+            float thr = ref_dists[i * (int64_t)k_ref + (at_k - 1)];
+            for (int32_t a = 0; a < at_k; ++a)
+                if (t[a] <= thr) ++hits;
+        }
+    }
+    return (double)hits / ((double)n * (double)at_k);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Row invariants of a k-NN graph (Sec. 2.1: exactly k neighbours per source */
+/* point, each entry an id and its distance from the source point).          */
+/* violations[0] id out of [0,n)      violations[1] self loop                */
+/* violations[2] duplicate id in row  violations[3] row not ascending under  */
+/*                                                  (dist, id)               */
+/* violations[4] |dist - sigma| > rel_tol*sigma + 1e-30                      */
+/* violations[5] negative or non-finite distance                             */
+/* Returns the total number of violations, or -1 on bad arguments.           */
+/* ------------------------------------------------------------------------ */
+int64_t oracle_check_graph(const float *points, int64_t n, int32_t d, int32_t metric,
+                           const int32_t *ids, const float *dists, int32_t k,
+                           double rel_tol, int64_t violations[6])
+{
+    if (!points || !ids || !dists || !violations || n < 2 || d < 1 || k < 1) return -1;
+    int64_t v0 = 0, v1 = 0, v2 = 0, v3 = 0, v4 = 0, v5 = 0;
+#pragma omp parallel for schedule(static) reduction(+ : v0, v1, v2, v3, v4, v5)
+    for (int64_t i = 0; i < n; ++i) {
+        const int32_t *ri = ids + i * (int64_t)k;
+        const float *rd = dists + i * (int64_t)k;
+        for (int32_t a = 0; a < k; ++a) {
+            int32_t id = ri[a];
+            if (!(rd[a] >= 0.0f) || isinf(rd[a])) ++v5;
+            if (id < 0 || (int64_t)id >= n) { ++v0; continue; }
+            if ((int64_t)id == i) ++v1;
+            for (int32_t b = 0; b < a; ++b)
+                if (ri[b] == id) { ++v2; break; }
+            if (a > 0 && !key_less(rd[a - 1], ri[a - 1], rd[a], id)) ++v3;
+            double s = (double)oracle_distance(points + i * (int64_t)d,
+                                               points + (int64_t)id * d, d, metric);
+            if (fabs((double)rd[a] - s) > rel_tol * s + 1e-30) ++v4;
+        }
+    }
+    violations[0] = v0; violations[1] = v1; violations[2] = v2;
+    violations[3] = v3; violations[4] = v4; violations[5] = v5;
+    return v0 + v1 + v2 + v3 + v4 + v5;
+}
+
+/* ======================================================================== */
+/* NN-Descent with per-point candidate lists (Sec. 3.1 and 3.1.1).           */
+/* ======================================================================== */
+
+/* The oracle's own stateless random numbers: a 64-bit mix of a counter.     */
+static uint64_t mix64(uint64_t z)
+{
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+typedef struct { uint64_t key, ctr; } rng_t;
+static rng_t rng_make(uint64_t seed, uint64_t a, uint64_t b)
+{
+    rng_t r;
+    r.key = mix64(mix64(seed ^ 0x6A09E667F3BCC908ull) + mix64(a * 0x100000001B3ull + b));
+    r.ctr = 0;
+    return r;
+}
+static uint64_t rng_next(rng_t *r) { return mix64(r->key + (r->ctr++) * 0xD1342543DE82EF95ull); }
+/* uniform integer in [0, m), m >= 1 (rejection, unbiased) */
+static uint64_t rng_below(rng_t *r, uint64_t m)
+{
+    uint64_t lim = UINT64_MAX - (UINT64_MAX % m);
+    uint64_t x;
+    do { x = rng_next(r); } while (x >= lim);
+    return x % m;
+}
+/* keep a uniformly random subset of size min(want,cnt) in a[0..], return its size */
+static int32_t choose_uniform(int32_t *a, int32_t cnt, int32_t want, rng_t *r)
+{
+    int32_t m = cnt < want ? cnt : want;
+    for (int32_t i = 0; i < m; ++i) {
+        int32_t j = i + (int32_t)rng_below(r, (uint64_t)(cnt - i));
+        int32_t t = a[i]; a[i] = a[j]; a[j] = t;
+    }
+    return m;
+}
+
+typedef struct { int32_t id; float dist; } cand_t;
+typedef struct { cand_t *v; int32_t cnt, cap; } candlist_t;
+
+typedef struct {
+    int64_t n; int32_t K;
+    int32_t *ids; float *dist; uint8_t *isnew;     /* [n][K], rows ascending */
+    candlist_t *cand; int32_t cand_cap;            /* 0 = unbounded */
+    int64_t dropped;
+} graph_t;
+
+/* Offer (l, b) to point a: appended iff closer than a's current farthest     */
+/* neighbour (Sec. 3.1.1); the list has a fixed size, a full list drops.      */
+static void offer(graph_t *g, int32_t a, int32_t b, float l)
+{
+    const int32_t K = g->K;
+    const float *rd = g->dist + (int64_t)a * K;
+    const int32_t *ri = g->ids + (int64_t)a * K;
+    if (!key_less(l, b, rd[K - 1], ri[K - 1])) return;
+    candlist_t *c = &g->cand[a];
+    if (g->cand_cap > 0 && c->cnt >= g->cand_cap) { ++g->dropped; return; }
+    if (c->cnt == c->cap) {
+        int32_t nc = c->cap ? 2 * c->cap : 16;
+        if (g->cand_cap > 0 && nc > g->cand_cap) nc = g->cand_cap;
+        c->v = (cand_t *)realloc(c->v, sizeof(cand_t) * (size_t)nc);
+        c->cap = nc;
+    }
+    c->v[c->cnt].id = b;
+    c->v[c->cnt].dist = l;
+    ++c->cnt;
+}
+
+/* One owner per point folds its candidate list into its row (Sec. 3.1.1).   */
+/* Returns the number of accepted updates for this row.                      */
+static int64_t merge_row(graph_t *g, int64_t a)
+{
+    const int32_t K = g->K;
+    int32_t *ri = g->ids + a * K;
+    float *rd = g->dist + a * K;
+    uint8_t *rf = g->isnew + a * K;
+    candlist_t *c = &g->cand[a];
+    int64_t acc = 0;
+    for (int32_t e = 0; e < c->cnt; ++e) {
+        int32_t id = c->v[e].id;
+        float l = c->v[e].dist;
+        if (!key_less(l, id, rd[K - 1], ri[K - 1])) continue;
+        int dup = 0;
+        for (int32_t p = 0; p < K; ++p)
+            if (ri[p] == id) { dup = 1; break; }
+        if (dup) continue;
+        int32_t p = K - 1;
+        while (p > 0 && key_less(l, id, rd[p - 1], ri[p - 1])) {
+            rd[p] = rd[p - 1]; ri[p] = ri[p - 1]; rf[p] = rf[p - 1];
+            --p;
+        }
+        rd[p] = l; ri[p] = id; rf[p] = 1;
+        ++acc;
+    }
+    c->cnt = 0;       /* the list is cleared after the update */
+    return acc;
+}
+
+static void append_unique(int32_t *dst, int32_t *cnt, int32_t id)
+{
+    for (int32_t i = 0; i < *cnt; ++i)
+        if (dst[i] == id) return;
+    dst[(*cnt)++] = id;
+}
+
+/*
+ * oracle_nn_descent
+ *
+ *  1. G starts with K distinct random neighbours != v per point, with their
+ *     true distances, rows ascending, every entry flagged new.   (Sec. 3.1)
+ *  2. Per iteration and point: up to s = ceil(rho*K) new-flagged entries,
+ *     chosen uniformly, form the forward new sample (their flags are cleared);
+ *     up to s entries that were not new, chosen uniformly, form the forward
+ *     old sample.  rho = 1 samples everything.                   (Sec. 3.1)
+ *  3. Reverse samples: for each u, up to s uniformly chosen v that hold u in
+ *     their forward new (old) sample.  NEW[v] = forward + reverse new, without
+ *     repeats; OLD[v] likewise, minus anything in NEW[v].
+ *  4. Neighbour check: for every point v, every unordered pair in NEW[v] and
+ *     every pair NEW[v] x OLD[v]: l = sigma(u1,u2); u2 is appended to u1's
+ *     candidate list if it is closer than u1's current farthest neighbour,
+ *     and u1 to u2's.  Lists hold cand_cap entries (0 = unbounded); a full
+ *     list drops.                                                (Sec. 3.1.1)
+ *  5. Each point's list is folded into its row by one owner: ids already
+ *     present and entries no longer closer than the farthest are rejected,
+ *     the rest inserted in order, flagged new, and counted as accepted
+ *     updates; the list is cleared.                              (Sec. 3.1.1)
+ *  6. Stop when the accepted updates of an iteration are < delta*K*n, or
+ *     after max_iters iterations.                                (Sec. 3.1, 5.3.1)
+ *  7. The first k of the K entries of every row are the result.  (Sec. 5.3.1)
+ *
+ * The distance evaluations of step 4 are computed for a batch of points at a
+ * time with one OpenMP iteration per pair; the offers are then made in the
+ * sequential enumeration order, so results do not depend on the thread count.
+ *
+ * stats (optional, int64[3 + max_iters]): [0] iterations run, [1] distance
+ * evaluations, [2] candidates dropped by full lists, [3+i] accepted updates
+ * of iteration i.  Returns 0, -1 on bad arguments, -2 on allocation failure.
+ */
+int oracle_nn_descent(const float *points, int64_t n, int32_t d, int32_t k, int32_t metric,
+                      int32_t K, double rho, double delta, int32_t max_iters,
+                      int32_t cand_cap, uint64_t seed,
+                      int32_t *ids_out, float *dists_out, int64_t *stats)
+{
+    if (!points || !ids_out || !dists_out || n < 2 || d < 1 || k < 1 || K < k ||
+        (int64_t)K > n - 1 || metric < 0 || metric > 2 || !(rho > 0.0) || rho > 1.0 ||
+        delta < 0.0 || max_iters < 0 || cand_cap < 0)
+        return -1;
+    int32_t s = (int32_t)ceil(rho * (double)K);
+    if (s > K) s = K;
+    if (s < 1) s = 1;
+
+    graph_t g;
+    g.n = n; g.K = K; g.cand_cap = cand_cap; g.dropped = 0;
+    g.ids = (int32_t *)malloc(sizeof(int32_t) * (size_t)n * K);
+    g.dist = (float *)malloc(sizeof(float) * (size_t)n * K);
+    g.isnew = (uint8_t *)malloc((size_t)n * K);
+    g.cand = (candlist_t *)calloc((size_t)n, sizeof(candlist_t));
+    /* forward samples [n][s] + counts; full lists [n][2s] + counts */
+    int32_t *newf = (int32_t *)malloc(sizeof(int32_t) * (size_t)n * s);
+    int32_t *oldf = (int32_t *)malloc(sizeof(int32_t) * (size_t)n * s);
+    int32_t *newf_cnt = (int32_t *)calloc((size_t)n, sizeof(int32_t));
+    int32_t *oldf_cnt = (int32_t *)calloc((size_t)n, sizeof(int32_t));
+    int32_t *NEW = (int32_t *)malloc(sizeof(int32_t) * (size_t)n * 2 * s);
+    int32_t *OLD = (int32_t *)malloc(sizeof(int32_t) * (size_t)n * 2 * s);
+    int32_t *NEW_cnt = (int32_t *)calloc((size_t)n, sizeof(int32_t));
+    int32_t *OLD_cnt = (int32_t *)calloc((size_t)n, sizeof(int32_t));
+    int64_t *rev_off = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+    int32_t *rev_src = (int32_t *)malloc(sizeof(int32_t) * (size_t)n * s);
+    if (!g.ids || !g.dist || !g.isnew || !g.cand || !newf || !oldf || !newf_cnt || !oldf_cnt ||
+        !NEW || !OLD || !NEW_cnt || !OLD_cnt || !rev_off || !rev_src)
+        return -2;
+
+    int64_t n_eval = 0;
+
+    /* ---- step 1: random initial graph ---- */
+#pragma omp parallel for schedule(static) reduction(+ : n_eval)
+    for (int64_t v = 0; v < n; ++v) {
+        rng_t r = rng_make(seed, 1, (uint64_t)v);
+        int32_t *ri = g.ids + v * K;
+        float *rd = g.dist + v * K;
+        if ((int64_t)K * 2 > n - 1) {
+            /* dense case: partial shuffle of all other points */
+            int32_t *all = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n - 1));
+            int32_t m = 0;
+            for (int64_t j = 0; j < n; ++j) if (j != v) all[m++] = (int32_t)j;
+            choose_uniform(all, m, K, &r);
+            memcpy(ri, all, sizeof(int32_t) * (size_t)K);
+            free(all);
+        } else {
+            int32_t c = 0;
+            while (c < K) {
+                int32_t id = (int32_t)rng_below(&r, (uint64_t)n);
+                if (id == v) continue;
+                int dup = 0;
+                for (int32_t p = 0; p < c; ++p) if (ri[p] == id) { dup = 1; break; }
+                if (!dup) ri[c++] = id;
+            }
+        }
+        for (int32_t p = 0; p < K; ++p)
+            rd[p] = oracle_distance(points + v * (int64_t)d, points + (int64_t)ri[p] * d, d, metric);
+        n_eval += K;
+        /* ascending by (dist, id): insertion sort */
+        for (int32_t p = 1; p < K; ++p) {
+            float l = rd[p]; int32_t id = ri[p]; int32_t q = p;
+            while (q > 0 && key_less(l, id, rd[q - 1], ri[q - 1])) {
+                rd[q] = rd[q - 1]; ri[q] = ri[q - 1]; --q;
+            }
+            rd[q] = l; ri[q] = id;
+        }
+        memset(g.isnew + v * K, 1, (size_t)K);
+    }
+
+    /* pair buffers for one batch of points */
+    const int64_t BATCH = 1024;
+    const int64_t max_pairs_pt = (int64_t)(2 * s) * (2 * s - 1) / 2 + (int64_t)(2 * s) * (2 * s);
+    int32_t *pa = (int32_t *)malloc(sizeof(int32_t) * (size_t)(BATCH * max_pairs_pt));
+    int32_t *pb = (int32_t *)malloc(sizeof(int32_t) * (size_t)(BATCH * max_pairs_pt));
+    float *pl = (float *)malloc(sizeof(float) * (size_t)(BATCH * max_pairs_pt));
+    if (!pa || !pb || !pl) return -2;
+
+    int32_t it = 0;
+    for (; it < max_iters; ++it) {
+        /* ---- step 2: forward samples ---- */
+        for (int64_t v = 0; v < n; ++v) {
+            rng_t r = rng_make(seed, 2 + 4 * (uint64_t)it, (uint64_t)v);
+            int32_t posn[K > 0 ? K : 1], poso[K > 0 ? K : 1];
+            int32_t cn = 0, co = 0;
+            for (int32_t p = 0; p < K; ++p) {
+                if (g.isnew[v * K + p]) posn[cn++] = p; else poso[co++] = p;
+            }
+            int32_t mn = choose_uniform(posn, cn, s, &r);
+            int32_t mo = choose_uniform(poso, co, s, &r);
+            for (int32_t i = 0; i < mn; ++i) {
+                newf[v * s + i] = g.ids[v * K + posn[i]];
+                g.isnew[v * K + posn[i]] = 0;
+            }
+            for (int32_t i = 0; i < mo; ++i) oldf[v * s + i] = g.ids[v * K + poso[i]];
+            newf_cnt[v] = mn; oldf_cnt[v] = mo;
+        }
+        /* ---- step 3: reverse samples, then the full lists ---- */
+        for (int pass = 0; pass < 2; ++pass) {
+            const int32_t *fwd = pass == 0 ? newf : oldf;
+            const int32_t *fcnt = pass == 0 ? newf_cnt : oldf_cnt;
+            int32_t *FULL = pass == 0 ? NEW : OLD;
+            int32_t *FCNT = pass == 0 ? NEW_cnt : OLD_cnt;
+            memset(rev_off, 0, sizeof(int64_t) * (size_t)(n + 1));
+            for (int64_t v = 0; v < n; ++v)
+                for (int32_t i = 0; i < fcnt[v]; ++i) ++rev_off[fwd[v * s + i] + 1];
+            for (int64_t u = 0; u < n; ++u) rev_off[u + 1] += rev_off[u];
+            {
+                int64_t *cur = (int64_t *)malloc(sizeof(int64_t) * (size_t)n);
+                if (!cur) return -2;
+                memcpy(cur, rev_off, sizeof(int64_t) * (size_t)n);
+                for (int64_t v = 0; v < n; ++v)
+                    for (int32_t i = 0; i < fcnt[v]; ++i) rev_src[cur[fwd[v * s + i]]++] = (int32_t)v;
+                free(cur);
+            }
+            for (int64_t u = 0; u < n; ++u) {
+                rng_t r = rng_make(seed, 3 + pass + 4 * (uint64_t)it, (uint64_t)u);
+                int32_t *dst = FULL + u * 2 * s;
+                int32_t c = 0;
+                for (int32_t i = 0; i < fcnt[u]; ++i) {
+                    int32_t id = fwd[u * s + i];
+                    int skip = 0;
+                    if (pass == 1)      /* OLD excludes what is in NEW */
+                        for (int32_t j = 0; j < NEW_cnt[u]; ++j)
+                            if (NEW[u * 2 * s + j] == id) { skip = 1; break; }
+                    if (!skip) append_unique(dst, &c, id);
+                }
+                int32_t rc = (int32_t)(rev_off[u + 1] - rev_off[u]);
+                int32_t *src = rev_src + rev_off[u];
+                int32_t m = choose_uniform(src, rc, s, &r);
+                for (int32_t i = 0; i < m; ++i) {
+                    int32_t id = src[i];
+                    int skip = 0;
+                    if (pass == 1)
+                        for (int32_t j = 0; j < NEW_cnt[u]; ++j)
+                            if (NEW[u * 2 * s + j] == id) { skip = 1; break; }
+                    if (!skip) append_unique(dst, &c, id);
+                }
+                FCNT[u] = c;
+            }
+        }
+        /* ---- step 4: neighbour check, offers into candidate lists ---- */
+        for (int64_t v0 = 0; v0 < n; v0 += BATCH) {
+            int64_t v1 = v0 + BATCH < n ? v0 + BATCH : n;
+            int64_t np = 0;
+            for (int64_t v = v0; v < v1; ++v) {
+                const int32_t *nw = NEW + v * 2 * s; int32_t cn = NEW_cnt[v];
+                const int32_t *ol = OLD + v * 2 * s; int32_t co = OLD_cnt[v];
+                for (int32_t i = 0; i < cn; ++i) {
+                    for (int32_t j = i + 1; j < cn; ++j) { pa[np] = nw[i]; pb[np] = nw[j]; ++np; }
+                    for (int32_t j = 0; j < co; ++j) { pa[np] = nw[i]; pb[np] = ol[j]; ++np; }
+                }
+            }
+#pragma omp parallel for schedule(static)
+            for (int64_t e = 0; e < np; ++e)
+                pl[e] = oracle_distance(points + (int64_t)pa[e] * d, points + (int64_t)pb[e] * d, d, metric);
+            n_eval += np;
+            for (int64_t e = 0; e < np; ++e) {
+                offer(&g, pa[e], pb[e], pl[e]);
+                offer(&g, pb[e], pa[e], pl[e]);
+            }
+        }
+        /* ---- step 5: single-owner merge, count accepted updates ---- */
+        int64_t c = 0;
+        for (int64_t a = 0; a < n; ++a) c += merge_row(&g, a);
+        if (stats) stats[3 + it] = c;
+        /* ---- step 6: convergence ---- */
+        if ((double)c < delta * (double)K * (double)n) { ++it; break; }
+    }
+    if (stats) { stats[0] = it; stats[1] = n_eval; stats[2] = g.dropped; }
+
+    /* ---- step 7: truncate to k ---- */
+    for (int64_t v = 0; v < n; ++v) {
+        memcpy(ids_out + v * k, g.ids + v * K, sizeof(int32_t) * (size_t)k);
+        memcpy(dists_out + v * k, g.dist + v * K, sizeof(float) * (size_t)k);
+    }
+    for (int64_t a = 0; a < n; ++a) free(g.cand[a].v);
+    free(g.cand); free(g.ids); free(g.dist); free(g.isnew);
+    free(newf); free(oldf); free(newf_cnt); free(oldf_cnt);
+    free(NEW); free(OLD); free(NEW_cnt); free(OLD_cnt);
+    free(rev_off); free(rev_src); free(pa); free(pb); free(pl);
+    return 0;
+}
