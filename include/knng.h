@@ -1,0 +1,160 @@
+/*
+ * knng.h -- C ABI of libknng: single-GPU k-nearest-neighbour-graph construction
+ * for AMD MI355X (gfx950), after the local kNNG construction of SOLANET
+ * (paper Sec. 3.1 "NN-Descent" and Sec. 3.1.1 "Lock-Free GPU-based NN-Descent").
+ *
+ * Conventions for every entry point
+ *   - Pointers named *_dev are DEVICE pointers (hipMalloc-class memory, as the
+ *     paper passes its dataset: Sec. 5.3.1); pointers named *_host are HOST
+ *     pointers.  The caller owns every buffer; the library never frees or keeps
+ *     a caller pointer after the call returns.
+ *   - The dataset is n feature vectors of equal dimensionality d, a row-major
+ *     fp32 matrix points[n][d] (Sec. 2.1).  It is read-only and never copied.
+ *   - A graph is two row-major matrices ids[rows][k] (int32) and
+ *     dists[rows][k] (fp32), exactly k entries per row, rows ascending under
+ *     (distance, id) (Sec. 2.1: G_id and G_dis).
+ *   - Distances (Sec. 2.1: sigma >= 0, smaller = more similar):
+ *       KNNG_METRIC_L2SQ     sum_t (a_t - b_t)^2
+ *       KNNG_METRIC_IP_UNIT  max(0, 1 - <a,b>); the caller guarantees unit rows
+ *     Every distance WRITTEN to an output is accumulated in fp64 over
+ *     t = 0..d-1 in index order with fused multiply-add and rounded once to
+ *     fp32.  Inputs must be finite; NaN/Inf inputs give unspecified ordering
+ *     (never a fault).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it; each call has completed on return.
+ *   - Return value: 0 (KNNG_OK) or a negative KNNG_E* code; knng_strerror()
+ *     gives text.  On KNNG_EINVAL / KNNG_EWORKSPACE nothing has been written.
+ *   - n <= 2^31 - 1; all byte offsets are 64-bit.
+ *   - Calls that overlap in time must not share a workspace.
+ */
+#ifndef KNNG_H
+#define KNNG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KNNG_VERSION 1
+
+enum {
+    KNNG_OK = 0,
+    KNNG_EINVAL = -1,      /* bad argument (null pointer, n < 2, k < 1, k > n-1, ...) */
+    KNNG_EWORKSPACE = -2,  /* workspace missing or smaller than knng_*_workspace_bytes */
+    KNNG_EHIP = -3         /* a HIP call failed; knng_strerror(KNNG_EHIP) has its text */
+};
+
+enum { KNNG_METRIC_L2SQ = 0, KNNG_METRIC_IP_UNIT = 1 };
+
+#define KNNG_MAX_K 64            /* largest k / k_build / cand_cap */
+#define KNNG_STATS_MAX_ITERS 128 /* per-iteration records kept in knng_stats_t */
+
+/* Filled by knng_build_knn_graph when params->stats_host != NULL (host memory). */
+typedef struct knng_stats {
+    int32_t iterations;        /* refinement iterations run                        */
+    int32_t converged;         /* 1: stopped by updates < delta*K*n; 0: max_iters  */
+    uint64_t updates[KNNG_STATS_MAX_ITERS]; /* accepted updates per iteration       */
+    float join_ms[KNNG_STATS_MAX_ITERS];    /* local-join kernel time per iteration */
+    uint64_t join_rows[KNNG_STATS_MAX_ITERS]; /* vectors gathered by that launch    */
+    float ms_init, ms_sample, ms_join, ms_merge, ms_finalize; /* summed kernel ms   */
+    float ms_total;            /* first enqueue to last completion                  */
+    uint64_t offers;           /* candidates offered to candidate lists (atomics)   */
+} knng_stats_t;
+
+/*
+ * Parameters of the build (Sec. 3.1: k, delta, rho; Sec. 5.3.1: iteration cap and
+ * a build degree larger than the target k).  Zero in a numeric field selects the
+ * default.  struct_size must be sizeof(knng_params_t) (ABI check).
+ */
+typedef struct knng_params {
+    uint32_t struct_size;
+    int32_t k_build;          /* K: internal degree, k <= K <= min(n-1, KNNG_MAX_K); default k.
+                                 The result is the nearest k of the K (Sec. 5.3.1).           */
+    float rho;                /* sampling rate in (0,1]; default 0.5 (Sec. 3.1, 5.4)           */
+    float delta;              /* stop when an iteration accepts < delta*K*n updates;
+                                 default 1e-4; negative = never stop early (Sec. 3.1)          */
+    int32_t max_iters;        /* default 100 (Sec. 5.3.1); negative = 0 iterations             */
+    int32_t cand_cap;         /* slots of each point's fixed-size candidate list
+                                 (Sec. 3.1.1), 1..KNNG_MAX_K; default K                        */
+    uint64_t seed;
+    const int32_t *init_ids_dev; /* optional warm start [n][K] (device); entries that are out
+                                 of range, self or repeated are replaced by random ids; NULL =
+                                 random initial graph (Sec. 3.1)                              */
+    void *stream;             /* hipStream_t; NULL = default stream                            */
+    void *workspace_dev;      /* device scratch, >= knng_build_workspace_bytes(), 256-B aligned */
+    uint64_t workspace_bytes;
+    knng_stats_t *stats_host; /* optional                                                      */
+} knng_params_t;
+
+/* Device scratch needed by knng_build_knn_graph for these sizes (0 on bad arguments). */
+uint64_t knng_build_workspace_bytes(int64_t n, int32_t d, int32_t k, const knng_params_t *params);
+
+/*
+ * Approximate k-NN graph of the n points (Sec. 3.1, 3.1.1).
+ *
+ * Random initial graph; then per iteration: per-point sampling of new and old
+ * neighbours (rate rho) with reverse edges; a local join per point that
+ * evaluates the distances among its sampled neighbours; every close pair is
+ * offered, lock-free, to the two points' fixed-size candidate lists when it
+ * beats their current farthest neighbour; one owner per point folds its list
+ * into its row and clears it.  Iterates until an iteration accepts fewer than
+ * delta*K*n updates or max_iters is reached (reaching max_iters is a normal
+ * return).  Finally every kept (point, neighbour) distance is recomputed in
+ * the fp64 recipe above, rows are sorted by (distance, id) and cut to k.
+ *
+ * points_dev [n][d] fp32 (device, read-only); ids_out_dev [n][k] int32 and
+ * dists_out_dev [n][k] fp32 (device, written in full on success).
+ * Errors: KNNG_EINVAL for null pointers, n < 2, d < 1, k < 1, K < k,
+ * K > min(n-1, KNNG_MAX_K), rho outside (0,1], cand_cap outside [1, KNNG_MAX_K],
+ * unknown metric, wrong struct_size; KNNG_EWORKSPACE; KNNG_EHIP.
+ * Host-synchronises `stream` once per iteration (the convergence test).
+ */
+int knng_build_knn_graph(const float *points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,
+                         const knng_params_t *params, int32_t *ids_out_dev, float *dists_out_dev);
+
+/* Device scratch needed by knng_brute_knn (0 on bad arguments). */
+uint64_t knng_brute_workspace_bytes(int64_t n, int32_t d, int32_t k, int64_t nq);
+
+/*
+ * Exact k-NN rows by brute force (Sec. 2.1: the exact kNNG recall is measured
+ * against; Sec. 5.3.1: ground truth "computed by a brute-force method").
+ *
+ * For query q the source point is r = query_rows_dev ? query_rows_dev[q] : q;
+ * every j != r is scored and the k smallest under (fp32 distance, id) are
+ * written ascending to ids_out_dev[q][0..k) / dists_out_dev[q][0..k).
+ * nq rows are produced (nq = n and query_rows_dev = NULL gives the whole graph);
+ * nq = 0 is a no-op.  k <= min(n-1, KNNG_MAX_K).  Results are deterministic.
+ */
+int knng_brute_knn(const float *points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,
+                   const int32_t *query_rows_dev, int64_t nq,
+                   int32_t *ids_out_dev, float *dists_out_dev,
+                   void *workspace_dev, uint64_t workspace_bytes, void *stream);
+
+/*
+ * Recall of a test graph against a reference graph over the nearest at_k
+ * entries of each row (Sec. 5.3.1), rows ascending in both.
+ *   mode 0 (Sec. 2.1): share of the test neighbours whose id also appears in
+ *          the reference row.  Needs the two id matrices.
+ *   mode 1 (Sec. 5.4.3): the reference row's at_k-th distance is a threshold;
+ *          share of the test neighbours with distance <= it.  Needs the two
+ *          distance matrices.
+ * test_* are [rows][k_test], ref_* are [rows][k_ref] (device); at_k <= both.
+ * The matrices a mode does not need may be NULL.  *recall_out_host (host)
+ * receives hits / (rows * at_k).  Allocates and frees 8 bytes of device memory.
+ */
+int knng_graph_recall(const int32_t *test_ids_dev, const float *test_dists_dev, int32_t k_test,
+                      const int32_t *ref_ids_dev, const float *ref_dists_dev, int32_t k_ref,
+                      int64_t rows, int32_t at_k, int32_t mode,
+                      double *recall_out_host, void *stream);
+
+/* Text for a return code; for KNNG_EHIP the text of the last HIP failure on this thread. */
+const char *knng_strerror(int code);
+
+/* KNNG_VERSION the library was built from. */
+int knng_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KNNG_H */

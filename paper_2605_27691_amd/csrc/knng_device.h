@@ -1,0 +1,79 @@
+// Device-side helpers shared by the libknng kernels (gfx950, 64-wide wavefronts).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace knng {
+
+typedef unsigned long long u64;
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int WAVE = 64;
+constexpr u64 EMPTY_KEY = ~0ull;
+
+// ---- packed neighbour entries -------------------------------------------------------------
+// A neighbour is one 64-bit word: [63:32] fp32 distance bits, [31:1] id, [0] "new" flag.
+// Distances are >= +0, so the words order exactly like (distance, id): one integer compare
+// (or one 64-bit atomic min) implements the (distance, id) order of the k-NN rows.
+__device__ __forceinline__ float nonneg(float x) { return x > 0.0f ? x : 0.0f; }
+__device__ __forceinline__ u64 pack_key(float dist, int id, int isnew)
+{
+    return ((u64)__float_as_uint(dist) << 32) | ((u64)(uint32_t)id << 1) | (u64)(isnew & 1);
+}
+__device__ __forceinline__ int key_id(u64 key) { return (int)((uint32_t)key >> 1); }
+__device__ __forceinline__ float key_dist(u64 key) { return __uint_as_float((uint32_t)(key >> 32)); }
+__device__ __forceinline__ u64 key_order(u64 key) { return key & ~1ull; }
+
+// ---- stateless random numbers ---------------------------------------------------------------
+// Counter-based: every draw is a hash of (seed, stream tag, row, slot); nothing is stored.
+__device__ __forceinline__ uint32_t hash32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352du;
+    x ^= x >> 15; x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+__device__ __forceinline__ uint32_t rnd32(u64 seed, uint32_t tag, uint32_t row, uint32_t slot)
+{
+    uint32_t h = hash32((uint32_t)seed ^ 0x9e3779b9u);
+    h = hash32(h ^ (uint32_t)(seed >> 32));
+    h = hash32(h + tag * 0x85ebca6bu);
+    h = hash32(h ^ row);
+    return hash32(h + slot * 0xc2b2ae35u);
+}
+// uniform-enough integer in [0, m): high half of a 32x32 product
+__device__ __forceinline__ uint32_t below(uint32_t r, uint32_t m) { return __umulhi(r, m); }
+
+// ---- wavefront helpers ------------------------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (WAVE - 1)); }
+__device__ __forceinline__ u64 lanemask_lt() { return (1ull << lane_id()) - 1ull; }
+// value held by lane `src` (src uniform across the wave)
+__device__ __forceinline__ uint32_t bcast32(uint32_t v, int src)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, src);
+}
+__device__ __forceinline__ u64 bcast64(u64 v, int src)
+{
+    uint32_t lo = bcast32((uint32_t)v, src), hi = bcast32((uint32_t)(v >> 32), src);
+    return ((u64)hi << 32) | lo;
+}
+
+// ---- the exact distance recipe ------------------------------------------------------------------
+// Accumulate in fp64 over t ascending with fma, one rounding to fp32 at the end.  The state
+// of one (a,b) pair is a single double so the chain can be continued across slabs of d.
+template <int METRIC> __device__ __forceinline__ double exact_step(double acc, float a, float b)
+{
+    if (METRIC == 0) {
+        double df = (double)a - (double)b;
+        return fma(df, df, acc);
+    }
+    return fma((double)a, (double)b, acc);
+}
+template <int METRIC> __device__ __forceinline__ float exact_finish(double acc)
+{
+    if (METRIC == 0) return (float)acc;
+    double r = 1.0 - acc;
+    return (float)(r > 0.0 ? r : 0.0);
+}
+
+}  // namespace knng

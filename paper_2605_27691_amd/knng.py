@@ -1,0 +1,215 @@
+"""ctypes binding over libknng.so: argument marshalling only.
+
+Every step of the path runs in the HIP library; torch is used for device
+memory (inputs, outputs, workspace) and for the current stream.  If the
+library is missing and cannot be built, calls raise: there is no fallback.
+Function names and argument meaning follow include/knng.h.
+"""
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+L2SQ, IP_UNIT = 0, 1
+MAX_K = 64
+STATS_MAX_ITERS = 128
+
+_P = ctypes.c_void_p
+
+
+class Stats(ctypes.Structure):
+    _fields_ = [("iterations", ctypes.c_int32),
+                ("converged", ctypes.c_int32),
+                ("updates", ctypes.c_uint64 * STATS_MAX_ITERS),
+                ("join_ms", ctypes.c_float * STATS_MAX_ITERS),
+                ("join_rows", ctypes.c_uint64 * STATS_MAX_ITERS),
+                ("ms_init", ctypes.c_float), ("ms_sample", ctypes.c_float),
+                ("ms_join", ctypes.c_float), ("ms_merge", ctypes.c_float),
+                ("ms_finalize", ctypes.c_float), ("ms_total", ctypes.c_float),
+                ("offers", ctypes.c_uint64)]
+
+
+class Params(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32),
+                ("k_build", ctypes.c_int32),
+                ("rho", ctypes.c_float),
+                ("delta", ctypes.c_float),
+                ("max_iters", ctypes.c_int32),
+                ("cand_cap", ctypes.c_int32),
+                ("seed", ctypes.c_uint64),
+                ("init_ids_dev", _P),
+                ("stream", _P),
+                ("workspace_dev", _P),
+                ("workspace_bytes", ctypes.c_uint64),
+                ("stats_host", ctypes.POINTER(Stats))]
+
+
+EXPORTS = ("knng_build_workspace_bytes", "knng_build_knn_graph", "knng_brute_workspace_bytes",
+           "knng_brute_knn", "knng_graph_recall", "knng_strerror", "knng_version")
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _build.LIB
+
+
+def load():
+    """Load libknng.so (building it once if no built library is present)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build(force=True)
+    L = ctypes.CDLL(_build.LIB)
+    i32, i64, u64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64
+    L.knng_build_workspace_bytes.restype = u64
+    L.knng_build_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(Params)]
+    L.knng_build_knn_graph.restype = ctypes.c_int
+    L.knng_build_knn_graph.argtypes = [_P, i64, i32, i32, i32, ctypes.POINTER(Params), _P, _P]
+    L.knng_brute_workspace_bytes.restype = u64
+    L.knng_brute_workspace_bytes.argtypes = [i64, i32, i32, i64]
+    L.knng_brute_knn.restype = ctypes.c_int
+    L.knng_brute_knn.argtypes = [_P, i64, i32, i32, i32, _P, i64, _P, _P, _P, u64, _P]
+    L.knng_graph_recall.restype = ctypes.c_int
+    L.knng_graph_recall.argtypes = [_P, _P, i32, _P, _P, i32, i64, i32, i32,
+                                    ctypes.POINTER(ctypes.c_double), _P]
+    L.knng_strerror.restype = ctypes.c_char_p
+    L.knng_strerror.argtypes = [ctypes.c_int]
+    L.knng_version.restype = ctypes.c_int
+    L.knng_version.argtypes = []
+    _lib = L
+    return L
+
+
+class KnngError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        super().__init__(f"libknng error {code}: {load().knng_strerror(code).decode()}")
+
+
+def _check(code: int):
+    if code != 0:
+        raise KnngError(code)
+
+
+def _dev(t, dtype, name):
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: expected a contiguous {dtype} tensor on the GPU")
+    return t
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def knng_version() -> int:
+    return int(load().knng_version())
+
+
+def make_params(k_build=0, rho=0.0, delta=0.0, max_iters=0, cand_cap=0, seed=0) -> Params:
+    p = Params()
+    p.struct_size = ctypes.sizeof(Params)
+    p.k_build, p.rho, p.delta, p.max_iters, p.cand_cap, p.seed = (
+        int(k_build), float(rho), float(delta), int(max_iters), int(cand_cap), int(seed))
+    return p
+
+
+def knng_build_workspace_bytes(n, d, k, params=None) -> int:
+    return int(load().knng_build_workspace_bytes(n, d, k, ctypes.byref(params) if params else None))
+
+
+def knng_build_knn_graph(points, k, metric=L2SQ, *, k_build=0, rho=0.0, delta=0.0, max_iters=0,
+                         cand_cap=0, seed=0, init_ids=None, workspace=None, want_stats=True,
+                         ids_out=None, dists_out=None):
+    """Approximate k-NN graph of `points` ([n][d] fp32, GPU).  -> (ids, dists, stats | None).
+
+    Zero-valued keyword parameters select the library defaults; max_iters=-1 runs
+    no refinement iteration (random graph).  `workspace` (uint8 GPU tensor) is
+    allocated here when not given.
+    """
+    L = load()
+    points = _dev(points, torch.float32, "points")
+    n, d = points.shape
+    p = make_params(k_build, rho, delta, max_iters, cand_cap, seed)
+    need = int(L.knng_build_workspace_bytes(n, d, k, ctypes.byref(p)))
+    if need == 0:
+        raise KnngError(-1)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=points.device)
+    workspace = _dev(workspace, torch.uint8, "workspace")
+    init_ids = _dev(init_ids, torch.int32, "init_ids")
+    if ids_out is None:
+        ids_out = torch.empty((n, k), dtype=torch.int32, device=points.device)
+    if dists_out is None:
+        dists_out = torch.empty((n, k), dtype=torch.float32, device=points.device)
+    ids_out = _dev(ids_out, torch.int32, "ids_out")
+    dists_out = _dev(dists_out, torch.float32, "dists_out")
+    st = Stats() if want_stats else None
+    p.init_ids_dev = _ptr(init_ids)
+    p.stream = _stream()
+    p.workspace_dev = _ptr(workspace)
+    p.workspace_bytes = workspace.numel()
+    if st is not None:
+        p.stats_host = ctypes.pointer(st)
+    _check(L.knng_build_knn_graph(_ptr(points), n, d, k, metric, ctypes.byref(p),
+                                  _ptr(ids_out), _ptr(dists_out)))
+    stats = None
+    if st is not None:
+        it = min(st.iterations, STATS_MAX_ITERS)
+        stats = {"iterations": st.iterations, "converged": bool(st.converged),
+                 "updates": list(st.updates[:it]), "join_ms": list(st.join_ms[:it]),
+                 "join_rows": list(st.join_rows[:it]), "ms_init": st.ms_init,
+                 "ms_sample": st.ms_sample, "ms_join": st.ms_join, "ms_merge": st.ms_merge,
+                 "ms_finalize": st.ms_finalize, "ms_total": st.ms_total}
+    return ids_out, dists_out, stats
+
+
+def knng_brute_workspace_bytes(n, d, k, nq) -> int:
+    return int(load().knng_brute_workspace_bytes(n, d, k, nq))
+
+
+def knng_brute_knn(points, k, metric=L2SQ, query_rows=None, workspace=None):
+    """Exact k-NN rows of all points, or of `query_rows` (int32 GPU tensor).  -> (ids, dists)."""
+    L = load()
+    points = _dev(points, torch.float32, "points")
+    n, d = points.shape
+    query_rows = _dev(query_rows, torch.int32, "query_rows")
+    nq = n if query_rows is None else query_rows.numel()
+    need = int(L.knng_brute_workspace_bytes(n, d, k, nq))
+    if need == 0:
+        raise KnngError(-1)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=points.device)
+    workspace = _dev(workspace, torch.uint8, "workspace")
+    ids = torch.empty((nq, k), dtype=torch.int32, device=points.device)
+    dists = torch.empty((nq, k), dtype=torch.float32, device=points.device)
+    _check(L.knng_brute_knn(_ptr(points), n, d, k, metric, _ptr(query_rows), nq, _ptr(ids), _ptr(dists),
+                            _ptr(workspace), workspace.numel(), _stream()))
+    return ids, dists
+
+
+def knng_graph_recall(test_ids, test_dists, ref_ids, ref_dists, at_k, mode=0) -> float:
+    """Recall of a test graph against a reference graph over the nearest at_k entries."""
+    L = load()
+    test_ids = _dev(test_ids, torch.int32, "test_ids")
+    ref_ids = _dev(ref_ids, torch.int32, "ref_ids")
+    test_dists = _dev(test_dists, torch.float32, "test_dists")
+    ref_dists = _dev(ref_dists, torch.float32, "ref_dists")
+    t = test_ids if test_ids is not None else test_dists
+    r = ref_ids if ref_ids is not None else ref_dists
+    if t is None or r is None or t.shape[0] != r.shape[0]:
+        raise KnngError(-1)
+    out = ctypes.c_double(0.0)
+    _check(L.knng_graph_recall(_ptr(test_ids), _ptr(test_dists), t.shape[1], _ptr(ref_ids),
+                               _ptr(ref_dists), r.shape[1], t.shape[0], at_k, mode,
+                               ctypes.byref(out), _stream()))
+    return float(out.value)

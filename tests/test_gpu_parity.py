@@ -1,0 +1,245 @@
+"""GPU parity: libknng (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: indices of the exact graph bit-exact (ties by id); every distance the build writes
+within 1e-5 relative of the oracle's recomputation (the implementation aims at 0 ulp); the
+approximate graph satisfies the row invariants and reaches recall@k >= 0.95.
+"""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_27691_amd import knng, workloads
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _gpu(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+
+
+def _brute_both(x, k, metric, rows=None):
+    gi, gd = knng.knng_brute_knn(_gpu(x), k, metric, None if rows is None else _gpu(rows))
+    oi, od = oracle.brute_knn(x, k, metric, query_rows=rows)
+    return gi.cpu().numpy(), gd.cpu().numpy(), oi, od
+
+
+# ------------------------------------------------------------------ brute_knn
+def test_brute_config0_full_bit_exact():
+    x, w = workloads.make(0)
+    gi, gd, oi, od = _brute_both(x, w.k, w.metric)
+    assert np.array_equal(gi, oi)
+    assert np.array_equal(gd.view(np.uint32), od.view(np.uint32))
+
+
+@pytest.mark.parametrize("n,d,k,metric", [
+    (2, 1, 1, 0), (65, 3, 64, 0), (130, 33, 7, 0), (1000, 128, 32, 0), (4133, 96, 32, 1),
+    (777, 50, 20, 1), (300, 960, 16, 0), (129, 4, 1, 0)])
+def test_brute_ragged_shapes_bit_exact(n, d, k, metric):
+    rng = np.random.default_rng(n * 131 + d)
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    if metric == 1:
+        x = (x / np.linalg.norm(x, axis=1, keepdims=True)).astype(np.float32)
+    gi, gd, oi, od = _brute_both(x, k, metric)
+    assert np.array_equal(gi, oi)
+    assert np.array_equal(gd.view(np.uint32), od.view(np.uint32))
+
+
+def test_brute_ties_are_broken_by_id():
+    e = np.eye(70, dtype=np.float32)                       # all pairs equidistant
+    for metric in (0, 1):
+        gi, gd, oi, od = _brute_both(e, 9, metric)
+        assert np.array_equal(gi, oi) and np.array_equal(gd, od)
+        assert gi[5].tolist() == [0, 1, 2, 3, 4, 6, 7, 8, 9]
+    same = np.full((200, 8), 0.25, np.float32)             # identical points, distance 0
+    gi, gd, oi, od = _brute_both(same, 12, 0)
+    assert np.array_equal(gi, oi) and np.all(gd == 0.0)
+    rc = np.array([(r, c) for r in range(40) for c in range(40)], np.float32)   # lattice shells
+    gi, gd, oi, od = _brute_both(rc, 24, 0)
+    assert np.array_equal(gi, oi) and np.array_equal(gd, od)
+
+
+def test_brute_integer_valued_data_config1_shape():
+    x, w = workloads.make(1, n=30_000)                     # many exact ties at integer distances
+    rows = workloads.sample_rows(30_000, 1500)
+    gi, gd, oi, od = _brute_both(x, w.k, w.metric, rows)
+    assert np.array_equal(gi, oi) and np.array_equal(gd, od)
+
+
+def test_brute_query_rows_and_split_reduction():
+    x, w = workloads.make(0, n=20_000)
+    rows = np.array([19_999, 0, 7, 7, 12_345], np.int32)   # few queries => many base ranges
+    gi, gd, oi, od = _brute_both(x, w.k, w.metric, rows)
+    assert np.array_equal(gi, oi) and np.array_equal(gd, od)
+    # nq = 0 is a no-op
+    empty = torch.empty(0, dtype=torch.int32, device=DEV)
+    ei, ed = knng.knng_brute_knn(_gpu(x), 4, 0, empty)
+    assert ei.shape == (0, 4)
+
+
+def test_brute_argument_errors():
+    x = _gpu(np.zeros((10, 4), np.float32))
+    with pytest.raises(knng.KnngError):
+        knng.knng_brute_knn(x, 10, 0)                      # k > n-1
+    with pytest.raises(knng.KnngError):
+        knng.knng_brute_knn(x, 3, 7)                       # unknown metric
+    ws = torch.empty(8, dtype=torch.uint8, device=DEV)
+    with pytest.raises(knng.KnngError) as ei:
+        knng.knng_brute_knn(x, 3, 0, workspace=ws)
+    assert ei.value.code == -2
+
+
+# ------------------------------------------------------------------ graph_recall
+def test_recall_matches_oracle_both_modes():
+    rng = np.random.default_rng(5)
+    n, kt, kr = 5000, 12, 16
+    ti = rng.integers(0, 60, (n, kt)).astype(np.int32)
+    ri = rng.integers(0, 60, (n, kr)).astype(np.int32)
+    td = np.sort(rng.random((n, kt)).astype(np.float32), axis=1)
+    rd = np.sort(rng.random((n, kr)).astype(np.float32), axis=1)
+    for at_k in (1, 5, 12):
+        for mode in (0, 1):
+            want = oracle.graph_recall(ti, td, ri, rd, at_k, mode)
+            got = knng.knng_graph_recall(_gpu(ti), _gpu(td), _gpu(ri), _gpu(rd), at_k, mode)
+            assert got == want
+    assert knng.knng_graph_recall(_gpu(ri), None, _gpu(ri), None, kr, 0) == 1.0
+    with pytest.raises(knng.KnngError):
+        knng.knng_graph_recall(_gpu(ti), _gpu(td), _gpu(ri), _gpu(rd), 13, 0)
+
+
+# ------------------------------------------------------------------ build_knn_graph
+def _check_build(x, k, metric, ids, dists, exact=None, min_recall=None):
+    ids, dists = ids.cpu().numpy(), dists.cpu().numpy()
+    viol = oracle.check_graph(x, ids, dists, metric, rel_tol=1e-5)
+    assert sum(viol.values()) == 0, viol
+    exact_viol = oracle.check_graph(x, ids, dists, metric, rel_tol=0.0)
+    assert exact_viol["distance_mismatch"] == 0            # the fp64 recipe is reproduced exactly
+    if exact is not None:
+        rec = oracle.graph_recall(ids, dists, exact[0], exact[1], k, 0)
+        rec1 = oracle.graph_recall(ids, dists, exact[0], exact[1], k, 1)
+        assert rec1 >= rec
+        if min_recall is not None:
+            assert rec >= min_recall, rec
+        return rec
+    return None
+
+
+def test_build_config0_invariants_distances_and_recall():
+    x, w = workloads.make(0)
+    exact = oracle.brute_knn(x, w.k, w.metric)
+    ids, dists, st = knng.knng_build_knn_graph(_gpu(x), w.k, w.metric, k_build=32, rho=0.5, seed=1)
+    rec = _check_build(x, w.k, w.metric, ids, dists, exact, min_recall=0.95)
+    assert st["iterations"] < 100 and st["converged"]
+    thr = 1e-4 * 32 * w.n
+    assert st["updates"][-1] < thr and all(u >= thr for u in st["updates"][:-1])
+    # the GPU recall routine agrees with the oracle's on the GPU's own output
+    g = knng.knng_graph_recall(ids, dists, _gpu(exact[0]), _gpu(exact[1]), w.k, 0)
+    assert g == pytest.approx(rec, abs=1e-12)
+
+
+@pytest.mark.parametrize("idx,n,kb,rho", [(1, 30_000, 32, 0.5), (2, 30_000, 32, 0.5), (3, 6_000, 32, 0.5),
+                                         (0, 5_003, 48, 0.8), (0, 3_001, 64, 1.0), (2, 4_000, 17, 1.0)])
+def test_build_other_shapes_and_metrics(idx, n, kb, rho):
+    x, w = workloads.make(idx, n=n)
+    k = min(w.k, kb)
+    exact = oracle.brute_knn(x, k, w.metric)
+    ids, dists, st = knng.knng_build_knn_graph(_gpu(x), k, w.metric, k_build=kb, rho=rho, seed=3)
+    _check_build(x, k, w.metric, ids, dists, exact, min_recall=0.95)
+
+
+def test_build_odd_dimension_uses_the_scalar_path():
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((3000, 13)).astype(np.float32)
+    exact = oracle.brute_knn(x, 10, 0)
+    ids, dists, _ = knng.knng_build_knn_graph(_gpu(x), 10, 0, k_build=20, rho=1.0, seed=2)
+    _check_build(x, 10, 0, ids, dists, exact, min_recall=0.95)
+
+
+@pytest.mark.parametrize("metric", (0, 1))
+def test_build_full_degree_is_the_exact_graph(metric):
+    rng = np.random.default_rng(21)
+    n, d, k = 40, 6, 5
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    if metric == 1:
+        x = (x / np.linalg.norm(x, axis=1, keepdims=True)).astype(np.float32)
+    oi, od = oracle.brute_knn(x, k, metric)
+    for iters in (-1, 3):
+        ids, dists, _ = knng.knng_build_knn_graph(_gpu(x), k, metric, k_build=n - 1, rho=1.0,
+                                                  delta=-1.0, max_iters=iters, seed=5)
+        assert np.array_equal(ids.cpu().numpy(), oi)
+        assert np.array_equal(dists.cpu().numpy(), od)
+
+
+def test_build_random_start_and_monotone_refinement():
+    x, w = workloads.make(0, n=4000)
+    k = 10
+    exact = oracle.brute_knn(x, k, w.metric)
+    prev = None
+    for iters in (-1, 1, 2, 4, 8):
+        ids, dists, st = knng.knng_build_knn_graph(_gpu(x), k, w.metric, rho=1.0, delta=-1.0,
+                                                   max_iters=iters, seed=11)
+        rec = _check_build(x, k, w.metric, ids, dists, exact)
+        assert st["iterations"] == max(iters, 0)
+        if iters == -1:
+            assert rec < 0.05
+        else:
+            assert rec >= prev - 0.01
+        prev = rec
+    assert prev >= 0.9
+
+
+def test_build_warm_start_keeps_a_good_graph():
+    x, w = workloads.make(0, n=3000)
+    k = 12
+    oi, od = oracle.brute_knn(x, k, w.metric)
+    init = oi.copy()
+    init[:, 0] = -7                     # an invalid entry per row is replaced, not trusted
+    ids, dists, st = knng.knng_build_knn_graph(_gpu(x), k, w.metric, rho=1.0, init_ids=_gpu(init), seed=4)
+    _check_build(x, k, w.metric, ids, dists, (oi, od), min_recall=0.99)
+
+
+def test_build_candidate_capacity_and_heavy_contention():
+    # tiny n with K close to n: every join hits the same few rows
+    rng = np.random.default_rng(13)
+    x = rng.standard_normal((70, 5)).astype(np.float32)
+    exact = oracle.brute_knn(x, 8, 0)
+    ids, dists, _ = knng.knng_build_knn_graph(_gpu(x), 8, 0, k_build=30, rho=1.0, cand_cap=3, seed=6)
+    _check_build(x, 8, 0, ids, dists, exact, min_recall=0.9)
+    x, w = workloads.make(0, n=6000)
+    exact = oracle.brute_knn(x, w.k, w.metric)
+    ids, dists, _ = knng.knng_build_knn_graph(_gpu(x), w.k, w.metric, k_build=32, cand_cap=4, seed=6)
+    _check_build(x, w.k, w.metric, ids, dists, exact, min_recall=0.9)
+
+
+def test_build_small_distances_keep_their_precision():
+    # tight unit-norm clusters: true cosine distances around 1e-5 (paper Sec. 5.3.2: a library
+    # that mishandles such small distances collapses)
+    rng = np.random.default_rng(17)
+    c = rng.standard_normal((20, 64))
+    x = c[rng.integers(0, 20, 4000)] + 3e-3 * rng.standard_normal((4000, 64))
+    x = (x / np.linalg.norm(x, axis=1, keepdims=True)).astype(np.float32)
+    exact = oracle.brute_knn(x, 16, 1)
+    assert np.median(exact[1]) < 1e-4
+    ids, dists, _ = knng.knng_build_knn_graph(_gpu(x), 16, 1, k_build=32, rho=1.0, seed=8)
+    _check_build(x, 16, 1, ids, dists, exact, min_recall=0.9)
+
+
+def test_build_argument_errors_leave_outputs_untouched():
+    x = _gpu(np.random.default_rng(0).standard_normal((100, 8)).astype(np.float32))
+    for kw in (dict(k_build=4), dict(rho=1.5), dict(k_build=100), dict(cand_cap=65)):
+        with pytest.raises(knng.KnngError) as ei:
+            knng.knng_build_knn_graph(x, 8, 0, **kw)
+        assert ei.value.code == -1
+    with pytest.raises(knng.KnngError):
+        knng.knng_build_knn_graph(x, 8, 5)
+    ids = torch.full((100, 8), -5, dtype=torch.int32, device=DEV)
+    dists = torch.full((100, 8), -5.0, device=DEV)
+    ws = torch.empty(256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(knng.KnngError) as ei:
+        knng.knng_build_knn_graph(x, 8, 0, workspace=ws, ids_out=ids, dists_out=dists)
+    assert ei.value.code == -2
+    assert bool((ids == -5).all()) and bool((dists == -5.0).all())

@@ -1,0 +1,77 @@
+"""The C-ABI library loads and exports what include/knng.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_27691_amd import knng
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    with open(os.path.join(ROOT, "include", "knng.h")) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(knng_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    assert _declared_functions() == sorted(knng.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = knng.load()
+    for name in _declared_functions():
+        assert hasattr(lib, name), name
+    assert knng.knng_version() == 1
+
+
+def test_struct_layouts_match_the_header_sizes():
+    # params: u32 i32 f32 f32 i32 i32 u64 ptr ptr ptr u64 ptr = 72 bytes on LP64
+    assert ctypes.sizeof(knng.Params) == 72
+    # stats: 2*i32 + 128*u64 + 128*f32 + 128*u64 + 6*f32 + u64 (8-byte aligned)
+    assert ctypes.sizeof(knng.Stats) == 8 + 1024 + 512 + 1024 + 24 + 8
+
+
+def test_workspace_queries_are_host_only_and_validate():
+    p = knng.make_params()
+    b = knng.knng_build_workspace_bytes(1_000_000, 128, 32, p)
+    # G + candidate slots + two sample lists + counters + thresholds, 256-B aligned pieces
+    n, K, C, s = 1_000_000, 32, 32, 16
+    assert b >= n * (K * 8 + C * 8 + 2 * (2 * s * 4) + 16 + 4)
+    assert b % 256 == 0
+    assert knng.knng_build_workspace_bytes(1, 128, 32, p) == 0          # n < 2
+    assert knng.knng_build_workspace_bytes(100, 128, 100, p) == 0       # k > n-1 / MAX_K
+    assert knng.knng_build_workspace_bytes(100, 0, 8, p) == 0           # d < 1
+    bad = knng.make_params(rho=1.5)
+    assert knng.knng_build_workspace_bytes(1000, 16, 8, bad) == 0
+    bad = knng.make_params(k_build=4)
+    assert knng.knng_build_workspace_bytes(1000, 16, 8, bad) == 0       # K < k
+    bad = knng.make_params()
+    bad.struct_size = 8
+    assert knng.knng_build_workspace_bytes(1000, 16, 8, bad) == 0       # ABI mismatch
+    assert knng.knng_brute_workspace_bytes(1000, 16, 8, 1000) >= 1000 * 8 * 8
+    assert knng.knng_brute_workspace_bytes(1000, 16, 65, 1000) == 0
+    assert knng.knng_brute_workspace_bytes(1000, 16, 8, -1) == 0
+
+
+def test_error_text():
+    lib = knng.load()
+    assert lib.knng_strerror(0) == b"success"
+    assert b"invalid" in lib.knng_strerror(-1)
+    assert b"workspace" in lib.knng_strerror(-2)
+    assert lib.knng_strerror(-99) is not None
+
+
+def test_argument_errors_are_reported_before_any_gpu_work():
+    lib = knng.load()
+    p = knng.make_params()
+    # null pointers / bad sizes are rejected by validation alone
+    assert lib.knng_build_knn_graph(None, 100, 8, 4, 0, ctypes.byref(p), None, None) == -1
+    assert lib.knng_brute_knn(None, 100, 8, 4, 0, None, 100, None, None, None, 0, None) == -1
+    out = ctypes.c_double(-1.0)
+    assert lib.knng_graph_recall(None, None, 4, None, None, 4, 10, 4, 0, ctypes.byref(out), None) == -1
+    assert lib.knng_graph_recall(None, None, 4, None, None, 4, 10, 5, 1, ctypes.byref(out), None) == -1
+    assert out.value == -1.0
