@@ -1,0 +1,150 @@
+#!/usr/bin/env python3
+"""Benchmark of the single-GPU k-NN-graph build (one MI355X).
+
+A step is one whole build (`knng_build_knn_graph`: init, all sample/join/merge
+iterations until convergence, finalize) of the workload, with the points
+already resident in HBM.  Prints ONE JSON line:
+
+  value      build throughput, points/s (n / seconds per build)
+  roofline   the local-join kernel: algorithmic bytes of its launches in the
+             timed region / their summed duration (HIP events recorded by the
+             library on its stream), against 8 TB/s HBM
+  cpu_baseline  the CPU oracle's NN-Descent timed on a bounded sample of the
+             same recipe, on the host cores
+
+Recall@k is measured outside the timed region against the exact rows of a
+seeded sample of points (GPU brute force, itself compared bit-for-bit with the
+CPU oracle on a few rows); the run fails if recall@k < 0.95.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+SIG_BYTES = 32          # row signature read per gathered member
+# HBM bytes per join launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a
+# copy kernel of known size); see profiles/.  None until measured for the default workload.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=1, help="workload index (0..4)")
+    ap.add_argument("--n", type=int, default=0, help="override the number of points")
+    ap.add_argument("--k-build", type=int, default=0)
+    ap.add_argument("--rho", type=float, default=0.0)
+    ap.add_argument("--delta", type=float, default=0.0)
+    ap.add_argument("--recall-rows", type=int, default=20000)
+    ap.add_argument("--oracle-rows", type=int, default=128)
+    ap.add_argument("--cpu-n", type=int, default=60000, help="points of the CPU-baseline sample (0 = skip)")
+    return ap.parse_args()
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (nothing here uses a second GPU)",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2605_27691_amd import knng, workloads
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    x, w = workloads.make(a.config, n=(a.n or None), device=dev)
+    n, d, k = w.n, w.d, w.k
+    kw = dict(k_build=a.k_build, rho=a.rho, delta=a.delta)
+    p = knng.make_params(**kw)
+    ws = torch.empty(knng.knng_build_workspace_bytes(n, d, k, p), dtype=torch.uint8, device=dev)
+    ids = torch.empty((n, k), dtype=torch.int32, device=dev)
+    dists = torch.empty((n, k), dtype=torch.float32, device=dev)
+
+    def step(seed):
+        return knng.knng_build_knn_graph(x, k, w.metric, seed=seed, workspace=ws, ids_out=ids,
+                                         dists_out=dists, **kw)[2]
+
+    for i in range(a.warmup):
+        step(1000 + i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    stats = [step(i) for i in range(a.steps)]
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / max(a.steps, 1)
+
+    # ---- roofline of the dominant kernel (local join), over the timed region
+    join_ms = sum(sum(s["join_ms"]) for s in stats)
+    launches = sum(len(s["join_ms"]) for s in stats)
+    rows = sum(sum(s["join_rows"]) for s in stats)
+    alg_bytes = rows * (4 * d + 4 + 4 + SIG_BYTES) + launches * n * 16
+    achieved = alg_bytes / (join_ms * 1e-3) / 1e9 if join_ms > 0 else 0.0
+    last = stats[-1]
+
+    # ---- quality, outside the timed region
+    rows_s = workloads.sample_rows(n, a.recall_rows)
+    rows_d = torch.from_numpy(rows_s).to(dev)
+    ex_i, ex_d = knng.knng_brute_knn(x, k, w.metric, rows_d)
+    sel = rows_d.long()
+    t_i, t_d = ids[sel].contiguous(), dists[sel].contiguous()
+    recall = knng.knng_graph_recall(t_i, t_d, ex_i, ex_d, k, 0)
+    recall_dist = knng.knng_graph_recall(t_i, t_d, ex_i, ex_d, k, 1)
+
+    # ---- the oracle: exact rows and row invariants on a few sampled rows, then the CPU baseline
+    import oracle
+    xh = x.cpu().numpy()
+    sub = np.arange(0, len(rows_s), max(1, len(rows_s) // max(a.oracle_rows, 1)))[:a.oracle_rows]
+    o_i, o_d = oracle.brute_knn(xh, k, w.metric, query_rows=rows_s[sub])
+    brute_ok = bool(np.array_equal(o_i, ex_i[sub].cpu().numpy()) and
+                    np.array_equal(o_d, ex_d[sub].cpu().numpy()))
+    viol = oracle.check_graph(xh, t_i[sub].cpu().numpy(), t_d[sub].cpu().numpy(), w.metric,
+                              rel_tol=1e-5, rows=rows_s[sub])
+    cpu = None
+    if a.cpu_n > 0:
+        xs, wsml = workloads.make(a.config, n=min(a.cpu_n, n))
+        Kb = a.k_build or k
+        t1 = time.perf_counter()
+        _, _, ost = oracle.nn_descent(xs, k, w.metric, k_build=Kb, rho=(a.rho or 0.5),
+                                      delta=(a.delta or 1e-4), max_iters=100, seed=0)
+        cpu_sec = time.perf_counter() - t1
+        cpu = {"value": wsml.n / cpu_sec, "unit": "points/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"oracle NN-Descent (fp64 distances) on {wsml.n} points of the same recipe "
+                         f"({wsml.n_centres} centres), {ost['iterations']} iterations, {cpu_sec:.1f} s"}
+
+    out = {
+        "metric": "kNN-graph build points/sec at recall@k>=0.95 (1 MI355X)",
+        "value": n / sec, "unit": "points/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n": n, "d": d, "k": k, "metric": ["l2sq", "ip_unit"][w.metric],
+                   "k_build": a.k_build or k, "rho": a.rho or 0.5, "delta": a.delta or 1e-4,
+                   "iterations": last["iterations"], "converged": last["converged"]},
+        "recall_at_k": recall, "recall_at_k_distance": recall_dist, "recall_rows": int(len(rows_s)),
+        "oracle_check": {"brute_rows_bit_exact": brute_ok, "rows": int(len(sub)),
+                         "graph_violations": int(sum(viol.values()))},
+        "kernel_ms": {"init": last["ms_init"], "sample": last["ms_sample"], "join": last["ms_join"],
+                      "merge": last["ms_merge"], "finalize": last["ms_finalize"], "total": last["ms_total"]},
+        "roofline": {"kernel": "k_join", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
+                     "launches": launches, "avg_launch_ms": join_ms / max(launches, 1),
+                     "alg_bytes_per_launch": alg_bytes / max(launches, 1)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    if recall < 0.95 or not brute_ok or sum(viol.values()) != 0:
+        print(f"bench.py: quality gate failed (recall={recall:.4f}, brute_ok={brute_ok}, viol={viol})",
+              file=sys.stderr)
+        sys.exit(1)
+
+
+if __name__ == "__main__":
+    main()

@@ -61,6 +61,35 @@ __device__ __forceinline__ float dist_group8(const float* __restrict__ a, const 
 }
 
 // ------------------------------------------------------------------------------------------
+// Row signature: a 256-bit Bloom-style set of the ids in a point's row (bit hash(id) & 255).
+// The join uses it to skip partners a member most likely already holds: such offers would be
+// rejected by the merge anyway, cost an atomic each, and would shadow real candidates in the
+// hashed candidate slots.  A false positive (about 12% at K = 32) only delays a candidate.
+// k_sample rebuilds every row's signature each iteration, right before the join reads it.
+// ------------------------------------------------------------------------------------------
+constexpr int SIG_WORDS = 8;
+// The bit an id maps to changes with the iteration (salt), so a false positive does not
+// shadow the same candidate for good.
+__device__ __forceinline__ uint32_t sig_bit(int id, uint32_t salt)
+{
+    return hash32((uint32_t)id ^ (salt * 0x9e3779b9u + 0x5bd1e995u)) & 255u;
+}
+// every lane contributes id (if has); lane w < 8 writes word w of the OR
+__device__ __forceinline__ void store_signature(uint32_t* __restrict__ dst, int id, bool has, uint32_t salt)
+{
+    const uint32_t h = sig_bit(id, salt);
+    uint32_t mine = 0;
+#pragma unroll
+    for (int w = 0; w < SIG_WORDS; ++w) {
+        uint32_t x = (has && (h >> 5) == (uint32_t)w) ? (1u << (h & 31u)) : 0u;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) x |= __shfl_xor(x, o);
+        if (lane_id() == w) mine = x;
+    }
+    if (lane_id() < SIG_WORDS) dst[lane_id()] = mine;
+}
+
+// ------------------------------------------------------------------------------------------
 // k_init: one wavefront per point.  K distinct ids != v (random, or the caller's warm start
 // with bad entries redrawn), their distances, row sorted by (distance, id), all flagged new.
 // Also puts the point's candidate slots, counters and threshold into their start state.
@@ -133,7 +162,8 @@ k_init(const float* __restrict__ pts, int64_t n, int d, int K, int C, u64 seed,
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 k_sample(int64_t n, int K, int s, u64 seed, uint32_t iter, u64* __restrict__ G,
-         int32_t* __restrict__ newl, int32_t* __restrict__ oldl, int32_t* __restrict__ cnt)
+         int32_t* __restrict__ newl, int32_t* __restrict__ oldl, int32_t* __restrict__ cnt,
+         uint32_t* __restrict__ sig)
 {
     const int lane = lane_id();
     const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -143,6 +173,7 @@ k_sample(int64_t n, int K, int s, u64 seed, uint32_t iter, u64* __restrict__ G,
     const bool isnew = active && (e & 1ull);
     const bool isold = active && !(e & 1ull);
     const int id = key_id(e);
+    store_signature(sig + v * SIG_WORDS, id, active, iter);
     const u64 newmask = __ballot(isnew), oldmask = __ballot(isold);
     const int cn = __popcll(newmask), co = __popcll(oldmask);
     const u64 lt = lanemask_lt();
@@ -214,6 +245,13 @@ k_count_rows(int64_t n, int s, const int32_t* __restrict__ cnt, u64* __restrict_
 //
 // S16 = number of 16-row tiles of NEW (2s <= 16*S16); DS = slab length in floats.
 // ------------------------------------------------------------------------------------------
+// Each member's partners are split into 4 residue classes (partner index mod 4), one per
+// lane; the closest partner of each class is offered (1, 2 or 4 offers per member and join).
+#ifndef KNNG_OFFERS_PER_MEMBER
+#define KNNG_OFFERS_PER_MEMBER 4
+#endif
+constexpr int OFFERS_PER_MEMBER = KNNG_OFFERS_PER_MEMBER;
+
 template <int S16> struct JoinCfg {
     static constexpr int MROWS = 16 * S16;            // max |NEW|
     static constexpr int NCOLS = 32 * S16;            // max |NEW| + |OLD|
@@ -222,14 +260,14 @@ template <int S16> struct JoinCfg {
     static constexpr int LDD = NCOLS + 1;             // row stride of the distance block
     static constexpr int NI = (S16 * S16 + 3) / 4;    // work items (16x32 outputs) per wavefront
     static constexpr int XBYTES = NCOLS * LD * 4 > MROWS * LDD * 4 ? NCOLS * LD * 4 : MROWS * LDD * 4;
-    static constexpr int LDS_BYTES = XBYTES + DS * 4 + NCOLS * 12;
+    static constexpr int LDS_BYTES = XBYTES + DS * 4 + NCOLS * (16 + 4 * SIG_WORDS);
 };
 
 template <int METRIC, int S16, bool VEC>
 __global__ void __launch_bounds__(256)
-k_join(const float* __restrict__ pts, int64_t n, int d, int K, int C, int s,
+k_join(const float* __restrict__ pts, int64_t n, int d, int K, int C, int s, uint32_t iter,
        const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl, int32_t* __restrict__ cnt,
-       const float* __restrict__ worst, u64* __restrict__ cand)
+       const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand)
 {
     using Cfg = JoinCfg<S16>;
     constexpr int DS = Cfg::DS, LD = Cfg::LD, LDD = Cfg::LDD, NI = Cfg::NI;
@@ -239,6 +277,8 @@ k_join(const float* __restrict__ pts, int64_t n, int d, int K, int C, int s,
     int* mid = reinterpret_cast<int*>(pivot + DS);             // [NCOLS] member ids
     float* nrm = reinterpret_cast<float*>(mid + Cfg::NCOLS);   // [NCOLS] |x_m - x_v|^2
     float* thr = nrm + Cfg::NCOLS;                             // [NCOLS] farthest-neighbour distance
+    uint32_t* hb = reinterpret_cast<uint32_t*>(thr + Cfg::NCOLS);  // [NCOLS] signature bit of the id
+    uint32_t* sg = hb + Cfg::NCOLS;                            // [NCOLS][SIG_WORDS] row signatures
 
     const int64_t v = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -262,6 +302,14 @@ k_join(const float* __restrict__ pts, int64_t n, int d, int K, int C, int s,
         mid[m] = id;
         thr[m] = worst[id];
         nrm[m] = 0.0f;
+        hb[m] = sig_bit(id, iter);
+    }
+    for (int i = tid; i < nTot * (SIG_WORDS / 4); i += 256) {      // 2 x 16 bytes per member
+        const int m = i / (SIG_WORDS / 4), q = i % (SIG_WORDS / 4);
+        int id;
+        if (m < nNew) id = newl[lbase + (m < nfn ? m : s + (m - nfn))];
+        else { int o = m - nNew; id = oldl[lbase + (o < nfo ? o : s + (o - nfo))]; }
+        reinterpret_cast<uint4*>(sg)[i] = reinterpret_cast<const uint4*>(sig + (int64_t)id * SIG_WORDS)[q];
     }
 
     floatx4 acc[NI][2];
@@ -329,6 +377,22 @@ k_join(const float* __restrict__ pts, int64_t n, int d, int K, int C, int s,
         }
     }
     __syncthreads();                                       // all wavefronts done with the slab
+    // The pivot's reverse members hold v in their rows, so |x_m - x_v|^2 is already known here:
+    // offer them to v itself (closes v<-m edges into v->m without an extra distance).
+    for (int m = tid; m < nTot; m += 256) {
+        const bool rev = (m >= nfn && m < nNew) || (m >= nNew + nfo);
+        if (!rev) continue;
+        float l = nrm[m];
+        if (METRIC == 1) l *= 0.5f;
+        l = nonneg(l);
+        const int pid = mid[m];
+        const uint32_t h = hb[m];
+        const uint32_t vw = sig[v * SIG_WORDS + (h >> 5)];
+        if (l < worst[v] && !((vw >> (h & 31u)) & 1u)) {
+            const uint32_t slot = below(hash32((uint32_t)pid), (uint32_t)C);
+            atomicMin(&cand[v * C + slot], pack_key(l, pid, 1));
+        }
+    }
     // distance block D[row][col] over the slab storage
     float* D = X;
 #pragma unroll
@@ -351,30 +415,31 @@ k_join(const float* __restrict__ pts, int64_t n, int d, int K, int C, int s,
         }
     }
     __syncthreads();
-    // per-member closest partner: 4 lanes per member
-    for (int m0 = 0; m0 < nTot; m0 += 64) {
-        const int m = m0 + (tid >> 2), sub = tid & 3;
+    // per-member candidates: LPM lanes per member, each lane scans the partners of one residue
+    // class (partner index mod LPM) and offers the closest of its class
+    constexpr int LPM = OFFERS_PER_MEMBER;
+    for (int m0 = 0; m0 < nTot; m0 += 256 / LPM) {
+        const int m = m0 + tid / LPM, sub = tid % LPM;
+        if (m >= nTot) continue;
+        const int myid = mid[m];
+        const uint32_t* msig = sg + m * SIG_WORDS;
         u64 best = EMPTY_KEY;
-        int myid = -1;
-        if (m < nTot) {
-            myid = mid[m];
-            if (m < nNew) {
-                for (int j = sub; j < nTot; j += 4) {
-                    if (mid[j] == myid) continue;
-                    u64 cnd = ((u64)__float_as_uint(D[m * LDD + j]) << 32) | (uint32_t)j;
-                    best = cnd < best ? cnd : best;
-                }
-            } else {
-                for (int i = sub; i < nNew; i += 4) {
-                    if (mid[i] == myid) continue;
-                    u64 cnd = ((u64)__float_as_uint(D[i * LDD + m]) << 32) | (uint32_t)i;
-                    best = cnd < best ? cnd : best;
-                }
+        if (m < nNew) {
+            for (int j = sub; j < nTot; j += LPM) {
+                const uint32_t h = hb[j];
+                if (mid[j] == myid || ((msig[h >> 5] >> (h & 31u)) & 1u)) continue;
+                u64 cnd = ((u64)__float_as_uint(D[m * LDD + j]) << 32) | (uint32_t)j;
+                best = cnd < best ? cnd : best;
+            }
+        } else {
+            for (int i = sub; i < nNew; i += LPM) {
+                const uint32_t h = hb[i];
+                if (mid[i] == myid || ((msig[h >> 5] >> (h & 31u)) & 1u)) continue;
+                u64 cnd = ((u64)__float_as_uint(D[i * LDD + m]) << 32) | (uint32_t)i;
+                best = cnd < best ? cnd : best;
             }
         }
-        u64 o = __shfl_xor(best, 1); best = o < best ? o : best;
-        o = __shfl_xor(best, 2);     best = o < best ? o : best;
-        if (sub == 0 && m < nTot && best != EMPTY_KEY) {
+        if (best != EMPTY_KEY) {
             const float l = __uint_as_float((uint32_t)(best >> 32));
             if (l < thr[m]) {
                 const int pid = mid[(int)(uint32_t)best];
@@ -504,7 +569,7 @@ k_finalize(const float* __restrict__ pts, int64_t n, int d, int K, int k,
 struct BuildPlan {
     int K, C, s, S16, max_iters;
     float rho, delta;
-    uint64_t off_G, off_cand, off_new, off_old, off_cnt, off_worst, off_ctr, total;
+    uint64_t off_G, off_cand, off_new, off_old, off_cnt, off_worst, off_sig, off_ctr, total;
 };
 
 static bool make_plan(int64_t n, int32_t d, int32_t k, const knng_params_t* p, BuildPlan* bp)
@@ -532,15 +597,16 @@ static bool make_plan(int64_t n, int32_t d, int32_t k, const knng_params_t* p, B
     bp->off_old = take((uint64_t)n * 2 * s * 4);
     bp->off_cnt = take((uint64_t)n * 16);
     bp->off_worst = take((uint64_t)n * 4);
+    bp->off_sig = take((uint64_t)n * SIG_WORDS * 4);
     bp->off_ctr = take(256);
     bp->total = off;
     return true;
 }
 
 template <int METRIC, int S16>
-static hipError_t launch_join(hipStream_t st, bool vec, const float* pts, int64_t n, int d,
+static hipError_t launch_join(hipStream_t st, bool vec, uint32_t iter, const float* pts, int64_t n, int d,
                               const BuildPlan& bp, const int32_t* newl, const int32_t* oldl,
-                              int32_t* cnt, const float* worst, u64* cand)
+                              int32_t* cnt, const float* worst, const uint32_t* sig, u64* cand)
 {
     const int lds = JoinCfg<S16>::LDS_BYTES;
     auto kv = k_join<METRIC, S16, true>;
@@ -550,23 +616,23 @@ static hipError_t launch_join(hipStream_t st, bool vec, const float* pts, int64_
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
     }
-    if (vec) hipLaunchKernelGGL(kv, dim3((unsigned)n), dim3(256), lds, st, pts, n, d, bp.K, bp.C, bp.s,
-                                newl, oldl, cnt, worst, cand);
-    else hipLaunchKernelGGL(ks, dim3((unsigned)n), dim3(256), lds, st, pts, n, d, bp.K, bp.C, bp.s,
-                            newl, oldl, cnt, worst, cand);
+    if (vec) hipLaunchKernelGGL(kv, dim3((unsigned)n), dim3(256), lds, st, pts, n, d, bp.K, bp.C, bp.s, iter,
+                                newl, oldl, cnt, worst, sig, cand);
+    else hipLaunchKernelGGL(ks, dim3((unsigned)n), dim3(256), lds, st, pts, n, d, bp.K, bp.C, bp.s, iter,
+                            newl, oldl, cnt, worst, sig, cand);
     return hipGetLastError();
 }
 
 template <int METRIC>
-static hipError_t launch_join_m(hipStream_t st, bool vec, const float* pts, int64_t n, int d,
+static hipError_t launch_join_m(hipStream_t st, bool vec, uint32_t iter, const float* pts, int64_t n, int d,
                                 const BuildPlan& bp, const int32_t* newl, const int32_t* oldl,
-                                int32_t* cnt, const float* worst, u64* cand)
+                                int32_t* cnt, const float* worst, const uint32_t* sig, u64* cand)
 {
     switch (bp.S16) {
-    case 1: return launch_join<METRIC, 1>(st, vec, pts, n, d, bp, newl, oldl, cnt, worst, cand);
-    case 2: return launch_join<METRIC, 2>(st, vec, pts, n, d, bp, newl, oldl, cnt, worst, cand);
-    case 4: return launch_join<METRIC, 4>(st, vec, pts, n, d, bp, newl, oldl, cnt, worst, cand);
-    default: return launch_join<METRIC, 8>(st, vec, pts, n, d, bp, newl, oldl, cnt, worst, cand);
+    case 1: return launch_join<METRIC, 1>(st, vec, iter, pts, n, d, bp, newl, oldl, cnt, worst, sig, cand);
+    case 2: return launch_join<METRIC, 2>(st, vec, iter, pts, n, d, bp, newl, oldl, cnt, worst, sig, cand);
+    case 4: return launch_join<METRIC, 4>(st, vec, iter, pts, n, d, bp, newl, oldl, cnt, worst, sig, cand);
+    default: return launch_join<METRIC, 8>(st, vec, iter, pts, n, d, bp, newl, oldl, cnt, worst, sig, cand);
     }
 }
 
@@ -608,6 +674,7 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
     int32_t* oldl = reinterpret_cast<int32_t*>(ws + bp.off_old);
     int32_t* cnt = reinterpret_cast<int32_t*>(ws + bp.off_cnt);
     float* worst = reinterpret_cast<float*>(ws + bp.off_worst);
+    uint32_t* sig = reinterpret_cast<uint32_t*>(ws + bp.off_sig);
     u64* ctr = reinterpret_cast<u64*>(ws + bp.off_ctr);      // [0] updates, [1] rows gathered
     knng_stats_t* stats = params->stats_host;
     const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(points_dev) & 15u) == 0);
@@ -644,7 +711,7 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
     for (int it = 0; it < bp.max_iters; ++it) {
         const bool rec = stats && it < max_rec;
         hipLaunchKernelGGL(k_sample, dim3(row_blocks), dim3(256), 0, st, n, bp.K, bp.s, params->seed,
-                           (uint32_t)it, G, newl, oldl, cnt);
+                           (uint32_t)it, G, newl, oldl, cnt, sig);
         HIPCHK(hipGetLastError());
         if (rec) {
             HIPCHK(hipEventRecord(ev[2 + 4 * it], st));
@@ -652,8 +719,8 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
             HIPCHK(hipGetLastError());
             HIPCHK(hipEventRecord(ev[3 + 4 * it], st));
         }
-        if (metric == 0) HIPCHK(launch_join_m<0>(st, vec, points_dev, n, d, bp, newl, oldl, cnt, worst, cand));
-        else HIPCHK(launch_join_m<1>(st, vec, points_dev, n, d, bp, newl, oldl, cnt, worst, cand));
+        if (metric == 0) HIPCHK(launch_join_m<0>(st, vec, (uint32_t)it, points_dev, n, d, bp, newl, oldl, cnt, worst, sig, cand));
+        else HIPCHK(launch_join_m<1>(st, vec, (uint32_t)it, points_dev, n, d, bp, newl, oldl, cnt, worst, sig, cand));
         if (rec) HIPCHK(hipEventRecord(ev[4 + 4 * it], st));
         hipLaunchKernelGGL(k_merge, dim3(merge_blocks), dim3(256), 0, st, n, bp.K, bp.C, G, cand, worst, ctr);
         HIPCHK(hipGetLastError());
