@@ -255,13 +255,26 @@ constexpr int OFFERS_PER_MEMBER = KNNG_OFFERS_PER_MEMBER;
 template <int S16> struct JoinCfg {
     static constexpr int MROWS = 16 * S16;            // max |NEW|
     static constexpr int NCOLS = 32 * S16;            // max |NEW| + |OLD|
-    static constexpr int DS = S16 <= 2 ? 128 : (S16 == 4 ? 64 : 32);
+    // short slabs keep the LDS footprint near 20 KB so seven workgroups fit a CU: the join is
+    // latency-bound and measured 1.6x faster at 64 than at 128 floats per slab (d = 128)
+    static constexpr int DS = S16 <= 2 ? 64 : (S16 == 4 ? 64 : 32);
     static constexpr int LD = DS + 4;                 // row stride of the vector slab (floats)
     static constexpr int LDD = NCOLS + 1;             // row stride of the distance block
-    static constexpr int NI = (S16 * S16 + 3) / 4;    // work items (16x32 outputs) per wavefront
+    static constexpr int NT = (2 * S16 * S16 + 3) / 4; // 16x16 output tiles per wavefront (upper bound)
+    static constexpr int NL = NCOLS * (DS / 4) / 256; // 16-byte pieces a thread gathers per slab
     static constexpr int XBYTES = NCOLS * LD * 4 > MROWS * LDD * 4 ? NCOLS * LD * 4 : MROWS * LDD * 4;
-    static constexpr int LDS_BYTES = XBYTES + DS * 4 + NCOLS * (16 + 4 * SIG_WORDS);
+    static constexpr int LDS_BYTES = XBYTES + NCOLS * (16 + 4 * SIG_WORDS);
 };
+
+template <bool VEC>
+__device__ __forceinline__ float4 load_piece(const float* __restrict__ row, int t, int d)
+{
+    if (VEC && t + 3 < d) return *reinterpret_cast<const float4*>(row + t);
+    float4 x;
+    x.x = t < d ? row[t] : 0.0f;         x.y = t + 1 < d ? row[t + 1] : 0.0f;
+    x.z = t + 2 < d ? row[t + 2] : 0.0f; x.w = t + 3 < d ? row[t + 3] : 0.0f;
+    return x;
+}
 
 template <int METRIC, int S16, bool VEC>
 __global__ void __launch_bounds__(256)
@@ -270,11 +283,10 @@ k_join(const float* __restrict__ pts, int64_t n, int d, int K, int C, int s, uin
        const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand)
 {
     using Cfg = JoinCfg<S16>;
-    constexpr int DS = Cfg::DS, LD = Cfg::LD, LDD = Cfg::LDD, NI = Cfg::NI;
+    constexpr int DS = Cfg::DS, LD = Cfg::LD, LDD = Cfg::LDD, NT = Cfg::NT, NL = Cfg::NL;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float* X = reinterpret_cast<float*>(smem);                 // [NCOLS][LD], later D [MROWS][LDD]
-    float* pivot = reinterpret_cast<float*>(smem + Cfg::XBYTES);  // [DS]
-    int* mid = reinterpret_cast<int*>(pivot + DS);             // [NCOLS] member ids
+    int* mid = reinterpret_cast<int*>(smem + Cfg::XBYTES);     // [NCOLS] member ids
     float* nrm = reinterpret_cast<float*>(mid + Cfg::NCOLS);   // [NCOLS] |x_m - x_v|^2
     float* thr = nrm + Cfg::NCOLS;                             // [NCOLS] farthest-neighbour distance
     uint32_t* hb = reinterpret_cast<uint32_t*>(thr + Cfg::NCOLS);  // [NCOLS] signature bit of the id
@@ -293,28 +305,44 @@ k_join(const float* __restrict__ pts, int64_t n, int d, int K, int C, int s, uin
     }
     if (nNew == 0) return;                    // nothing new around v: no pair to evaluate
 
-    // member ids, thresholds, zeroed norms
+    // member ids (one member per thread: NCOLS <= 256)
     const int64_t lbase = v * 2 * (int64_t)s;
-    for (int m = tid; m < nTot; m += 256) {
-        int id;
-        if (m < nNew) id = newl[lbase + (m < nfn ? m : s + (m - nfn))];
-        else { int o = m - nNew; id = oldl[lbase + (o < nfo ? o : s + (o - nfo))]; }
-        mid[m] = id;
-        thr[m] = worst[id];
+    int my_member = -1;
+    if (tid < nTot) {
+        const int m = tid;
+        if (m < nNew) my_member = newl[lbase + (m < nfn ? m : s + (m - nfn))];
+        else { int o = m - nNew; my_member = oldl[lbase + (o < nfo ? o : s + (o - nfo))]; }
+        mid[m] = my_member;
         nrm[m] = 0.0f;
-        hb[m] = sig_bit(id, iter);
     }
-    for (int i = tid; i < nTot * (SIG_WORDS / 4); i += 256) {      // 2 x 16 bytes per member
-        const int m = i / (SIG_WORDS / 4), q = i % (SIG_WORDS / 4);
-        int id;
-        if (m < nNew) id = newl[lbase + (m < nfn ? m : s + (m - nfn))];
-        else { int o = m - nNew; id = oldl[lbase + (o < nfo ? o : s + (o - nfo))]; }
-        reinterpret_cast<uint4*>(sg)[i] = reinterpret_cast<const uint4*>(sig + (int64_t)id * SIG_WORDS)[q];
+    __syncthreads();
+    // thresholds and signatures of the members: issued now, parked in registers while the
+    // vector gather below is in flight
+    float thr_r = 0.0f;
+    uint4 sg_r0 = uint4{0, 0, 0, 0}, sg_r1 = uint4{0, 0, 0, 0};
+    if (tid < nTot) {
+        thr_r = worst[my_member];
+        const uint4* sp = reinterpret_cast<const uint4*>(sig + (int64_t)my_member * SIG_WORDS);
+        sg_r0 = sp[0];
+        sg_r1 = sp[1];
     }
 
-    floatx4 acc[NI][2];
+    // Output tiles (16x16): rows = NEW members, columns = NEW|OLD members.  Tiles strictly below
+    // the diagonal of the NEW x NEW part are skipped (the block is symmetric there); the kept
+    // tiles are dealt round-robin to the four wavefronts so every SIMD gets matrix work.
+    const int nrt = (nNew + 15) >> 4, nct = (nTot + 15) >> 4;
+    const int ntiles = nrt * nct - nrt * (nrt - 1) / 2;
+    floatx4 acc[NT];
+    int trow[NT], tcol[NT];
 #pragma unroll
-    for (int q = 0; q < NI; ++q) { acc[q][0] = floatx4{0, 0, 0, 0}; acc[q][1] = floatx4{0, 0, 0, 0}; }
+    for (int q = 0; q < NT; ++q) {
+        acc[q] = floatx4{0, 0, 0, 0};
+        int rem = w + 4 * q, rt = 0;
+        if (rem < ntiles) {
+            while (rem >= nct - rt) { rem -= nct - rt; ++rt; }
+            trow[q] = rt; tcol[q] = rt + rem;
+        } else { trow[q] = -1; tcol[q] = 0; }
+    }
 
     const int r16 = lane & 15, kq = lane >> 4;
     const float* xv = pts + v * (int64_t)d;
@@ -322,56 +350,57 @@ k_join(const float* __restrict__ pts, int64_t n, int d, int K, int C, int s, uin
     for (int k0 = 0; k0 < d; k0 += DS) {
         const int len = (d - k0) < DS ? (d - k0) : DS;     // valid floats in this slab
         const int len16 = (len + 15) & ~15;                // padded with zeros for the MFMA k-loop
-        const int q4 = len16 >> 2;
-        __syncthreads();                                   // previous slab fully consumed; ids visible
-        for (int c4 = tid; c4 < q4; c4 += 256) {
-            int t = k0 + 4 * c4;
-            float4 p;
-            if (VEC && t + 3 < d) p = *reinterpret_cast<const float4*>(xv + t);
-            else {
-                p.x = t < d ? xv[t] : 0.0f;         p.y = t + 1 < d ? xv[t + 1] : 0.0f;
-                p.z = t + 2 < d ? xv[t + 2] : 0.0f; p.w = t + 3 < d ? xv[t + 3] : 0.0f;
-            }
-            *reinterpret_cast<float4*>(pivot + 4 * c4) = p;
-        }
-        __syncthreads();
-        const int total = nTot * q4;
-        for (int idx = tid; idx < total; idx += 256) {
-            const int row = idx / q4, c4 = idx - row * q4;
-            const int t = k0 + 4 * c4;
-            const float* xr = pts + (int64_t)mid[row] * d;
-            float4 x;
-            if (VEC && t + 3 < d) x = *reinterpret_cast<const float4*>(xr + t);
-            else {
-                x.x = t < d ? xr[t] : 0.0f;         x.y = t + 1 < d ? xr[t + 1] : 0.0f;
-                x.z = t + 2 < d ? xr[t + 2] : 0.0f; x.w = t + 3 < d ? xr[t + 3] : 0.0f;
-            }
-            const float4 p = *reinterpret_cast<const float4*>(pivot + 4 * c4);
-            x.x -= p.x; x.y -= p.y; x.z -= p.z; x.w -= p.w;
-            *reinterpret_cast<float4*>(X + row * LD + 4 * c4) = x;
-            atomicAdd(&nrm[row], x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w);
-        }
-        __syncthreads();
-        // Gram block: item q of wavefront w covers row tile rt, column tiles 2cp and 2cp+1
+        const int q4 = len16 >> 2;                         // 16-byte pieces per row
+        // thread -> (piece c4 of the row, row rsub + i*RP): QP = pieces rounded up to a power of
+        // two, so a row's pieces sit in QP adjacent lanes and c4 is the same in every pass
+        int qshift = 2;
+        while ((1 << qshift) < q4) ++qshift;
+        const int QP = 1 << qshift, RP = 256 >> qshift;
+        const int c4 = tid & (QP - 1), rsub = tid >> qshift;
+        const int t = k0 + 4 * c4;
+        const bool col_ok = c4 < q4;
+        float4 buf[NL];
+        float4 pv = float4{0, 0, 0, 0};
+        if (col_ok) pv = load_piece<VEC>(xv, t, d);
 #pragma unroll
-        for (int q = 0; q < NI; ++q) {
-            const int item = w * NI + q;
-            const int rt = item / S16, cp = item % S16;
-            if (item < S16 * S16 && rt * 16 < nNew && cp * 32 < nTot) {
-                const float* xa = X + (rt * 16 + r16) * LD + 4 * kq;
-                const float* xb = X + (cp * 32 + r16) * LD + 4 * kq;
+        for (int i = 0; i < NL; ++i) {
+            const int row = rsub + i * RP;
+            buf[i] = float4{0, 0, 0, 0};
+            if (col_ok && row < nTot) buf[i] = load_piece<VEC>(pts + (int64_t)mid[row] * d, t, d);
+        }
+        if (k0 == 0 && tid < nTot) {
+            thr[tid] = thr_r;
+            hb[tid] = sig_bit(my_member, iter);
+            reinterpret_cast<uint4*>(sg)[2 * tid] = sg_r0;
+            reinterpret_cast<uint4*>(sg)[2 * tid + 1] = sg_r1;
+        }
+        if (k0 > 0) __syncthreads();                       // previous slab fully consumed
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int row = rsub + i * RP;
+            float4 x = buf[i];
+            x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w;
+            float ss = x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+            for (int o = QP >> 1; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+            if (row < nTot) {
+                if (col_ok) *reinterpret_cast<float4*>(X + row * LD + 4 * c4) = x;
+                if (c4 == 0) nrm[row] += ss;
+            }
+        }
+        __syncthreads();
+        // Gram tiles of this slab
+#pragma unroll
+        for (int q = 0; q < NT; ++q) {
+            if (trow[q] >= 0) {
+                const float* xa = X + (trow[q] * 16 + r16) * LD + 4 * kq;
+                const float* xb = X + (tcol[q] * 16 + r16) * LD + 4 * kq;
                 for (int kk = 0; kk < len16; kk += 16) {
                     const float4 a = *reinterpret_cast<const float4*>(xa + kk);
-                    const float4 b0 = *reinterpret_cast<const float4*>(xb + kk);
-                    const float4 b1 = *reinterpret_cast<const float4*>(xb + 16 * LD + kk);
-                    acc[q][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b0.x, acc[q][0], 0, 0, 0);
-                    acc[q][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b1.x, acc[q][1], 0, 0, 0);
-                    acc[q][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b0.y, acc[q][0], 0, 0, 0);
-                    acc[q][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b1.y, acc[q][1], 0, 0, 0);
-                    acc[q][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b0.z, acc[q][0], 0, 0, 0);
-                    acc[q][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b1.z, acc[q][1], 0, 0, 0);
-                    acc[q][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b0.w, acc[q][0], 0, 0, 0);
-                    acc[q][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b1.w, acc[q][1], 0, 0, 0);
+                    const float4 b = *reinterpret_cast<const float4*>(xb + kk);
+                    acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc[q], 0, 0, 0);
+                    acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc[q], 0, 0, 0);
+                    acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc[q], 0, 0, 0);
+                    acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc[q], 0, 0, 0);
                 }
             }
         }
@@ -396,21 +425,16 @@ k_join(const float* __restrict__ pts, int64_t n, int d, int K, int C, int s, uin
     // distance block D[row][col] over the slab storage
     float* D = X;
 #pragma unroll
-    for (int q = 0; q < NI; ++q) {
-        const int item = w * NI + q;
-        const int rt = item / S16, cp = item % S16;
-        if (item < S16 * S16 && rt * 16 < nNew && cp * 32 < nTot) {
+    for (int q = 0; q < NT; ++q) {
+        if (trow[q] >= 0) {
+            const int col = tcol[q] * 16 + r16;
+            const float nc = nrm[col < nTot ? col : 0];
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int col = cp * 32 + h * 16 + r16;
-                const float nc = nrm[col < nTot ? col : 0];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = rt * 16 + 4 * kq + r;
-                    float l = nrm[row < nTot ? row : 0] + nc - 2.0f * acc[q][h][r];
-                    if (METRIC == 1) l *= 0.5f;            // unit rows: 1 - <a,b> = |a-b|^2 / 2
-                    D[row * LDD + col] = nonneg(l);
-                }
+            for (int r = 0; r < 4; ++r) {
+                const int row = trow[q] * 16 + 4 * kq + r;
+                float l = nrm[row < nTot ? row : 0] + nc - 2.0f * acc[q][r];
+                if (METRIC == 1) l *= 0.5f;                // unit rows: 1 - <a,b> = |a-b|^2 / 2
+                D[row * LDD + col] = nonneg(l);
             }
         }
     }
@@ -423,25 +447,30 @@ k_join(const float* __restrict__ pts, int64_t n, int d, int K, int C, int s, uin
         if (m >= nTot) continue;
         const int myid = mid[m];
         const uint32_t* msig = sg + m * SIG_WORDS;
+        const float mythr = thr[m];
         u64 best = EMPTY_KEY;
         if (m < nNew) {
             for (int j = sub; j < nTot; j += LPM) {
+                const float l = ((j >> 4) < (m >> 4)) ? D[j * LDD + m] : D[m * LDD + j];
+                if (!(l < mythr)) continue;
                 const uint32_t h = hb[j];
                 if (mid[j] == myid || ((msig[h >> 5] >> (h & 31u)) & 1u)) continue;
-                u64 cnd = ((u64)__float_as_uint(D[m * LDD + j]) << 32) | (uint32_t)j;
+                u64 cnd = ((u64)__float_as_uint(l) << 32) | (uint32_t)j;
                 best = cnd < best ? cnd : best;
             }
         } else {
             for (int i = sub; i < nNew; i += LPM) {
+                const float l = D[i * LDD + m];
+                if (!(l < mythr)) continue;
                 const uint32_t h = hb[i];
                 if (mid[i] == myid || ((msig[h >> 5] >> (h & 31u)) & 1u)) continue;
-                u64 cnd = ((u64)__float_as_uint(D[i * LDD + m]) << 32) | (uint32_t)i;
+                u64 cnd = ((u64)__float_as_uint(l) << 32) | (uint32_t)i;
                 best = cnd < best ? cnd : best;
             }
         }
         if (best != EMPTY_KEY) {
             const float l = __uint_as_float((uint32_t)(best >> 32));
-            if (l < thr[m]) {
+            {
                 const int pid = mid[(int)(uint32_t)best];
                 const uint32_t slot = below(hash32((uint32_t)pid), (uint32_t)C);
                 atomicMin(&cand[(int64_t)myid * C + slot], pack_key(l, pid, 1));
