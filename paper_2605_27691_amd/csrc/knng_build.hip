@@ -214,268 +214,410 @@ k_sample(int64_t n, int K, int s, u64 seed, uint32_t iter, u64* __restrict__ G,
     }
 }
 
-// Number of vectors the next join launch gathers (statistics only).
+// ------------------------------------------------------------------------------------------
+// k_plan: after sampling, fix each point's four list lengths for the join (reverse counts
+// clamped to s), hand the atomic reverse counters back at zero, append the points that have
+// anything new around them to the active list, and count the vectors the join will gather.
+// ctr[1] += vectors, ctr[2] += active points.
+// ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_count_rows(int64_t n, int s, const int32_t* __restrict__ cnt, u64* __restrict__ out)
+k_plan(int64_t n, int s, int32_t* __restrict__ cnt, int4* __restrict__ plan,
+       int32_t* __restrict__ active, u64* __restrict__ ctr)
 {
     __shared__ u64 part[4];
-    u64 acc = 0;
-    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += (int64_t)gridDim.x * blockDim.x) {
-        int4 c = reinterpret_cast<const int4*>(cnt)[v];
-        int nn = c.x + (c.z < s ? c.z : s);
-        if (nn > 0) acc += (u64)(nn + c.y + (c.w < s ? c.w : s));
+    const int lane = lane_id();
+    u64 rows = 0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t nround = (n + stride - 1) / stride * stride;      // whole wavefronts stay in the loop
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nround; v += stride) {
+        bool act = false;
+        if (v < n) {
+            int4 c = reinterpret_cast<const int4*>(cnt)[v];
+            c.z = c.z < s ? c.z : s;
+            c.w = c.w < s ? c.w : s;
+            plan[v] = c;
+            if (c.z | c.w) reinterpret_cast<int2*>(cnt)[2 * v + 1] = int2{0, 0};
+            act = (c.x + c.z) > 0;
+            if (act) rows += (u64)(c.x + c.y + c.z + c.w);
+        }
+        const u64 m = __ballot(act);
+        if (m) {
+            unsigned long long base = 0;
+            if (lane == 0) base = atomicAdd(ctr + 2, (u64)__popcll(m));
+            base = bcast64(base, 0);
+            if (act) active[base + __popcll(m & lanemask_lt())] = (int32_t)v;
+        }
     }
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-    if (lane_id() == 0) part[threadIdx.x >> 6] = acc;
+    for (int o = 32; o > 0; o >>= 1) rows += __shfl_xor(rows, o);
+    if (lane == 0) part[threadIdx.x >> 6] = rows;
     __syncthreads();
-    if (threadIdx.x == 0) atomicAdd(out, part[0] + part[1] + part[2] + part[3]);
+    if (threadIdx.x == 0) atomicAdd(ctr + 1, part[0] + part[1] + part[2] + part[3]);
 }
 
 // ------------------------------------------------------------------------------------------
-// k_join: the local join, one 256-thread workgroup per point v.
+// k_join: the local join.  Persistent 256-thread workgroups walk the active points; the work
+// of a point is split into slabs of DS coordinates, and the loop is software-pipelined over
+// (point, slab) units: while the matrix cores and the selection work on the unit in LDS, the
+// global loads of the next unit (and the list record of the point after) are already in
+// flight into registers.  Barriers wait on LDS traffic only, never on outstanding global loads.
 //
-// Members: m in [0,nNew) = NEW[v], m in [nNew,nTot) = OLD[v].  Their vectors are gathered
-// from HBM with 16-byte coalesced loads, the pivot x_v is subtracted (keeps the Gram form
-// |a|^2+|b|^2-2ab away from cancellation: all members are near v), and the centred slab is
-// staged in LDS.  Four wavefronts then compute the NEW x (NEW|OLD) Gram block with
-// v_mfma_f32_16x16x4_f32, 16x32 outputs per work item, accumulating over slabs of d.
-// The distance block goes to LDS (over the vector slab), each member takes its closest
-// partner, and if that beats the member's current farthest neighbour the pair is offered to
-// the member's candidate list: one 64-bit atomic min on slot hash(partner) % C.
+// Members of point v: m in [0,nNew) = NEW[v] (forward then reverse sample), m in [nNew,nTot)
+// = OLD[v].  Their vectors are gathered with 16-byte loads (a row's pieces in adjacent lanes),
+// the pivot x_v is subtracted (keeps |a|^2+|b|^2-2ab away from cancellation: members are near
+// v) and the centred slab is stored in LDS.  The four wavefronts compute the NEW x (NEW|OLD)
+// Gram block with v_mfma_f32_16x16x4_f32, accumulating over slabs.  The distance block then
+// replaces the slab in LDS; every member takes, per residue class of partner index, its
+// closest partner that beats the member's farthest neighbour and is not in the member's
+// signature, and offers it with one 64-bit atomic min on cand[member][hash(partner) % C].
 //
 // S16 = number of 16-row tiles of NEW (2s <= 16*S16); DS = slab length in floats.
 // ------------------------------------------------------------------------------------------
-// Each member's partners are split into 4 residue classes (partner index mod 4), one per
-// lane; the closest partner of each class is offered (1, 2 or 4 offers per member and join).
+// Each member's partners are split into residue classes (partner index mod LPM), one per lane.
 #ifndef KNNG_OFFERS_PER_MEMBER
 #define KNNG_OFFERS_PER_MEMBER 4
 #endif
+#ifndef KNNG_JOIN_WAVES
+#define KNNG_JOIN_WAVES
+#endif
+#ifndef KNNG_JOIN_DS
+#define KNNG_JOIN_DS 64       // slab length for s <= 16 (the paper's default parameters)
+#endif
 constexpr int OFFERS_PER_MEMBER = KNNG_OFFERS_PER_MEMBER;
 
-template <int S16> struct JoinCfg {
+template <int S16, int DS_> struct JoinCfg {
     static constexpr int MROWS = 16 * S16;            // max |NEW|
     static constexpr int NCOLS = 32 * S16;            // max |NEW| + |OLD|
-    // short slabs keep the LDS footprint near 20 KB so seven workgroups fit a CU: the join is
-    // latency-bound and measured 1.6x faster at 64 than at 128 floats per slab (d = 128)
-    static constexpr int DS = S16 <= 2 ? 64 : (S16 == 4 ? 64 : 32);
+    static constexpr int DS = DS_;
     static constexpr int LD = DS + 4;                 // row stride of the vector slab (floats)
     static constexpr int LDD = NCOLS + 1;             // row stride of the distance block
-    static constexpr int NT = (2 * S16 * S16 + 3) / 4; // 16x16 output tiles per wavefront (upper bound)
+    static constexpr int NT = (3 * S16 * S16 + 3 * S16 + 7) / 8; // 16x16 tiles per wavefront (upper bound)
     static constexpr int NL = NCOLS * (DS / 4) / 256; // 16-byte pieces a thread gathers per slab
     static constexpr int XBYTES = NCOLS * LD * 4 > MROWS * LDD * 4 ? NCOLS * LD * 4 : MROWS * LDD * 4;
-    static constexpr int LDS_BYTES = XBYTES + NCOLS * (16 + 4 * SIG_WORDS);
+    static constexpr int LDS_BYTES = XBYTES + NCOLS * (8 + 8 + 8 + 4 * SIG_WORDS) + 16 + 4 * SIG_WORDS;
 };
 
+// 16-byte piece [t, t+4) of a row, zero beyond d.  VEC: d % 4 == 0 and rows 16-byte aligned, so
+// a piece is either whole or empty and one vector load serves.
 template <bool VEC>
 __device__ __forceinline__ float4 load_piece(const float* __restrict__ row, int t, int d)
 {
-    if (VEC && t + 3 < d) return *reinterpret_cast<const float4*>(row + t);
-    float4 x;
-    x.x = t < d ? row[t] : 0.0f;         x.y = t + 1 < d ? row[t + 1] : 0.0f;
-    x.z = t + 2 < d ? row[t + 2] : 0.0f; x.w = t + 3 < d ? row[t + 3] : 0.0f;
+    float4 x = float4{0.0f, 0.0f, 0.0f, 0.0f};
+    if (VEC) {
+        if (t < d) x = *reinterpret_cast<const float4*>(row + t);
+    } else {
+        if (t < d) x.x = row[t];
+        if (t + 1 < d) x.y = row[t + 1];
+        if (t + 2 < d) x.z = row[t + 2];
+        if (t + 3 < d) x.w = row[t + 3];
+    }
     return x;
 }
 
-template <int METRIC, int S16, bool VEC>
-__global__ void __launch_bounds__(256)
-k_join(const float* __restrict__ pts, int64_t n, int d, int K, int C, int s, uint32_t iter,
-       const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl, int32_t* __restrict__ cnt,
+// Workgroup barrier that orders LDS accesses only: outstanding global loads stay in flight.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// thread -> (piece c4 of a row, rows rsub + i*RP) for a slab with q4 pieces per row: pieces are
+// rounded up to a power of two QP so a row's pieces sit in QP adjacent lanes
+struct SlabMap {
+    int len16, q4, qshift, c4, rsub, RP;
+    bool col_ok;
+};
+__device__ __forceinline__ SlabMap slab_map(int d, int k0, int DS, int tid)
+{
+    SlabMap m;
+    const int len = (d - k0) < DS ? (d - k0) : DS;
+    m.len16 = (len + 15) & ~15;                        // zero-padded for the MFMA k-loop
+    m.q4 = m.len16 >> 2;
+    m.qshift = 2;
+    while ((1 << m.qshift) < m.q4) ++m.qshift;
+    m.RP = 256 >> m.qshift;
+    m.c4 = tid & ((1 << m.qshift) - 1);
+    m.rsub = tid >> m.qshift;
+    m.col_ok = m.c4 < m.q4;
+    return m;
+}
+
+struct PointPlan { int nfn, nfo, nNew, nTot; };
+__device__ __forceinline__ PointPlan make_point(int4 c)
+{
+    PointPlan p;
+    p.nfn = __builtin_amdgcn_readfirstlane(c.x);
+    p.nfo = __builtin_amdgcn_readfirstlane(c.y);
+    p.nNew = p.nfn + __builtin_amdgcn_readfirstlane(c.z);
+    p.nTot = p.nNew + p.nfo + __builtin_amdgcn_readfirstlane(c.w);
+    return p;
+}
+// member index of list slot t (t in [0,2s): NEW list, [2s,4s): OLD list), or -1
+__device__ __forceinline__ int member_of_slot(int t, int s, int4 c)
+{
+    const int nNew = c.x + c.z;
+    if (t < s) return t < c.x ? t : -1;
+    if (t < 2 * s) return (t - s) < c.z ? c.x + (t - s) : -1;
+    if (t < 3 * s) return (t - 2 * s) < c.y ? nNew + (t - 2 * s) : -1;
+    if (t < 4 * s) return (t - 3 * s) < c.w ? nNew + c.y + (t - 3 * s) : -1;
+    return -1;
+}
+
+template <int METRIC, int S16, int DS_, bool VEC>
+__global__ void __launch_bounds__(256) KNNG_JOIN_WAVES
+k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
+       const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl, const int4* __restrict__ plan,
+       const int32_t* __restrict__ active, const u64* __restrict__ nactive_ptr,
        const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand)
 {
-    using Cfg = JoinCfg<S16>;
-    constexpr int DS = Cfg::DS, LD = Cfg::LD, LDD = Cfg::LDD, NT = Cfg::NT, NL = Cfg::NL;
+    using Cfg = JoinCfg<S16, DS_>;
+    constexpr int DS = Cfg::DS, LD = Cfg::LD, LDD = Cfg::LDD, NT = Cfg::NT, NL = Cfg::NL, NCOLS = Cfg::NCOLS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float* X = reinterpret_cast<float*>(smem);                 // [NCOLS][LD], later D [MROWS][LDD]
-    int* mid = reinterpret_cast<int*>(smem + Cfg::XBYTES);     // [NCOLS] member ids
-    float* nrm = reinterpret_cast<float*>(mid + Cfg::NCOLS);   // [NCOLS] |x_m - x_v|^2
-    float* thr = nrm + Cfg::NCOLS;                             // [NCOLS] farthest-neighbour distance
-    uint32_t* hb = reinterpret_cast<uint32_t*>(thr + Cfg::NCOLS);  // [NCOLS] signature bit of the id
-    uint32_t* sg = hb + Cfg::NCOLS;                            // [NCOLS][SIG_WORDS] row signatures
+    int* midbuf = reinterpret_cast<int*>(smem + Cfg::XBYTES);  // [2][NCOLS] member ids, double-buffered
+    int2* mh = reinterpret_cast<int2*>(midbuf + 2 * NCOLS);    // [NCOLS] {member id, its signature bit}
+    float* nrm = reinterpret_cast<float*>(mh + NCOLS);         // [NCOLS] |x_m - x_v|^2
+    float* thr = nrm + NCOLS;                                  // [NCOLS] farthest-neighbour distance
+    uint32_t* sg = reinterpret_cast<uint32_t*>(thr + NCOLS);   // [NCOLS + 1][SIG_WORDS] row signatures
+    float* thr_v = reinterpret_cast<float*>(sg + (NCOLS + 1) * SIG_WORDS);  // [4] the pivot's threshold
 
-    const int64_t v = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);    // wavefront index, kept scalar
+    const int r16 = lane & 15, kq = lane >> 4;
+    const int64_t nact = (int64_t)*nactive_ptr;
+    const int64_t G = gridDim.x;
+    int64_t pos = blockIdx.x;
+    if (pos >= nact) return;
 
-    const int4 c = reinterpret_cast<const int4*>(cnt)[v];
-    const int nfn = c.x, nfo = c.y;
-    const int nrn = c.z < s ? c.z : s, nro = c.w < s ? c.w : s;
-    const int nNew = nfn + nrn, nOld = nfo + nro, nTot = nNew + nOld;
-    if (tid == 0 && (c.z | c.w)) {            // hand the reverse counters back at zero
-        cnt[v * 4 + 2] = 0;
-        cnt[v * 4 + 3] = 0;
+    // list record of a point: its plan (all threads) and the list slot this thread owns
+    auto load_slot = [&](int64_t v) -> int {
+        if (tid < 2 * s) return newl[v * 2 * (int64_t)s + tid];
+        if (tid < 4 * s) return oldl[v * 2 * (int64_t)s + (tid - 2 * s)];
+        return 0;
+    };
+
+    // ---- prologue: first point's ids into LDS, its first slab and member data into registers
+    int64_t v = active[pos];
+    int64_t v_nx = pos + G < nact ? (int64_t)active[pos + G] : -1;       // next point
+    int64_t v_nx2 = pos + 2 * G < nact ? (int64_t)active[pos + 2 * G] : -1;
+    int4 rc = plan[v];
+    int rid = load_slot(v);
+    int cur = 0;
+    {
+        const int m = member_of_slot(tid, s, rc);
+        if (m >= 0) midbuf[m] = rid;
     }
-    if (nNew == 0) return;                    // nothing new around v: no pair to evaluate
+    PointPlan P = make_point(rc);
+    lds_barrier();
 
-    // member ids (one member per thread: NCOLS <= 256)
-    const int64_t lbase = v * 2 * (int64_t)s;
-    int my_member = -1;
-    if (tid < nTot) {
-        const int m = tid;
-        if (m < nNew) my_member = newl[lbase + (m < nfn ? m : s + (m - nfn))];
-        else { int o = m - nNew; my_member = oldl[lbase + (o < nfo ? o : s + (o - nfo))]; }
-        mid[m] = my_member;
-        nrm[m] = 0.0f;
-    }
-    __syncthreads();
-    // thresholds and signatures of the members: issued now, parked in registers while the
-    // vector gather below is in flight
+    float4 buf[NL];
+    float4 pv;
     float thr_r = 0.0f;
     uint4 sg_r0 = uint4{0, 0, 0, 0}, sg_r1 = uint4{0, 0, 0, 0};
-    if (tid < nTot) {
-        thr_r = worst[my_member];
-        const uint4* sp = reinterpret_cast<const uint4*>(sig + (int64_t)my_member * SIG_WORDS);
-        sg_r0 = sp[0];
-        sg_r1 = sp[1];
-    }
-
-    // Output tiles (16x16): rows = NEW members, columns = NEW|OLD members.  Tiles strictly below
-    // the diagonal of the NEW x NEW part are skipped (the block is symmetric there); the kept
-    // tiles are dealt round-robin to the four wavefronts so every SIMD gets matrix work.
-    const int nrt = (nNew + 15) >> 4, nct = (nTot + 15) >> 4;
-    const int ntiles = nrt * nct - nrt * (nrt - 1) / 2;
-    floatx4 acc[NT];
-    int trow[NT], tcol[NT];
-#pragma unroll
-    for (int q = 0; q < NT; ++q) {
-        acc[q] = floatx4{0, 0, 0, 0};
-        int rem = w + 4 * q, rt = 0;
-        if (rem < ntiles) {
-            while (rem >= nct - rt) { rem -= nct - rt; ++rt; }
-            trow[q] = rt; tcol[q] = rt + rem;
-        } else { trow[q] = -1; tcol[q] = 0; }
-    }
-
-    const int r16 = lane & 15, kq = lane >> 4;
-    const float* xv = pts + v * (int64_t)d;
-
-    for (int k0 = 0; k0 < d; k0 += DS) {
-        const int len = (d - k0) < DS ? (d - k0) : DS;     // valid floats in this slab
-        const int len16 = (len + 15) & ~15;                // padded with zeros for the MFMA k-loop
-        const int q4 = len16 >> 2;                         // 16-byte pieces per row
-        // thread -> (piece c4 of the row, row rsub + i*RP): QP = pieces rounded up to a power of
-        // two, so a row's pieces sit in QP adjacent lanes and c4 is the same in every pass
-        int qshift = 2;
-        while ((1 << qshift) < q4) ++qshift;
-        const int QP = 1 << qshift, RP = 256 >> qshift;
-        const int c4 = tid & (QP - 1), rsub = tid >> qshift;
-        const int t = k0 + 4 * c4;
-        const bool col_ok = c4 < q4;
-        float4 buf[NL];
-        float4 pv = float4{0, 0, 0, 0};
-        if (col_ok) pv = load_piece<VEC>(xv, t, d);
+    int my_member = 0;
+    // thread tid < nTot holds member tid; thread tid == nTot holds the pivot itself (when all
+    // 256 slots are members there is no thread left and the pivot takes no offers of its own)
+    auto issue_members = [&](const int* mid, int nTot, int64_t pivot_row) {
+        if (tid <= nTot) {
+            my_member = tid < nTot ? mid[tid] : (int)pivot_row;
+            thr_r = worst[my_member];
+            const uint4* sp = reinterpret_cast<const uint4*>(sig + (int64_t)my_member * SIG_WORDS);
+            sg_r0 = sp[0];
+            sg_r1 = sp[1];
+        }
+    };
+    auto issue_slab = [&](const int* mid, int nTot, int64_t pivot_row, int k0) {
+        const SlabMap sm = slab_map(d, k0, DS, tid);
+        const int t = k0 + 4 * sm.c4;
+        pv = float4{0, 0, 0, 0};
+        if (sm.col_ok && nTot > 0) pv = load_piece<VEC>(pts + pivot_row * d, t, d);
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int row = rsub + i * RP;
+            const int row = sm.rsub + i * sm.RP;
             buf[i] = float4{0, 0, 0, 0};
-            if (col_ok && row < nTot) buf[i] = load_piece<VEC>(pts + (int64_t)mid[row] * d, t, d);
+            if (sm.col_ok && row < nTot) buf[i] = load_piece<VEC>(pts + (int64_t)mid[row] * d, t, d);
         }
-        if (k0 == 0 && tid < nTot) {
-            thr[tid] = thr_r;
-            hb[tid] = sig_bit(my_member, iter);
-            reinterpret_cast<uint4*>(sg)[2 * tid] = sg_r0;
-            reinterpret_cast<uint4*>(sg)[2 * tid + 1] = sg_r1;
-        }
-        if (k0 > 0) __syncthreads();                       // previous slab fully consumed
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int row = rsub + i * RP;
-            float4 x = buf[i];
-            x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w;
-            float ss = x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
-            for (int o = QP >> 1; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-            if (row < nTot) {
-                if (col_ok) *reinterpret_cast<float4*>(X + row * LD + 4 * c4) = x;
-                if (c4 == 0) nrm[row] += ss;
-            }
-        }
-        __syncthreads();
-        // Gram tiles of this slab
+    };
+
+    issue_members(midbuf, P.nTot, v);
+    issue_slab(midbuf, P.nTot, v, 0);
+    int4 rc_n = int4{0, 0, 0, 0};
+    int rid_n = 0;
+    if (v_nx >= 0) { rc_n = plan[v_nx]; rid_n = load_slot(v_nx); }
+
+    for (;;) {
+        const int* mid = midbuf + cur * NCOLS;
+        const int nNew = P.nNew, nTot = P.nTot, nfn = P.nfn, nfo = P.nfo;
+        // Output tiles (16x16): rows = NEW members, columns = NEW|OLD members.  Tiles strictly
+        // below the diagonal of the NEW x NEW part are skipped (the block is symmetric there).
+        // The diagonal tiles of the remaining column tiles are added: the diagonal of the Gram
+        // block is |x_m - x_v|^2, so the matrix cores also deliver every member's norm.
+        // The tiles are dealt round-robin to the four wavefronts.
+        const int nrt = (nNew + 15) >> 4, nct = (nTot + 15) >> 4;
+        const int ntm = nrt * nct - nrt * (nrt - 1) / 2;
+        const int ntiles = ntm + (nct - nrt);
+        floatx4 acc[NT];
+        int trow[NT], tcol[NT];
 #pragma unroll
         for (int q = 0; q < NT; ++q) {
-            if (trow[q] >= 0) {
-                const float* xa = X + (trow[q] * 16 + r16) * LD + 4 * kq;
-                const float* xb = X + (tcol[q] * 16 + r16) * LD + 4 * kq;
-                for (int kk = 0; kk < len16; kk += 16) {
-                    const float4 a = *reinterpret_cast<const float4*>(xa + kk);
-                    const float4 b = *reinterpret_cast<const float4*>(xb + kk);
-                    acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc[q], 0, 0, 0);
-                    acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc[q], 0, 0, 0);
-                    acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc[q], 0, 0, 0);
-                    acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc[q], 0, 0, 0);
+            acc[q] = floatx4{0, 0, 0, 0};
+            int rem = w + 4 * q, rt = 0;
+            if (rem < ntm) {
+                while (rem >= nct - rt) { rem -= nct - rt; ++rt; }
+                trow[q] = rt; tcol[q] = rt + rem;
+            } else if (rem < ntiles) {
+                trow[q] = tcol[q] = nrt + (rem - ntm);
+            } else { trow[q] = -1; tcol[q] = 0; }
+        }
+        PointPlan Pn = make_point(rc_n);
+
+        for (int k0 = 0; k0 < d; k0 += DS) {
+            const bool first = k0 == 0, last = k0 + DS >= d;
+            const SlabMap sm = slab_map(d, k0, DS, tid);
+            // ---- A: registers -> LDS
+            if (first) {
+                if (tid == NCOLS - 1 && nTot == NCOLS) thr_v[0] = 0.0f;     // no thread holds the pivot
+                if (tid == nTot) {
+                    thr_v[0] = thr_r;
+                    reinterpret_cast<uint4*>(sg)[2 * NCOLS] = sg_r0;
+                    reinterpret_cast<uint4*>(sg)[2 * NCOLS + 1] = sg_r1;
+                }
+                if (tid < nTot) {
+                    thr[tid] = thr_r;
+                    mh[tid] = int2{my_member, (int)sig_bit(my_member, iter)};
+                    reinterpret_cast<uint4*>(sg)[2 * tid] = sg_r0;
+                    reinterpret_cast<uint4*>(sg)[2 * tid + 1] = sg_r1;
+                }
+            }
+            if (sm.col_ok) {
+                float* xdst = X + sm.rsub * LD + 4 * sm.c4;
+#pragma unroll
+                for (int i = 0; i < NL; ++i) {
+                    float4 x = buf[i];
+                    x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w;
+                    if (sm.rsub + i * sm.RP < nTot) *reinterpret_cast<float4*>(xdst + i * sm.RP * LD) = x;
+                }
+            }
+            if (last && v_nx >= 0) {                       // next point's member ids
+                const int m = member_of_slot(tid, s, rc_n);
+                if (m >= 0) midbuf[(cur ^ 1) * NCOLS + m] = rid_n;
+            }
+            lds_barrier();
+            // ---- B: issue the loads of the next unit
+            // (one call site, so the prefetch registers are the same on every path)
+            {
+                const bool to_next = last;
+                const int* nmid = to_next ? midbuf + (cur ^ 1) * NCOLS : mid;
+                const int n_tot = to_next ? (v_nx >= 0 ? Pn.nTot : 0) : nTot;
+                const int64_t n_piv = to_next ? (v_nx >= 0 ? v_nx : v) : v;
+                if (to_next && v_nx >= 0) issue_members(nmid, n_tot, n_piv);
+                issue_slab(nmid, n_tot, n_piv, to_next ? 0 : k0 + DS);
+                if (to_next && v_nx2 >= 0) { rc_n = plan[v_nx2]; rid_n = load_slot(v_nx2); }
+            }
+            // ---- C: Gram tiles of this slab
+#pragma unroll
+            for (int q = 0; q < NT; ++q) {
+                if (trow[q] >= 0) {
+                    const float* xa = X + (trow[q] * 16 + r16) * LD + 4 * kq;
+                    const float* xb = X + (tcol[q] * 16 + r16) * LD + 4 * kq;
+                    for (int kk = 0; kk < sm.len16; kk += 16) {
+                        const float4 a = *reinterpret_cast<const float4*>(xa + kk);
+                        const float4 b = *reinterpret_cast<const float4*>(xb + kk);
+                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc[q], 0, 0, 0);
+                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc[q], 0, 0, 0);
+                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc[q], 0, 0, 0);
+                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc[q], 0, 0, 0);
+                    }
+                }
+            }
+            if (last) {
+                // member norms from the diagonal tiles: lane (r16, kq) holds rows 4kq..4kq+3 of
+                // column r16, so the diagonal element sits in lanes with r16 / 4 == kq
+#pragma unroll
+                for (int q = 0; q < NT; ++q) {
+                    if (trow[q] >= 0 && trow[q] == tcol[q] && (r16 >> 2) == kq) {
+                        const int e = r16 & 3;
+                        const float dv = e == 0 ? acc[q][0] : e == 1 ? acc[q][1] : e == 2 ? acc[q][2] : acc[q][3];
+                        nrm[trow[q] * 16 + r16] = dv;
+                    }
+                }
+            }
+            lds_barrier();                                 // slab consumed by every wavefront
+        }
+
+        // The pivot's reverse members hold v in their rows, so |x_m - x_v|^2 is already known:
+        // offer them to v itself (closes v<-m edges into v->m without an extra distance).
+        if (tid < nTot) {
+            const int m = tid;
+            const bool rev = (m >= nfn && m < nNew) || (m >= nNew + nfo);
+            if (rev) {
+                float l = nrm[m];
+                if (METRIC == 1) l *= 0.5f;
+                l = nonneg(l);
+                const int2 me = mh[m];
+                const uint32_t h = (uint32_t)me.y;
+                const uint32_t vw = sg[NCOLS * SIG_WORDS + (h >> 5)];
+                if (l < thr_v[0] && !((vw >> (h & 31u)) & 1u)) {
+                    const uint32_t slot = below(hash32((uint32_t)me.x), (uint32_t)C);
+                    atomicMin(&cand[v * C + slot], pack_key(l, me.x, 1));
                 }
             }
         }
-    }
-    __syncthreads();                                       // all wavefronts done with the slab
-    // The pivot's reverse members hold v in their rows, so |x_m - x_v|^2 is already known here:
-    // offer them to v itself (closes v<-m edges into v->m without an extra distance).
-    for (int m = tid; m < nTot; m += 256) {
-        const bool rev = (m >= nfn && m < nNew) || (m >= nNew + nfo);
-        if (!rev) continue;
-        float l = nrm[m];
-        if (METRIC == 1) l *= 0.5f;
-        l = nonneg(l);
-        const int pid = mid[m];
-        const uint32_t h = hb[m];
-        const uint32_t vw = sig[v * SIG_WORDS + (h >> 5)];
-        if (l < worst[v] && !((vw >> (h & 31u)) & 1u)) {
-            const uint32_t slot = below(hash32((uint32_t)pid), (uint32_t)C);
-            atomicMin(&cand[v * C + slot], pack_key(l, pid, 1));
-        }
-    }
-    // distance block D[row][col] over the slab storage
-    float* D = X;
+        // distance block D[row][col] over the slab storage
+        float* D = X;
 #pragma unroll
-    for (int q = 0; q < NT; ++q) {
-        if (trow[q] >= 0) {
-            const int col = tcol[q] * 16 + r16;
-            const float nc = nrm[col < nTot ? col : 0];
+        for (int q = 0; q < NT; ++q) {
+            if (trow[q] >= 0 && trow[q] < nrt) {           // norm-only diagonal tiles have no D rows
+                const int col = tcol[q] * 16 + r16;
+                const float nc = nrm[col];
+                const float4 nr = *reinterpret_cast<const float4*>(nrm + trow[q] * 16 + 4 * kq);
+                const float nra[4] = {nr.x, nr.y, nr.z, nr.w};
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = trow[q] * 16 + 4 * kq + r;
-                float l = nrm[row < nTot ? row : 0] + nc - 2.0f * acc[q][r];
-                if (METRIC == 1) l *= 0.5f;                // unit rows: 1 - <a,b> = |a-b|^2 / 2
-                D[row * LDD + col] = nonneg(l);
+                for (int r = 0; r < 4; ++r) {
+                    const int row = trow[q] * 16 + 4 * kq + r;
+                    float l = nra[r] + nc - 2.0f * acc[q][r];
+                    if (METRIC == 1) l *= 0.5f;            // unit rows: 1 - <a,b> = |a-b|^2 / 2
+                    D[row * LDD + col] = nonneg(l);
+                }
             }
         }
-    }
-    __syncthreads();
-    // per-member candidates: LPM lanes per member, each lane scans the partners of one residue
-    // class (partner index mod LPM) and offers the closest of its class
-    constexpr int LPM = OFFERS_PER_MEMBER;
-    for (int m0 = 0; m0 < nTot; m0 += 256 / LPM) {
-        const int m = m0 + tid / LPM, sub = tid % LPM;
-        if (m >= nTot) continue;
-        const int myid = mid[m];
-        const uint32_t* msig = sg + m * SIG_WORDS;
-        const float mythr = thr[m];
-        u64 best = EMPTY_KEY;
-        if (m < nNew) {
-            for (int j = sub; j < nTot; j += LPM) {
-                const float l = ((j >> 4) < (m >> 4)) ? D[j * LDD + m] : D[m * LDD + j];
-                if (!(l < mythr)) continue;
-                const uint32_t h = hb[j];
-                if (mid[j] == myid || ((msig[h >> 5] >> (h & 31u)) & 1u)) continue;
-                u64 cnd = ((u64)__float_as_uint(l) << 32) | (uint32_t)j;
-                best = cnd < best ? cnd : best;
+        lds_barrier();
+        // per-member candidates: LPM lanes per member, each lane scans the partners of one
+        // residue class (partner index mod LPM) and offers the closest of its class that beats
+        // the member's threshold and is not in the member's signature (branch-free scan)
+        constexpr int LPM = OFFERS_PER_MEMBER;
+        for (int m0 = 0; m0 < nTot; m0 += 256 / LPM) {
+            const int m = m0 + tid / LPM, sub = tid % LPM;
+            if (m >= nTot) continue;
+            const int myid = mh[m].x;
+            const uint32_t* msig = sg + m * SIG_WORDS;
+            const uint32_t mythr = __float_as_uint(thr[m]);    // non-negative floats order as integers
+            uint32_t best_l = 0xffffffffu, best_j = 0;
+            const bool isnew = m < nNew;
+            const int jend = isnew ? nTot : nNew;
+            for (int j = sub; j < jend; j += LPM) {
+                const bool tr = isnew && ((j >> 4) < (m >> 4));
+                const uint32_t l = __float_as_uint(tr ? D[j * LDD + m] : D[(isnew ? m : j) * LDD + (isnew ? j : m)]);
+                const int2 pj = mh[j];
+                const uint32_t h = (uint32_t)pj.y;
+                const uint32_t known = (msig[h >> 5] >> (h & 31u)) & 1u;
+                const bool ok = (l < mythr) && (l < best_l) && (pj.x != myid) && !known;
+                best_l = ok ? l : best_l;
+                best_j = ok ? (uint32_t)j : best_j;
             }
-        } else {
-            for (int i = sub; i < nNew; i += LPM) {
-                const float l = D[i * LDD + m];
-                if (!(l < mythr)) continue;
-                const uint32_t h = hb[i];
-                if (mid[i] == myid || ((msig[h >> 5] >> (h & 31u)) & 1u)) continue;
-                u64 cnd = ((u64)__float_as_uint(l) << 32) | (uint32_t)i;
-                best = cnd < best ? cnd : best;
-            }
-        }
-        if (best != EMPTY_KEY) {
-            const float l = __uint_as_float((uint32_t)(best >> 32));
-            {
-                const int pid = mid[(int)(uint32_t)best];
+            if (best_l != 0xffffffffu) {
+                const int pid = mh[best_j].x;
                 const uint32_t slot = below(hash32((uint32_t)pid), (uint32_t)C);
-                atomicMin(&cand[(int64_t)myid * C + slot], pack_key(l, pid, 1));
+                atomicMin(&cand[(int64_t)myid * C + slot], pack_key(__uint_as_float(best_l), pid, 1));
             }
         }
+        // ---- advance to the next point of this workgroup
+        if (v_nx < 0) break;
+        lds_barrier();                                     // D and the member arrays are free again
+        pos += G;
+        v = v_nx;
+        v_nx = v_nx2;
+        v_nx2 = pos + 2 * G < nact ? (int64_t)active[pos + 2 * G] : -1;
+        P = Pn;
+        cur ^= 1;
     }
 }
 
@@ -598,7 +740,7 @@ k_finalize(const float* __restrict__ pts, int64_t n, int d, int K, int k,
 struct BuildPlan {
     int K, C, s, S16, max_iters;
     float rho, delta;
-    uint64_t off_G, off_cand, off_new, off_old, off_cnt, off_worst, off_sig, off_ctr, total;
+    uint64_t off_G, off_cand, off_new, off_old, off_cnt, off_plan, off_active, off_worst, off_sig, off_ctr, total;
 };
 
 static bool make_plan(int64_t n, int32_t d, int32_t k, const knng_params_t* p, BuildPlan* bp)
@@ -625,6 +767,8 @@ static bool make_plan(int64_t n, int32_t d, int32_t k, const knng_params_t* p, B
     bp->off_new = take((uint64_t)n * 2 * s * 4);
     bp->off_old = take((uint64_t)n * 2 * s * 4);
     bp->off_cnt = take((uint64_t)n * 16);
+    bp->off_plan = take((uint64_t)n * 16);
+    bp->off_active = take((uint64_t)n * 4);
     bp->off_worst = take((uint64_t)n * 4);
     bp->off_sig = take((uint64_t)n * SIG_WORDS * 4);
     bp->off_ctr = take(256);
@@ -632,37 +776,47 @@ static bool make_plan(int64_t n, int32_t d, int32_t k, const knng_params_t* p, B
     return true;
 }
 
-template <int METRIC, int S16>
-static hipError_t launch_join(hipStream_t st, bool vec, uint32_t iter, const float* pts, int64_t n, int d,
-                              const BuildPlan& bp, const int32_t* newl, const int32_t* oldl,
-                              int32_t* cnt, const float* worst, const uint32_t* sig, u64* cand)
+struct JoinArgs {
+    const float* pts; int d; int C; int s; uint32_t iter;
+    const int32_t* newl; const int32_t* oldl; const int4* plan; const int32_t* active;
+    const u64* nactive; const float* worst; const uint32_t* sig; u64* cand;
+    int num_cu; int64_t n;
+};
+
+template <int METRIC, int S16, int DS, bool VEC>
+static hipError_t launch_join_k(hipStream_t st, const JoinArgs& a)
 {
-    const int lds = JoinCfg<S16>::LDS_BYTES;
-    auto kv = k_join<METRIC, S16, true>;
-    auto ks = k_join<METRIC, S16, false>;
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(vec ? kv : ks),
+    const int lds = JoinCfg<S16, DS>::LDS_BYTES;
+    auto kern = k_join<METRIC, S16, DS, VEC>;
+    static int blocks_per_cu = 0;            // per instantiation: resident workgroups per CU
+    if (blocks_per_cu == 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
+        int occ = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, 256, lds);
+        if (e != hipSuccess) return e;
+        blocks_per_cu = occ > 0 ? occ : 1;
     }
-    if (vec) hipLaunchKernelGGL(kv, dim3((unsigned)n), dim3(256), lds, st, pts, n, d, bp.K, bp.C, bp.s, iter,
-                                newl, oldl, cnt, worst, sig, cand);
-    else hipLaunchKernelGGL(ks, dim3((unsigned)n), dim3(256), lds, st, pts, n, d, bp.K, bp.C, bp.s, iter,
-                            newl, oldl, cnt, worst, sig, cand);
+    int64_t grid = (int64_t)a.num_cu * blocks_per_cu;
+    if (grid > a.n) grid = a.n;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a.pts, a.d, a.C, a.s, a.iter, a.newl,
+                       a.oldl, a.plan, a.active, a.nactive, a.worst, a.sig, a.cand);
     return hipGetLastError();
 }
 
 template <int METRIC>
-static hipError_t launch_join_m(hipStream_t st, bool vec, uint32_t iter, const float* pts, int64_t n, int d,
-                                const BuildPlan& bp, const int32_t* newl, const int32_t* oldl,
-                                int32_t* cnt, const float* worst, const uint32_t* sig, u64* cand)
+static hipError_t launch_join(hipStream_t st, bool vec, int S16, const JoinArgs& a)
 {
-    switch (bp.S16) {
-    case 1: return launch_join<METRIC, 1>(st, vec, iter, pts, n, d, bp, newl, oldl, cnt, worst, sig, cand);
-    case 2: return launch_join<METRIC, 2>(st, vec, iter, pts, n, d, bp, newl, oldl, cnt, worst, sig, cand);
-    case 4: return launch_join<METRIC, 4>(st, vec, iter, pts, n, d, bp, newl, oldl, cnt, worst, sig, cand);
-    default: return launch_join<METRIC, 8>(st, vec, iter, pts, n, d, bp, newl, oldl, cnt, worst, sig, cand);
+#define KNNG_JOIN_CASE(S, DSV)                                                      \
+    return vec ? launch_join_k<METRIC, S, DSV, true>(st, a) : launch_join_k<METRIC, S, DSV, false>(st, a)
+    switch (S16) {
+    case 1: KNNG_JOIN_CASE(1, KNNG_JOIN_DS);
+    case 2: KNNG_JOIN_CASE(2, KNNG_JOIN_DS);
+    case 4: KNNG_JOIN_CASE(4, 64);
+    default: KNNG_JOIN_CASE(8, 32);
     }
+#undef KNNG_JOIN_CASE
 }
 
 }  // namespace knng
@@ -702,6 +856,8 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
     int32_t* newl = reinterpret_cast<int32_t*>(ws + bp.off_new);
     int32_t* oldl = reinterpret_cast<int32_t*>(ws + bp.off_old);
     int32_t* cnt = reinterpret_cast<int32_t*>(ws + bp.off_cnt);
+    int4* plan = reinterpret_cast<int4*>(ws + bp.off_plan);
+    int32_t* active = reinterpret_cast<int32_t*>(ws + bp.off_active);
     float* worst = reinterpret_cast<float*>(ws + bp.off_worst);
     uint32_t* sig = reinterpret_cast<uint32_t*>(ws + bp.off_sig);
     u64* ctr = reinterpret_cast<u64*>(ws + bp.off_ctr);      // [0] updates, [1] rows gathered
@@ -712,6 +868,7 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
     const double stop_below = (double)bp.delta * (double)bp.K * (double)n;
 
     int rc = KNNG_OK;
+    int num_cu = 0;
     u64* host_ctr = nullptr;
     // events: [0] start, [1] after init, then 4 per iteration (sample, join start, join end, merge), last = end
     const int max_rec = bp.max_iters < KNNG_STATS_MAX_ITERS ? bp.max_iters : KNNG_STATS_MAX_ITERS;
@@ -720,6 +877,12 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
     int iters = 0, converged = 0;
     if (stats) memset(stats, 0, sizeof(*stats));
 
+    {
+        int dev = 0;
+        HIPCHK(hipGetDevice(&dev));
+        HIPCHK(hipDeviceGetAttribute(&num_cu, hipDeviceAttributeMultiprocessorCount, dev));
+        if (num_cu < 1) num_cu = 1;
+    }
     HIPCHK(hipHostMalloc(reinterpret_cast<void**>(&host_ctr), 64, hipHostMallocDefault));
     if (stats) {
         ev = new hipEvent_t[n_ev];
@@ -742,20 +905,24 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
         hipLaunchKernelGGL(k_sample, dim3(row_blocks), dim3(256), 0, st, n, bp.K, bp.s, params->seed,
                            (uint32_t)it, G, newl, oldl, cnt, sig);
         HIPCHK(hipGetLastError());
+        hipLaunchKernelGGL(k_plan, dim3(1024), dim3(256), 0, st, n, bp.s, cnt, plan, active, ctr);
+        HIPCHK(hipGetLastError());
         if (rec) {
             HIPCHK(hipEventRecord(ev[2 + 4 * it], st));
-            hipLaunchKernelGGL(k_count_rows, dim3(1024), dim3(256), 0, st, n, bp.s, cnt, ctr + 1);
-            HIPCHK(hipGetLastError());
             HIPCHK(hipEventRecord(ev[3 + 4 * it], st));
         }
-        if (metric == 0) HIPCHK(launch_join_m<0>(st, vec, (uint32_t)it, points_dev, n, d, bp, newl, oldl, cnt, worst, sig, cand));
-        else HIPCHK(launch_join_m<1>(st, vec, (uint32_t)it, points_dev, n, d, bp, newl, oldl, cnt, worst, sig, cand));
+        {
+            JoinArgs ja{points_dev, d, bp.C, bp.s, (uint32_t)it, newl, oldl, plan, active, ctr + 2,
+                        worst, sig, cand, num_cu, n};
+            if (metric == 0) HIPCHK(launch_join<0>(st, vec, bp.S16, ja));
+            else HIPCHK(launch_join<1>(st, vec, bp.S16, ja));
+        }
         if (rec) HIPCHK(hipEventRecord(ev[4 + 4 * it], st));
         hipLaunchKernelGGL(k_merge, dim3(merge_blocks), dim3(256), 0, st, n, bp.K, bp.C, G, cand, worst, ctr);
         HIPCHK(hipGetLastError());
         if (rec) HIPCHK(hipEventRecord(ev[5 + 4 * it], st));
-        HIPCHK(hipMemcpyAsync(host_ctr, ctr, 16, hipMemcpyDeviceToHost, st));
-        HIPCHK(hipMemsetAsync(ctr, 0, 16, st));
+        HIPCHK(hipMemcpyAsync(host_ctr, ctr, 24, hipMemcpyDeviceToHost, st));
+        HIPCHK(hipMemsetAsync(ctr, 0, 24, st));
         HIPCHK(hipStreamSynchronize(st));
         iters = it + 1;
         if (rec) { stats->updates[it] = host_ctr[0]; stats->join_rows[it] = host_ctr[1]; }
