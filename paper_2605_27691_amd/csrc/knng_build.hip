@@ -776,6 +776,10 @@ static bool make_plan(int64_t n, int32_t d, int32_t k, const knng_params_t* p, B
     return true;
 }
 
+}  // namespace knng
+#include "knng_join_wave.h"
+namespace knng {
+
 struct JoinArgs {
     const float* pts; int d; int C; int s; uint32_t iter;
     const int32_t* newl; const int32_t* oldl; const int4* plan; const int32_t* active;
@@ -805,9 +809,34 @@ static hipError_t launch_join_k(hipStream_t st, const JoinArgs& a)
     return hipGetLastError();
 }
 
+template <int METRIC, int S16, bool VEC>
+static hipError_t launch_join_w(hipStream_t st, const JoinArgs& a)
+{
+    const int lds = 4 * WaveCfg<S16>::WBYTES;
+    auto kern = k_join_wave<METRIC, S16, VEC>;
+    static int blocks_per_cu = 0;            // per instantiation: resident workgroups per CU
+    if (blocks_per_cu == 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        int occ = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, 256, lds);
+        if (e != hipSuccess) return e;
+        blocks_per_cu = occ > 0 ? occ : 1;
+    }
+    int64_t grid = (int64_t)a.num_cu * blocks_per_cu;
+    if (grid > (a.n + 3) / 4) grid = (a.n + 3) / 4;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a.pts, a.d, a.C, a.s, a.iter, a.newl,
+                       a.oldl, a.plan, a.active, a.nactive, a.worst, a.sig, a.cand);
+    return hipGetLastError();
+}
+
 template <int METRIC>
 static hipError_t launch_join(hipStream_t st, bool vec, int S16, const JoinArgs& a)
 {
+    // s <= 16: one wavefront per point; larger samples: one workgroup per point
+    if (S16 == 1) return vec ? launch_join_w<METRIC, 1, true>(st, a) : launch_join_w<METRIC, 1, false>(st, a);
+    if (S16 == 2) return vec ? launch_join_w<METRIC, 2, true>(st, a) : launch_join_w<METRIC, 2, false>(st, a);
 #define KNNG_JOIN_CASE(S, DSV)                                                      \
     return vec ? launch_join_k<METRIC, S, DSV, true>(st, a) : launch_join_k<METRIC, S, DSV, false>(st, a)
     switch (S16) {

@@ -1,0 +1,364 @@
+// knng_join_wave.h -- the local join for s <= 16 (the paper's default parameters): one
+// wavefront per point, no workgroup barriers.  Included by knng_build.hip.
+//
+// With at most 64 members per point a point maps onto one 64-lane wavefront: lane m owns
+// member m (its id, threshold and signature bit live in that lane's registers; other lanes
+// read them with v_readlane), the wavefront owns every Gram tile of the point, and all
+// cross-lane traffic goes through the wavefront's private LDS region in program order, so no
+// s_barrier is needed.  Four wavefronts of a workgroup work on four different points and only
+// share the LDS allocation.  Each wavefront is persistent and software-pipelined over
+// (point, slab) units of 32 coordinates: while the matrix cores and the selection work on the
+// unit in LDS, the global loads of the next unit and the list record of the point after next
+// are in flight into registers.
+//
+// Per unit:  A  prefetched 16-byte pieces - pivot -> LDS slab X[64][36]
+//            B  issue the loads of the next unit
+//            C  one pass of v_mfma_f32_16x16x4_f32 over all tiles of the point: the operand
+//               tiles (16 members x 16 coordinates) are read once per k-step and shared by all
+//               output tiles, so up to 36 MFMAs follow 4 LDS reads
+// After the last slab: member norms from the diagonal tiles, distance block D to LDS (over X),
+// then lane m scans member m's partners: per residue class (partner index mod 4) the closest
+// partner that beats the member's threshold and is not in the member's signature is offered
+// with one 64-bit atomic min on cand[member][hash(partner) % C].
+//
+// The kernel is bound by instruction issue inside the CU, not by HBM (it runs at the same
+// speed on a cache-resident point set), so the code below trades generality for straight-line
+// instruction streams and a small register footprint (three wavefronts per SIMD without
+// spills): the gather has one uniform guard per group of rows, the Gram pass reads each
+// operand tile once per k-step, and the partner scan advances one LDS address per partner.
+// (Specialising the Gram pass on the tile counts was tried: the extra code paths cost 40
+// registers, spills, and 25% of the speed.)
+#pragma once
+
+namespace knng {
+
+template <int S16> struct WaveCfg {
+    static constexpr int NCOLS = 32 * S16;            // max members (<= 64 lanes)
+    static constexpr int MROWS = 16 * S16;            // max |NEW|
+    static constexpr int CT = 2 * S16;                // 16-member operand tiles
+#ifndef KNNG_WAVE_DS
+#define KNNG_WAVE_DS 32
+#endif
+    static constexpr int DS = KNNG_WAVE_DS;           // slab length (floats)
+    static constexpr int LD = DS + 4;                 // slab row stride: conflict-free ds_read_b128
+    static constexpr int LDD = NCOLS + 1;             // distance-block row stride (last column: +inf cell)
+    static constexpr int NL = NCOLS * (DS / 4) / 64;  // 16-byte pieces per lane and slab
+    static constexpr int NTILES = (3 * S16 * S16 + 3 * S16) / 2;  // upper triangle rows<S16 + extra diagonals
+    static constexpr int XBYTES = NCOLS * LD * 4 > MROWS * LDD * 4 ? NCOLS * LD * 4 : MROWS * LDD * 4;
+    // X/D | mid[2][NCOLS] | nrm[NCOLS] | sg[NCOLS+1][8]
+    static constexpr int WBYTES = ((XBYTES + NCOLS * (8 + 4) + (NCOLS + 1) * 4 * SIG_WORDS) + 255) & ~255;
+};
+
+// orders this wavefront's LDS accesses (they execute in order; this keeps the compiler from
+// moving them and makes returned data available)
+__device__ __forceinline__ void wave_lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+#ifndef KNNG_WAVE_OCC
+#define KNNG_WAVE_OCC 3
+#endif
+template <int METRIC, int S16, bool VEC>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(KNNG_WAVE_OCC, KNNG_WAVE_OCC)))
+k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
+            const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl, const int4* __restrict__ plan,
+            const int32_t* __restrict__ active, const u64* __restrict__ nactive_ptr,
+            const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand)
+{
+    using Cfg = WaveCfg<S16>;
+    constexpr int NCOLS = Cfg::NCOLS, CT = Cfg::CT, DS = Cfg::DS, LD = Cfg::LD, LDD = Cfg::LDD,
+                  NL = Cfg::NL, NTILES = Cfg::NTILES;
+    constexpr int INF_CELL = NCOLS;                             // D[0][NCOLS]: holds +inf
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int lane = lane_id();
+    const int wib = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    unsigned char* wbase = smem + wib * Cfg::WBYTES;
+    float* X = reinterpret_cast<float*>(wbase);                 // [NCOLS][LD], later D [MROWS][LDD]
+    int* midbuf = reinterpret_cast<int*>(wbase + Cfg::XBYTES);  // [2][NCOLS] member ids, double-buffered
+    float* nrm = reinterpret_cast<float*>(midbuf + 2 * NCOLS);  // [NCOLS] |x_m - x_v|^2
+    uint32_t* sg = reinterpret_cast<uint32_t*>(nrm + NCOLS);    // [NCOLS + 1][SIG_WORDS], slot nTot = pivot
+
+    const int r16 = lane & 15, kq = lane >> 4;
+    const int64_t nact = (int64_t)*nactive_ptr;
+    const int64_t GW = (int64_t)gridDim.x * 4;                  // wavefronts in the grid
+    int64_t pos = (int64_t)blockIdx.x * 4 + wib;
+    if (pos >= nact) return;
+
+    auto load_slot = [&](int64_t v) -> int {
+        if (lane < 2 * s) return newl[v * 2 * (int64_t)s + lane];
+        if (lane < 4 * s) return oldl[v * 2 * (int64_t)s + (lane - 2 * s)];
+        return 0;
+    };
+
+    // ---- prologue
+    int64_t v = active[pos];
+    int64_t v_nx = pos + GW < nact ? (int64_t)active[pos + GW] : -1;
+    int64_t v_nx2 = pos + 2 * GW < nact ? (int64_t)active[pos + 2 * GW] : -1;
+    int4 rc = plan[v];
+    int rid = load_slot(v);
+    int cur = 0;
+    {
+        const int m = member_of_slot(lane, s, rc);
+        if (m >= 0) midbuf[m] = rid;
+    }
+    PointPlan P = make_point(rc);
+    wave_lds_sync();
+
+    float4 buf[NL];
+    float4 pv;
+    // lane m < nTot: member m; lane nTot (if any): the pivot itself
+    int id_r = 0;
+    float thr_r = 0.0f;
+    uint4 sg_r0 = uint4{0, 0, 0, 0}, sg_r1 = uint4{0, 0, 0, 0};
+    auto issue_members = [&](const int* mid, int nTot, int64_t pivot_row) {
+        if (lane <= nTot) {
+            id_r = lane < nTot ? mid[lane] : (int)pivot_row;
+            thr_r = worst[id_r];
+            const uint4* sp = reinterpret_cast<const uint4*>(sig + (int64_t)id_r * SIG_WORDS);
+            sg_r0 = sp[0];
+            sg_r1 = sp[1];
+        }
+    };
+    // slab pieces: lane -> (piece c4 = lane & 7, rows (lane >> 3) + 8 i).  Rows are clamped to the
+    // last member instead of predicated: a group of 8 rows is loaded whole or not at all.
+    constexpr int QP = DS / 4, RPW = 64 / QP;              // pieces per row, rows per load
+    const int c4 = lane & (QP - 1), rsub = lane / QP;
+    auto issue_slab = [&](const int* mid, int nTot, int64_t pivot_row, int k0) {
+        const int t = k0 + 4 * c4;
+        pv = load_piece<VEC>(pts + pivot_row * d, t, d);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            if (RPW * i < nTot) {                               // uniform
+                const int row = rsub + RPW * i < nTot ? rsub + RPW * i : nTot - 1;
+                buf[i] = load_piece<VEC>(pts + (int64_t)mid[row] * d, t, d);
+            }
+        }
+    };
+
+    issue_members(midbuf, P.nTot, v);
+    issue_slab(midbuf, P.nTot, v, 0);
+    int4 rc_n = int4{0, 0, 0, 0};
+    int rid_n = 0;
+    if (v_nx >= 0) { rc_n = plan[v_nx]; rid_n = load_slot(v_nx); }
+
+    for (;;) {
+        const int* mid = midbuf + cur * NCOLS;
+        const int nNew = P.nNew, nTot = P.nTot, nfn = P.nfn, nfo = P.nfo;
+        const int nrt = (nNew + 15) >> 4, nct = (nTot + 15) >> 4;
+        const PointPlan Pn = make_point(rc_n);
+
+        // this point's member registers (loaded during the previous unit)
+        const int my_id = id_r;
+        const uint32_t my_thr = __float_as_uint(thr_r);
+        const uint32_t my_hb = sig_bit(my_id, iter);
+        if (lane <= nTot) {                                     // slot nTot <= NCOLS exists
+            reinterpret_cast<uint4*>(sg)[2 * lane] = sg_r0;
+            reinterpret_cast<uint4*>(sg)[2 * lane + 1] = sg_r1;
+        }
+
+        floatx4 acc[NTILES];
+#pragma unroll
+        for (int q = 0; q < NTILES; ++q) acc[q] = floatx4{0, 0, 0, 0};
+
+        for (int k0 = 0; k0 < d; k0 += DS) {
+            const bool last = k0 + DS >= d;
+            const int len = (d - k0) < DS ? (d - k0) : DS;
+            const int len16 = (len + 15) & ~15;
+            // ---- A: registers -> LDS (rows up to the end of the last loaded group of 8)
+            {
+                float* xdst = X + rsub * LD + 4 * c4;
+#pragma unroll
+                for (int i = 0; i < NL; ++i) {
+                    if (RPW * i < nTot) {                       // uniform
+                        float4 x = buf[i];
+                        x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w;
+                        *reinterpret_cast<float4*>(xdst + RPW * i * LD) = x;
+                    }
+                }
+            }
+            if (last && v_nx >= 0) {                            // next point's member ids
+                const int m = member_of_slot(lane, s, rc_n);
+                if (m >= 0) midbuf[(cur ^ 1) * NCOLS + m] = rid_n;
+            }
+            wave_lds_sync();
+            // ---- B: issue the loads of the next unit (one call site)
+            if (!last || v_nx >= 0) {
+                const int* nmid = last ? midbuf + (cur ^ 1) * NCOLS : mid;
+                const int n_tot = last ? Pn.nTot : nTot;
+                const int64_t n_piv = last ? v_nx : v;
+                if (last) issue_members(nmid, n_tot, n_piv);
+                issue_slab(nmid, n_tot, n_piv, last ? 0 : k0 + DS);
+                if (last && v_nx2 >= 0) { rc_n = plan[v_nx2]; rid_n = load_slot(v_nx2); }
+            }
+            // ---- C: all Gram tiles of the point for this slab
+                        for (int kk = 0; kk < len16; kk += 16) {
+                float4 x[CT];
+#pragma unroll
+                for (int t = 0; t < CT; ++t)
+                    if (t < nct) x[t] = *reinterpret_cast<const float4*>(X + (t * 16 + r16) * LD + 4 * kq + kk);
+                int q = 0;
+#pragma unroll
+                for (int rt = 0; rt < S16; ++rt) {
+#pragma unroll
+                    for (int ct = rt; ct < CT; ++ct, ++q) {
+                        if (ct < nct && (rt < nrt || rt == ct)) {
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[rt].x, x[ct].x, acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[rt].y, x[ct].y, acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[rt].z, x[ct].z, acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[rt].w, x[ct].w, acc[q], 0, 0, 0);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int ct = S16; ct < CT; ++ct, ++q) {
+                    if (ct < nct) {
+                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[ct].x, x[ct].x, acc[q], 0, 0, 0);
+                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[ct].y, x[ct].y, acc[q], 0, 0, 0);
+                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[ct].z, x[ct].z, acc[q], 0, 0, 0);
+                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[ct].w, x[ct].w, acc[q], 0, 0, 0);
+                    }
+                }
+            }
+            wave_lds_sync();
+        }
+
+        // ---- member norms from the diagonal tiles: lane (r16, kq) holds rows 4kq..4kq+3 of
+        // column r16, so the diagonal element sits in the lanes with r16 / 4 == kq
+        {
+            const int e = r16 & 3;
+            int q = 0;
+#pragma unroll
+            for (int rt = 0; rt < S16; ++rt) {
+#pragma unroll
+                for (int ct = rt; ct < CT; ++ct, ++q) {
+                    if (ct == rt && ct < nct && (r16 >> 2) == kq)
+                        nrm[ct * 16 + r16] = e == 0 ? acc[q][0] : e == 1 ? acc[q][1] : e == 2 ? acc[q][2] : acc[q][3];
+                }
+            }
+#pragma unroll
+            for (int ct = S16; ct < CT; ++ct, ++q) {
+                if (ct < nct && (r16 >> 2) == kq)
+                    nrm[ct * 16 + r16] = e == 0 ? acc[q][0] : e == 1 ? acc[q][1] : e == 2 ? acc[q][2] : acc[q][3];
+            }
+        }
+        wave_lds_sync();
+        // ---- distance block D[row][col] over the slab storage; cells outside NEW x members are
+        // +inf so the partner scan needs no bounds tests
+        float* D = X;
+        {
+            const float inf = __uint_as_float(0x7f800000u);
+            int q = 0;
+#pragma unroll
+            for (int rt = 0; rt < S16; ++rt) {
+#pragma unroll
+                for (int ct = rt; ct < CT; ++ct, ++q) {
+                    if (ct < nct && rt < nrt) {
+                        const int col = ct * 16 + r16;
+                        const float nc = nrm[col];
+                        const float4 nr = *reinterpret_cast<const float4*>(nrm + rt * 16 + 4 * kq);
+                        const float nra[4] = {nr.x, nr.y, nr.z, nr.w};
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int row = rt * 16 + 4 * kq + r;
+                            float l = nra[r] + nc - 2.0f * acc[q][r];
+                            if (METRIC == 1) l *= 0.5f;        // unit rows: 1 - <a,b> = |a-b|^2 / 2
+                            l = nonneg(l);
+                            D[row * LDD + col] = (row < nNew && col < nTot) ? l : inf;
+                        }
+                    }
+                }
+            }
+            if (lane == 0) D[INF_CELL] = inf;
+        }
+        // ---- the pivot's reverse members hold v in their rows, so |x_m - x_v|^2 is already
+        // known: offer them to v itself (closes v<-m edges into v->m without an extra distance)
+        {
+            const int m = lane;
+            const bool rev = m < nTot && ((m >= nfn && m < nNew) || (m >= nNew + nfo));
+            const uint32_t pthr = nTot < 64 ? (uint32_t)__builtin_amdgcn_readlane((int)my_thr, nTot & 63) : 0u;
+            if (rev) {
+                float l = nrm[m];
+                if (METRIC == 1) l *= 0.5f;
+                l = nonneg(l);
+                const uint32_t vw = sg[nTot * SIG_WORDS + (my_hb >> 5)];
+                if (__float_as_uint(l) < pthr && !((vw >> (my_hb & 31u)) & 1u)) {
+                    const uint32_t slot = below(hash32((uint32_t)my_id), (uint32_t)C);
+                    atomicMin(&cand[v * C + slot], pack_key(l, my_id, 1));
+                }
+            }
+        }
+        wave_lds_sync();
+        // ---- selection: lane m scans member m's partners j (j uniform, 4 residue classes).
+        // D[m][j] is stored at [lower tile][higher tile]: a lane walks its row (address + 1 per
+        // partner) or, where the partner's tile is the lower one, the partner's column
+        // (address + LDD).  OLD members pair with NEW partners only (column walk); lanes with
+        // nothing to look at sit on the +inf cell.
+        {
+            const int m = lane;
+            const bool ismem = m < nTot, isnew = m < nNew;
+            const int mt = m >> 4;
+            uint32_t bl[4], bj[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { bl[u] = ismem ? my_thr : 0u; bj[u] = 0xffffffffu; }
+            const uint32_t* msig = sg + m * SIG_WORDS;
+            const int nNew4 = (nNew + 3) & ~3, nTot4 = (nTot + 3) & ~3;
+            // four partners per step: their distances are read together, a wavefront-wide vote
+            // skips groups in which nobody improves, then the four signature words are read
+            // together -- two LDS round trips per four partners
+            auto scan = [&](int jb, int je, int addr, int step) {
+                for (int j0 = jb; j0 < je; j0 += 4) {
+                    uint32_t l[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) l[u] = __float_as_uint(D[addr + u * step]);
+                    addr += 4 * step;
+                    bool any = false;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) any = any || (l[u] < bl[u]);
+                    if (__ballot(any) == 0ull) continue;
+                    uint32_t hj[4], wv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        hj[u] = (uint32_t)__builtin_amdgcn_readlane((int)my_hb, j0 + u);
+                        wv[u] = msig[hj[u] >> 5];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int idj = __builtin_amdgcn_readlane(my_id, j0 + u);
+                        const bool ok = (l[u] < bl[u]) && idj != my_id && ((wv[u] >> (hj[u] & 31u)) & 1u) == 0u;
+                        bl[u] = ok ? l[u] : bl[u];
+                        bj[u] = ok ? (uint32_t)(j0 + u) : bj[u];
+                    }
+                }
+            };
+            // NEW partners below 16: NEW members of tile 0 walk their row, everyone else the column
+            {
+                const int je = nNew4 < 16 ? nNew4 : 16;
+                const bool row = isnew && mt == 0;
+                scan(0, je, !ismem ? INF_CELL : row ? m * LDD : m, !ismem ? 0 : row ? 1 : LDD);
+            }
+            // NEW partners from 16: NEW members walk their row, OLD members the column
+            if (nNew4 > 16)
+                scan(16, nNew4, !ismem ? INF_CELL : isnew ? m * LDD + 16 : 16 * LDD + m, !ismem ? 0 : isnew ? 1 : LDD);
+            // OLD partners: NEW members only
+            if (nTot4 > nNew4)
+                scan(nNew4, nTot4, isnew ? m * LDD + nNew4 : INF_CELL, isnew ? 1 : 0);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int pid = __shfl(my_id, (int)(bj[u] & 63u)); // all lanes take part in the shuffle
+                if (bj[u] != 0xffffffffu) {
+                    const uint32_t slot = below(hash32((uint32_t)pid), (uint32_t)C);
+                    atomicMin(&cand[(int64_t)my_id * C + slot], pack_key(__uint_as_float(bl[u]), pid, 1));
+                }
+            }
+        }
+        // ---- advance
+        if (v_nx < 0) break;
+        wave_lds_sync();
+        pos += GW;
+        v = v_nx;
+        v_nx = v_nx2;
+        v_nx2 = pos + 2 * GW < nact ? (int64_t)active[pos + 2 * GW] : -1;
+        P = Pn;
+        cur ^= 1;
+    }
+}
+
+}  // namespace knng
