@@ -28,9 +28,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 SIG_BYTES = 32          # row signature read per gathered member
-# HBM bytes per join launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a
-# copy kernel of known size); see profiles/.  None until measured for the default workload.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+# HBM-side bytes per join launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each
+# scaled by what a plain 1 GiB device copy reads: 2.0 and 1.0 KiB per count), averaged over the same
+# launch mix as the timed region.  Only measured for the default workload and parameters
+# (profiles/k_join_config1_1m_d128_hbm_traffic.txt: 18.32 GB fetched + 1.77 GB written).
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("u8gmm1024_1m_d128_l2", 32, 0.5): 20.09e9}
 
 
 def parse():
@@ -46,6 +48,8 @@ def parse():
     ap.add_argument("--recall-rows", type=int, default=20000)
     ap.add_argument("--oracle-rows", type=int, default=128)
     ap.add_argument("--cpu-n", type=int, default=60000, help="points of the CPU-baseline sample (0 = skip)")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (counter calibration under rocprofv3 --pmc)")
     return ap.parse_args()
 
 
@@ -80,6 +84,13 @@ def main():
     stats = [step(i) for i in range(a.steps)]
     torch.cuda.synchronize()
     sec = (time.perf_counter() - t0) / max(a.steps, 1)
+
+    if a.calib_copy_mib > 0:       # a copy kernel of known size: FETCH_SIZE / WRITE_SIZE should read this many MiB
+        src = torch.empty(a.calib_copy_mib * 262144, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- roofline of the dominant kernel (local join), over the timed region
     join_ms = sum(sum(s["join_ms"]) for s in stats)
@@ -134,7 +145,7 @@ def main():
                       "merge": last["ms_merge"], "finalize": last["ms_finalize"], "total": last["ms_total"]},
         "roofline": {"kernel": "k_join", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
+                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((w.name, a.k_build or k, a.rho or 0.5)),
                      "launches": launches, "avg_launch_ms": join_ms / max(launches, 1),
                      "alg_bytes_per_launch": alg_bytes / max(launches, 1)},
         "cpu_baseline": cpu,
