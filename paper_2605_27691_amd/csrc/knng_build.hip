@@ -1,16 +1,17 @@
 // knng_build.hip -- lock-free NN-Descent on one MI355X (gfx950).
 //
 // Implements knng_build_knn_graph: random initial graph, then per iteration
-//   k_sample   per-point sampling of new / old neighbours with reverse edges  (paper Sec. 3.1)
+//   k_update   one wavefront per point folds its candidate list into its row   (Sec. 3.1.1)
+//              and samples new / old neighbours with reverse edges for the next join (Sec. 3.1)
+//   k_plan     fixes the list lengths and compacts the points that have work
 //   k_join     local join: gather the sampled neighbours' vectors into LDS, fp32 MFMA Gram
 //              block, per-member best candidate, 64-bit atomic-min into the fixed-size
 //              candidate lists of the two end points                           (Sec. 3.1.1)
-//   k_merge    one wavefront per point folds its candidate list into its row   (Sec. 3.1.1)
 // until an iteration accepts fewer than delta*K*n updates (Sec. 3.1), then
 //   k_finalize exact fp64 re-evaluation of every kept distance, sort, cut to k (Sec. 5.3.1).
 //
-// Memory model: G is only ever written by the wavefront that owns the row (k_init, k_sample,
-// k_merge); all cross-row traffic of an iteration goes through the candidate slots with
+// Memory model: G is only ever written by the wavefront that owns the row (k_init, k_update);
+// all cross-row traffic of an iteration goes through the candidate slots with
 // order-independent atomic mins, so there are no locks and no retry loops anywhere.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -65,9 +66,12 @@ __device__ __forceinline__ float dist_group8(const float* __restrict__ a, const 
 // The join uses it to skip partners a member most likely already holds: such offers would be
 // rejected by the merge anyway, cost an atomic each, and would shadow real candidates in the
 // hashed candidate slots.  A false positive (about 12% at K = 32) only delays a candidate.
-// k_sample rebuilds every row's signature each iteration, right before the join reads it.
+// k_update rebuilds every row's signature each iteration, right before the join reads it.
 // ------------------------------------------------------------------------------------------
 constexpr int SIG_WORDS = 8;
+// orders one wavefront's own LDS accesses (they execute in order; this keeps the compiler from
+// moving them and makes returned data available) -- enough for wavefront-private LDS regions
+__device__ __forceinline__ void wave_lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 // The bit an id maps to changes with the iteration (salt), so a false positive does not
 // shadow the same candidate for good.
 __device__ __forceinline__ uint32_t sig_bit(int id, uint32_t salt)
@@ -153,64 +157,156 @@ k_init(const float* __restrict__ pts, int64_t n, int d, int K, int C, u64 seed,
 }
 
 // ------------------------------------------------------------------------------------------
-// k_sample: one wavefront per point.  Up to s new-flagged entries (a cyclic window of the
-// flagged ones from a random start, so every flagged entry is equally likely) become the
-// forward new sample and lose their flag; up to s unflagged entries the forward old sample.
-// Each forward edge v->u also puts v into u's reverse sample: an atomic counter hands out the
-// first s slots, later arrivals replace a random slot with probability s/(arrivals so far).
-// Lists: NEW[v] = [fwd 0..s) [rev s..2s), OLD likewise; cnt[v] = {fwd new, fwd old, rev new, rev old}.
+// k_update: the per-point work between two joins, one wavefront per point (persistent
+// wavefronts stride over the points and prefetch the next point's row and candidate slots).
+//
+// Merge (Sec. 3.1.1: a single owner per point folds its candidate list into its row, so no
+// races): a candidate is accepted if its id is not already in the row and it sorts before the
+// row's K-th entry; the union is re-ranked by counting, the first K kept, accepted entries
+// flagged new and counted as updates; used slots are set back to empty.
+//
+// Sample (Sec. 3.1, rate rho) for the next join, from the merged row while it is still in
+// registers: up to s new-flagged entries (a cyclic window of the flagged ones from a random
+// start, so every flagged entry is equally likely) become the forward new sample and lose
+// their flag; up to s unflagged entries the forward old sample.  Each forward edge v->u also
+// puts v into u's reverse sample: an atomic counter hands out the first s slots, later
+// arrivals replace a random slot with probability s/(arrivals so far).
+// Lists: NEW[v] = [fwd 0..s) [rev s..2s), OLD likewise; cnt[v] = {fwd new, fwd old, rev new,
+// rev old}.  The row's signature for this iteration is rebuilt here as well.
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_sample(int64_t n, int K, int s, u64 seed, uint32_t iter, u64* __restrict__ G,
-         int32_t* __restrict__ newl, int32_t* __restrict__ oldl, int32_t* __restrict__ cnt,
-         uint32_t* __restrict__ sig)
+k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
+         u64* __restrict__ G, u64* __restrict__ cand, int32_t* __restrict__ newl, int32_t* __restrict__ oldl,
+         int32_t* __restrict__ cnt, uint32_t* __restrict__ sig, float* __restrict__ worst,
+         u64* __restrict__ updates)
 {
+    __shared__ u64 rowbuf[4][WAVE];
+    __shared__ uint32_t sigbuf[4][SIG_WORDS];
+    __shared__ u64 part[4];
     const int lane = lane_id();
-    const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (v >= n) return;
-    const bool active = lane < K;
-    u64 e = active ? G[v * K + lane] : 0ull;
-    const bool isnew = active && (e & 1ull);
-    const bool isold = active && !(e & 1ull);
-    const int id = key_id(e);
-    store_signature(sig + v * SIG_WORDS, id, active, iter);
-    const u64 newmask = __ballot(isnew), oldmask = __ballot(isold);
-    const int cn = __popcll(newmask), co = __popcll(oldmask);
+    const int w = (int)(threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
     const u64 lt = lanemask_lt();
-    const int64_t base = v * 2 * (int64_t)s;
     const uint32_t tag = 0x200u + 4u * iter;
-    if (isnew) {
-        int off = (int)below(rnd32(seed, tag, (uint32_t)v, 0u), (uint32_t)cn);
-        int p = __popcll(newmask & lt) - off;
-        if (p < 0) p += cn;
-        if (p < s) {
-            newl[base + p] = id;
-            G[v * K + lane] = e & ~1ull;
-            int pos = atomicAdd(&cnt[(int64_t)id * 4 + 2], 1);
-            if (pos < s) newl[(int64_t)id * 2 * s + s + pos] = (int32_t)v;
-            else {
-                int r = (int)below(rnd32(seed, tag + 2u, (uint32_t)v, (uint32_t)lane), (uint32_t)pos + 1u);
-                if (r < s) newl[(int64_t)id * 2 * s + s + r] = (int32_t)v;
+    u64 accepted = 0;
+
+    int64_t v = (int64_t)blockIdx.x * 4 + w;
+    u64 lk_n = EMPTY_KEY, ck_n = EMPTY_KEY;
+    if (v < n) {
+        if (lane < K) lk_n = G[v * K + lane];
+        if (lane < C) ck_n = cand[v * C + lane];
+    }
+    for (; v < n; v += nwaves) {
+        u64 row = lk_n;                              // lane < K: entry `lane` of the row
+        const u64 ck = ck_n;
+        const int64_t vn = v + nwaves;
+        lk_n = EMPTY_KEY; ck_n = EMPTY_KEY;
+        if (vn < n) {                                // prefetch the next point of this wavefront
+            if (lane < K) lk_n = G[vn * K + lane];
+            if (lane < C) ck_n = cand[vn * C + lane];
+        }
+        bool changed = false;
+        // ---- merge
+        if (__ballot(ck != EMPTY_KEY) != 0ull) {
+            if (ck != EMPTY_KEY) cand[v * C + lane] = EMPTY_KEY;
+            const u64 lo = key_order(row);
+            const u64 co = key_order(ck);
+            const u64 last = bcast64(lo, K - 1);
+            bool valid = ck != EMPTY_KEY && co < last;
+            const int cid = key_id(ck), lid = key_id(row);
+            if (__ballot(valid) != 0ull) {
+                for (int i = 0; i < K; ++i) {
+                    int li = (int)bcast32((uint32_t)lid, i);
+                    if (li == cid) valid = false;
+                }
+                const u64 vm = __ballot(valid);
+                if (vm != 0ull) {
+                    // ranks in the union of the row and the accepted candidates
+                    int rl = lane;                   // the row is ascending already
+                    int rc = 0;
+                    for (u64 m = vm; m; m &= m - 1) {
+                        int j = __ffsll((long long)m) - 1;
+                        u64 cj = bcast64(co, j);
+                        rl += (cj < lo) ? 1 : 0;
+                        rc += (cj < co) ? 1 : 0;
+                    }
+                    for (int i = 0; i < K; ++i) rc += (bcast64(lo, i) < co) ? 1 : 0;
+                    const bool in = valid && rc < K;
+                    if (lane < K && rl < K) rowbuf[w][rl] = row;
+                    if (in) rowbuf[w][rc] = ck | 1ull;
+                    wave_lds_sync();
+                    row = lane < K ? rowbuf[w][lane] : EMPTY_KEY;
+                    wave_lds_sync();
+                    changed = true;
+                    accepted += (u64)__popcll(__ballot(in));
+                    if (lane == K - 1) worst[v] = key_dist(row);
+                }
             }
         }
-    }
-    if (isold) {
-        int off = (int)below(rnd32(seed, tag + 1u, (uint32_t)v, 0u), (uint32_t)co);
-        int p = __popcll(oldmask & lt) - off;
-        if (p < 0) p += co;
-        if (p < s) {
-            oldl[base + p] = id;
-            int pos = atomicAdd(&cnt[(int64_t)id * 4 + 3], 1);
-            if (pos < s) oldl[(int64_t)id * 2 * s + s + pos] = (int32_t)v;
-            else {
-                int r = (int)below(rnd32(seed, tag + 3u, (uint32_t)v, (uint32_t)lane), (uint32_t)pos + 1u);
-                if (r < s) oldl[(int64_t)id * 2 * s + s + r] = (int32_t)v;
+        if (!do_sample) {
+            if (changed && lane < K) G[v * K + lane] = row;
+            continue;
+        }
+        // ---- sample for the next join
+        const bool active = lane < K;
+        const bool isnew = active && (row & 1ull);
+        const bool isold = active && !(row & 1ull);
+        const int id = key_id(row);
+        const u64 newmask = __ballot(isnew), oldmask = __ballot(isold);
+        const int cn = __popcll(newmask), co_ = __popcll(oldmask);
+        const int64_t base = v * 2 * (int64_t)s;
+        bool cleared = false;
+        if (isnew) {
+            int off = (int)below(rnd32(seed, tag, (uint32_t)v, 0u), (uint32_t)cn);
+            int p = __popcll(newmask & lt) - off;
+            if (p < 0) p += cn;
+            if (p < s) {
+                newl[base + p] = id;
+                row &= ~1ull;
+                cleared = true;
+                int pos = atomicAdd(&cnt[(int64_t)id * 4 + 2], 1);
+                if (pos < s) newl[(int64_t)id * 2 * s + s + pos] = (int32_t)v;
+                else {
+                    int r = (int)below(rnd32(seed, tag + 2u, (uint32_t)v, (uint32_t)lane), (uint32_t)pos + 1u);
+                    if (r < s) newl[(int64_t)id * 2 * s + s + r] = (int32_t)v;
+                }
             }
         }
+        if (isold) {
+            int off = (int)below(rnd32(seed, tag + 1u, (uint32_t)v, 0u), (uint32_t)co_);
+            int p = __popcll(oldmask & lt) - off;
+            if (p < 0) p += co_;
+            if (p < s) {
+                oldl[base + p] = id;
+                int pos = atomicAdd(&cnt[(int64_t)id * 4 + 3], 1);
+                if (pos < s) oldl[(int64_t)id * 2 * s + s + pos] = (int32_t)v;
+                else {
+                    int r = (int)below(rnd32(seed, tag + 3u, (uint32_t)v, (uint32_t)lane), (uint32_t)pos + 1u);
+                    if (r < s) oldl[(int64_t)id * 2 * s + s + r] = (int32_t)v;
+                }
+            }
+        }
+        if (active && (changed || cleared)) G[v * K + lane] = row;
+        if (lane == 0) {
+            cnt[v * 4 + 0] = cn < s ? cn : s;
+            cnt[v * 4 + 1] = co_ < s ? co_ : s;
+        }
+        // ---- signature of the row for this iteration: OR of one bit per entry, through LDS
+        if (lane < SIG_WORDS) sigbuf[w][lane] = 0u;
+        wave_lds_sync();
+        if (active) {
+            const uint32_t h = sig_bit(id, iter);
+            atomicOr(&sigbuf[w][h >> 5], 1u << (h & 31u));
+        }
+        wave_lds_sync();
+        if (lane < SIG_WORDS) sig[v * SIG_WORDS + lane] = sigbuf[w][lane];
+        wave_lds_sync();
     }
-    if (lane == 0) {
-        cnt[v * 4 + 0] = cn < s ? cn : s;
-        cnt[v * 4 + 1] = co < s ? co : s;
+    if (lane == 0) part[w] = accepted;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u64 t = part[0] + part[1] + part[2] + part[3];
+        if (t) atomicAdd(updates, t);
     }
 }
 
@@ -622,67 +718,6 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
 }
 
 // ------------------------------------------------------------------------------------------
-// k_merge: one wavefront per point folds the candidate slots into the row (Sec. 3.1.1: a
-// single owner per point, so no races).  A candidate is accepted if its id is not already in
-// the row and it sorts before the row's K-th entry; the union is re-ranked by counting, the
-// first K kept, accepted entries flagged new and counted; used slots are set back to empty.
-// ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
-k_merge(int64_t n, int K, int C, u64* __restrict__ G, u64* __restrict__ cand,
-        float* __restrict__ worst, u64* __restrict__ updates)
-{
-    __shared__ u64 part[4];
-    const int lane = lane_id();
-    const int64_t wave0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t nwaves = (int64_t)gridDim.x * 4;
-    u64 accepted = 0;
-    for (int64_t v = wave0; v < n; v += nwaves) {
-        u64 ck = lane < C ? cand[v * C + lane] : EMPTY_KEY;
-        if (__ballot(ck != EMPTY_KEY) == 0ull) continue;
-        if (ck != EMPTY_KEY) cand[v * C + lane] = EMPTY_KEY;
-        const u64 lk = lane < K ? G[v * K + lane] : EMPTY_KEY;
-        const u64 lo = key_order(lk);
-        const u64 co = key_order(ck);
-        const u64 last = bcast64(lo, K - 1);
-        bool valid = ck != EMPTY_KEY && co < last;
-        const int cid = key_id(ck), lid = key_id(lk);
-        if (__ballot(valid) == 0ull) continue;
-        for (int i = 0; i < K; ++i) {
-            int li = (int)bcast32((uint32_t)lid, i);
-            if (li == cid) valid = false;
-        }
-        u64 vm = __ballot(valid);
-        if (vm == 0ull) continue;
-        // ranks in the union of the row and the accepted candidates
-        int rl = lane;                           // the row is ascending already
-        int rc = 0;
-        for (u64 m = vm; m; m &= m - 1) {
-            int j = __ffsll((long long)m) - 1;
-            u64 cj = bcast64(co, j);
-            rl += (cj < lo) ? 1 : 0;
-            rc += (cj < co) ? 1 : 0;
-        }
-        for (int i = 0; i < K; ++i) rc += (bcast64(lo, i) < co) ? 1 : 0;
-        if (lane < K && rl < K) {
-            G[v * K + rl] = lk;
-            if (rl == K - 1) worst[v] = key_dist(lk);
-        }
-        const bool in = valid && rc < K;
-        if (in) {
-            G[v * K + rc] = ck | 1ull;
-            if (rc == K - 1) worst[v] = key_dist(ck);
-        }
-        accepted += (u64)__popcll(__ballot(in));
-    }
-    if (lane == 0) part[threadIdx.x >> 6] = accepted;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        u64 t = part[0] + part[1] + part[2] + part[3];
-        if (t) atomicAdd(updates, t);
-    }
-}
-
-// ------------------------------------------------------------------------------------------
 // k_finalize: one wavefront per point, 4 points per workgroup.  The K neighbour vectors are
 // staged slab by slab in LDS (coalesced), then lane i walks neighbour i's slab in index order
 // with the fp64 recipe, so the value written equals a sequential fp64 evaluation bit for bit.
@@ -893,7 +928,7 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
     knng_stats_t* stats = params->stats_host;
     const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(points_dev) & 15u) == 0);
     const unsigned row_blocks = (unsigned)((n + 3) / 4);
-    const unsigned merge_blocks = row_blocks < 256u * 16u ? row_blocks : 256u * 16u;
+    unsigned upd_blocks = 0;                          // persistent k_update grid, set once num_cu is known
     const double stop_below = (double)bp.delta * (double)bp.K * (double)n;
 
     int rc = KNNG_OK;
@@ -901,7 +936,7 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
     u64* host_ctr = nullptr;
     // events: [0] start, [1] after init, then 4 per iteration (sample, join start, join end, merge), last = end
     const int max_rec = bp.max_iters < KNNG_STATS_MAX_ITERS ? bp.max_iters : KNNG_STATS_MAX_ITERS;
-    const int n_ev = stats ? 4 + 4 * max_rec : 0;
+    const int n_ev = stats ? 8 + 4 * max_rec : 0;
     hipEvent_t* ev = nullptr;
     int iters = 0, converged = 0;
     if (stats) memset(stats, 0, sizeof(*stats));
@@ -911,6 +946,7 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
         HIPCHK(hipGetDevice(&dev));
         HIPCHK(hipDeviceGetAttribute(&num_cu, hipDeviceAttributeMultiprocessorCount, dev));
         if (num_cu < 1) num_cu = 1;
+        upd_blocks = row_blocks < (unsigned)num_cu * 8u ? row_blocks : (unsigned)num_cu * 8u;
     }
     HIPCHK(hipHostMalloc(reinterpret_cast<void**>(&host_ctr), 64, hipHostMallocDefault));
     if (stats) {
@@ -929,17 +965,32 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
     HIPCHK(hipGetLastError());
     if (stats) HIPCHK(hipEventRecord(ev[1], st));
 
-    for (int it = 0; it < bp.max_iters; ++it) {
+    // Iteration it: k_update merges what join it-1 offered and samples for join it; the host
+    // reads the update count of iteration it-1 (the only device->host crossing of the loop)
+    // and stops before join it if it fell below delta*K*n.
+    for (int it = 0; it <= bp.max_iters; ++it) {
+        const bool more = it < bp.max_iters;         // false: final merge-only pass
+        if (it == 0 && !more) break;
         const bool rec = stats && it < max_rec;
-        hipLaunchKernelGGL(k_sample, dim3(row_blocks), dim3(256), 0, st, n, bp.K, bp.s, params->seed,
-                           (uint32_t)it, G, newl, oldl, cnt, sig);
+        hipLaunchKernelGGL(k_update, dim3(upd_blocks), dim3(256), 0, st, n, bp.K, bp.C, bp.s, params->seed,
+                           (uint32_t)it, more ? 1 : 0, G, cand, newl, oldl, cnt, sig, worst, ctr);
         HIPCHK(hipGetLastError());
+        if (rec) HIPCHK(hipEventRecord(ev[2 + 4 * it], st));
+        if (stats && !more) HIPCHK(hipEventRecord(ev[n_ev - 2], st));
+        if (it > 0) {
+            HIPCHK(hipMemcpyAsync(host_ctr, ctr, 24, hipMemcpyDeviceToHost, st));
+            HIPCHK(hipMemsetAsync(ctr, 0, 24, st));
+            HIPCHK(hipStreamSynchronize(st));
+            if (stats && it - 1 < max_rec) {
+                stats->updates[it - 1] = host_ctr[0];
+                stats->join_rows[it - 1] = host_ctr[1];
+            }
+            if ((double)host_ctr[0] < stop_below) { converged = 1; break; }
+        }
+        if (!more) break;
         hipLaunchKernelGGL(k_plan, dim3(1024), dim3(256), 0, st, n, bp.s, cnt, plan, active, ctr);
         HIPCHK(hipGetLastError());
-        if (rec) {
-            HIPCHK(hipEventRecord(ev[2 + 4 * it], st));
-            HIPCHK(hipEventRecord(ev[3 + 4 * it], st));
-        }
+        if (rec) HIPCHK(hipEventRecord(ev[3 + 4 * it], st));
         {
             JoinArgs ja{points_dev, d, bp.C, bp.s, (uint32_t)it, newl, oldl, plan, active, ctr + 2,
                         worst, sig, cand, num_cu, n};
@@ -947,15 +998,7 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
             else HIPCHK(launch_join<1>(st, vec, bp.S16, ja));
         }
         if (rec) HIPCHK(hipEventRecord(ev[4 + 4 * it], st));
-        hipLaunchKernelGGL(k_merge, dim3(merge_blocks), dim3(256), 0, st, n, bp.K, bp.C, G, cand, worst, ctr);
-        HIPCHK(hipGetLastError());
-        if (rec) HIPCHK(hipEventRecord(ev[5 + 4 * it], st));
-        HIPCHK(hipMemcpyAsync(host_ctr, ctr, 24, hipMemcpyDeviceToHost, st));
-        HIPCHK(hipMemsetAsync(ctr, 0, 24, st));
-        HIPCHK(hipStreamSynchronize(st));
         iters = it + 1;
-        if (rec) { stats->updates[it] = host_ctr[0]; stats->join_rows[it] = host_ctr[1]; }
-        if ((double)host_ctr[0] < stop_below) { converged = 1; break; }
     }
     {
         const int lds = 4 * (bp.K + 1) * FIN_LD * 4;
@@ -976,14 +1019,21 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
         HIPCHK(hipEventElapsedTime(&ms, ev[0], ev[1])); stats->ms_init = ms;
         const int recd = iters < max_rec ? iters : max_rec;
         for (int it = 0; it < recd; ++it) {
-            hipEvent_t prev = it == 0 ? ev[1] : ev[5 + 4 * (it - 1)];
+            hipEvent_t prev = it == 0 ? ev[1] : ev[4 + 4 * (it - 1)];
             HIPCHK(hipEventElapsedTime(&ms, prev, ev[2 + 4 * it])); stats->ms_sample += ms;
             HIPCHK(hipEventElapsedTime(&ms, ev[3 + 4 * it], ev[4 + 4 * it]));
             stats->join_ms[it] = ms; stats->ms_join += ms;
-            HIPCHK(hipEventElapsedTime(&ms, ev[4 + 4 * it], ev[5 + 4 * it])); stats->ms_merge += ms;
         }
-        hipEvent_t lastit = recd > 0 ? ev[5 + 4 * (recd - 1)] : ev[1];
-        HIPCHK(hipEventElapsedTime(&ms, lastit, ev[n_ev - 1])); stats->ms_finalize = ms;
+        // the k_update after the last join (merge; when stopped by convergence also a sample)
+        hipEvent_t lastj = recd > 0 ? ev[4 + 4 * (recd - 1)] : ev[1];
+        if (recd > 0) {
+            hipEvent_t lastu = (iters == bp.max_iters) ? ev[n_ev - 2] : ev[2 + 4 * (recd < max_rec ? recd : max_rec - 1)];
+            if (iters == bp.max_iters || recd < max_rec) {
+                HIPCHK(hipEventElapsedTime(&ms, lastj, lastu)); stats->ms_merge = ms;
+                lastj = lastu;
+            }
+        }
+        HIPCHK(hipEventElapsedTime(&ms, lastj, ev[n_ev - 1])); stats->ms_finalize = ms;
         HIPCHK(hipEventElapsedTime(&ms, ev[0], ev[n_ev - 1])); stats->ms_total = ms;
     }
 done:

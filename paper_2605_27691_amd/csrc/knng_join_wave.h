@@ -49,10 +49,6 @@ template <int S16> struct WaveCfg {
     static constexpr int WBYTES = ((XBYTES + NCOLS * (8 + 4) + (NCOLS + 1) * 4 * SIG_WORDS) + 255) & ~255;
 };
 
-// orders this wavefront's LDS accesses (they execute in order; this keeps the compiler from
-// moving them and makes returned data available)
-__device__ __forceinline__ void wave_lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-
 #ifndef KNNG_WAVE_OCC
 #define KNNG_WAVE_OCC 3
 #endif
