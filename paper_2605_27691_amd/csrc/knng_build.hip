@@ -184,7 +184,7 @@ k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
     __shared__ uint32_t sigbuf[4][SIG_WORDS];
     __shared__ u64 part[4];
     const int lane = lane_id();
-    const int w = (int)(threadIdx.x >> 6);
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // keeps v scalar
     const int64_t nwaves = (int64_t)gridDim.x * 4;
     const u64 lt = lanemask_lt();
     const uint32_t tag = 0x200u + 4u * iter;

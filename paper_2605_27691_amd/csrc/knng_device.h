@@ -35,9 +35,9 @@ __device__ __forceinline__ uint32_t hash32(uint32_t x)
 }
 __device__ __forceinline__ uint32_t rnd32(u64 seed, uint32_t tag, uint32_t row, uint32_t slot)
 {
-    uint32_t h = hash32((uint32_t)seed ^ 0x9e3779b9u);
-    h = hash32(h ^ (uint32_t)(seed >> 32));
-    h = hash32(h + tag * 0x85ebca6bu);
+    // (seed, tag) and usually row are uniform across a wavefront, so the first two rounds run on
+    // the scalar unit; only the last round is per lane
+    uint32_t h = hash32(((uint32_t)seed ^ 0x9e3779b9u) + (uint32_t)(seed >> 32) * 0x85ebca6bu + tag * 0x27d4eb2fu);
     h = hash32(h ^ row);
     return hash32(h + slot * 0xc2b2ae35u);
 }

@@ -246,3 +246,53 @@ def test_build_argument_errors_leave_outputs_untouched():
         knng.knng_build_knn_graph(x, 8, 0, workspace=ws, ids_out=ids, dists_out=dists)
     assert ei.value.code == -2
     assert bool((ids == -5).all()) and bool((dists == -5.0).all())
+
+
+# ------------------------------------------------------------------ full-size workloads (sampled checks)
+def _full_size_case(idx, kw, oracle_rows, recall_rows=10_000, min_recall=0.95):
+    """The benchmark's launch configuration at the workload's full size: exact rows and row
+    invariants are checked against the oracle on sampled rows, recall on a larger sample
+    whose exact rows come from the GPU brute force (itself checked on the oracle rows)."""
+    x, w = workloads.make(idx, device=DEV)
+    n, k = w.n, w.k
+    rows = workloads.sample_rows(n, recall_rows)
+    rows_d = torch.from_numpy(rows).to(DEV)
+    ex_i, ex_d = knng.knng_brute_knn(x, k, w.metric, rows_d)
+    ids, dists, st = knng.knng_build_knn_graph(x, k, w.metric, seed=0, **kw)
+    sel = rows_d.long()
+    t_i, t_d = ids[sel].contiguous(), dists[sel].contiguous()
+    rec = knng.knng_graph_recall(t_i, t_d, ex_i, ex_d, k, 0)
+    rec1 = knng.knng_graph_recall(t_i, t_d, ex_i, ex_d, k, 1)
+    assert rec >= min_recall and rec1 >= rec, (rec, rec1)
+    assert st["converged"] and st["iterations"] < 100
+    # oracle on a few of the sampled rows
+    xh = x.cpu().numpy()
+    sub = np.linspace(0, len(rows) - 1, oracle_rows).astype(np.int64)
+    o_i, o_d = oracle.brute_knn(xh, k, w.metric, query_rows=rows[sub])
+    assert np.array_equal(o_i, ex_i[sub].cpu().numpy())
+    assert np.array_equal(o_d, ex_d[sub].cpu().numpy())
+    viol = oracle.check_graph(xh, t_i[sub].cpu().numpy(), t_d[sub].cpu().numpy(), w.metric,
+                              rel_tol=0.0, rows=rows[sub])
+    assert sum(viol.values()) == 0, viol
+    # properties that hold at any size, on every row: ids in range, no self loops, rows ascending
+    assert int(ids.min()) >= 0 and int(ids.max()) < n
+    assert not bool((ids == torch.arange(n, device=DEV, dtype=torch.int32)[:, None]).any())
+    assert bool((dists[:, 1:] >= dists[:, :-1]).all()) and bool((dists >= 0).all())
+    srt = ids.sort(dim=1).values
+    assert not bool((srt[:, 1:] == srt[:, :-1]).any())             # no duplicate ids in a row
+
+
+def test_full_size_config1_sift_shape():
+    _full_size_case(1, {}, oracle_rows=48)
+
+
+def test_full_size_config2_unit_vectors_ip():
+    _full_size_case(2, {}, oracle_rows=48)
+
+
+def test_full_size_config3_gist_shape():
+    _full_size_case(3, {}, oracle_rows=16, recall_rows=4000)
+
+
+def test_full_size_config4_twenty_million():
+    _full_size_case(4, dict(k_build=64), oracle_rows=8, recall_rows=4000)
