@@ -291,9 +291,10 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             const int m = lane;
             const bool ismem = m < nTot, isnew = m < nNew;
             const int mt = m >> 4;
-            uint32_t bl[4], bj[4];
+            constexpr int NCLS = OFFERS_PER_MEMBER;            // residue classes = offers per member
+            uint32_t bl[NCLS], bj[NCLS];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) { bl[u] = ismem ? my_thr : 0u; bj[u] = 0xffffffffu; }
+            for (int u = 0; u < NCLS; ++u) { bl[u] = ismem ? my_thr : 0u; bj[u] = 0xffffffffu; }
             const uint32_t* msig = sg + m * SIG_WORDS;
             const int nNew4 = (nNew + 3) & ~3, nTot4 = (nTot + 3) & ~3;
             // four partners per step: their distances are read together, a wavefront-wide vote
@@ -307,7 +308,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                     addr += 4 * step;
                     bool any = false;
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) any = any || (l[u] < bl[u]);
+                    for (int u = 0; u < 4; ++u) any = any || (l[u] < bl[u % NCLS]);
                     if (__ballot(any) == 0ull) continue;
                     uint32_t hj[4], wv[4];
 #pragma unroll
@@ -318,9 +319,9 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         const int idj = __builtin_amdgcn_readlane(my_id, j0 + u);
-                        const bool ok = (l[u] < bl[u]) && idj != my_id && ((wv[u] >> (hj[u] & 31u)) & 1u) == 0u;
-                        bl[u] = ok ? l[u] : bl[u];
-                        bj[u] = ok ? (uint32_t)(j0 + u) : bj[u];
+                        const bool ok = (l[u] < bl[u % NCLS]) && idj != my_id && ((wv[u] >> (hj[u] & 31u)) & 1u) == 0u;
+                        bl[u % NCLS] = ok ? l[u] : bl[u % NCLS];
+                        bj[u % NCLS] = ok ? (uint32_t)(j0 + u) : bj[u % NCLS];
                     }
                 }
             };
@@ -337,7 +338,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             if (nTot4 > nNew4)
                 scan(nNew4, nTot4, isnew ? m * LDD + nNew4 : INF_CELL, isnew ? 1 : 0);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < NCLS; ++u) {
                 const int pid = __shfl(my_id, (int)(bj[u] & 63u)); // all lanes take part in the shuffle
                 if (bj[u] != 0xffffffffu) {
                     const uint32_t slot = below(hash32((uint32_t)pid), (uint32_t)C);
