@@ -52,6 +52,13 @@ template <int S16> struct WaveCfg {
 #ifndef KNNG_WAVE_OCC
 #define KNNG_WAVE_OCC 3
 #endif
+// 16-byte piece at t; VEC: the caller keeps t inside the row, so the load is unconditional
+template <bool VEC>
+__device__ __forceinline__ float4 load_piece_inside(const float* __restrict__ row, int t, int d)
+{
+    if (VEC) return *reinterpret_cast<const float4*>(row + t);
+    return load_piece<false>(row, t, d);
+}
 template <int METRIC, int S16, bool VEC>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(KNNG_WAVE_OCC, KNNG_WAVE_OCC)))
 k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
@@ -91,11 +98,12 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
     int4 rc = plan[v];
     int rid = load_slot(v);
     int cur = 0;
+    PointPlan P = make_point(rc);
     {
         const int m = member_of_slot(lane, s, rc);
         if (m >= 0) midbuf[m] = rid;
+        if (lane >= P.nTot && lane < NCOLS) midbuf[lane] = (int)v;
     }
-    PointPlan P = make_point(rc);
     wave_lds_sync();
 
     float4 buf[NL];
@@ -113,24 +121,31 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             sg_r1 = sp[1];
         }
     };
-    // slab pieces: lane -> (piece c4 = lane & 7, rows (lane >> 3) + 8 i).  Rows are clamped to the
-    // last member instead of predicated: a group of 8 rows is loaded whole or not at all.
+    // slab pieces: lane -> (piece c4 = lane & 7, rows (lane >> 3) + 8 i).  A group of 8 rows is
+    // loaded whole or not at all: the id slots past the last member hold the pivot's id (its
+    // centred row is zero and its cells are masked out of the distance block).  All ids are read
+    // from LDS before the first load is issued: one LDS round trip per slab, not one per group.
     constexpr int QP = DS / 4, RPW = 64 / QP;              // pieces per row, rows per load
     const int c4 = lane & (QP - 1), rsub = lane / QP;
     auto issue_slab = [&](const int* mid, int nTot, int64_t pivot_row, int k0) {
-        const int t = k0 + 4 * c4;
-        pv = load_piece<VEC>(pts + pivot_row * d, t, d);
+        int t = k0 + 4 * c4;
+        // VEC: pieces past the end of the row are loaded from its last piece and zeroed when
+        // they are stored to LDS (a zero fill before a predicated load would make the compiler
+        // wait for every load in flight)
+        if (VEC) t = t < d ? t : d - 4;
+        int rowid[NL];
+#pragma unroll
+        for (int i = 0; i < NL; ++i) rowid[i] = mid[rsub + RPW * i];
+        pv = load_piece_inside<VEC>(pts + pivot_row * d, t, d);
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            if (RPW * i < nTot) {                               // uniform
-                const int row = rsub + RPW * i < nTot ? rsub + RPW * i : nTot - 1;
-                buf[i] = load_piece<VEC>(pts + (int64_t)mid[row] * d, t, d);
-            }
+            if (RPW * i < nTot)                                 // uniform
+                buf[i] = load_piece_inside<VEC>(pts + (int64_t)rowid[i] * d, t, d);
         }
     };
 
-    issue_members(midbuf, P.nTot, v);
     issue_slab(midbuf, P.nTot, v, 0);
+    issue_members(midbuf, P.nTot, v);
     int4 rc_n = int4{0, 0, 0, 0};
     int rid_n = 0;
     if (v_nx >= 0) { rc_n = plan[v_nx]; rid_n = load_slot(v_nx); }
@@ -161,11 +176,13 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             // ---- A: registers -> LDS (rows up to the end of the last loaded group of 8)
             {
                 float* xdst = X + rsub * LD + 4 * c4;
+                const bool inb = !VEC || k0 + 4 * c4 < d;
 #pragma unroll
                 for (int i = 0; i < NL; ++i) {
                     if (RPW * i < nTot) {                       // uniform
                         float4 x = buf[i];
                         x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w;
+                        if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
                         *reinterpret_cast<float4*>(xdst + RPW * i * LD) = x;
                     }
                 }
@@ -173,6 +190,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             if (last && v_nx >= 0) {                            // next point's member ids
                 const int m = member_of_slot(lane, s, rc_n);
                 if (m >= 0) midbuf[(cur ^ 1) * NCOLS + m] = rid_n;
+                if (lane >= Pn.nTot && lane < NCOLS) midbuf[(cur ^ 1) * NCOLS + lane] = (int)v_nx;
             }
             wave_lds_sync();
             // ---- B: issue the loads of the next unit (one call site)
@@ -180,8 +198,10 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 const int* nmid = last ? midbuf + (cur ^ 1) * NCOLS : mid;
                 const int n_tot = last ? Pn.nTot : nTot;
                 const int64_t n_piv = last ? v_nx : v;
-                if (last) issue_members(nmid, n_tot, n_piv);
+                // the slab first: whatever the compiler makes the wavefront wait for before it
+                // reuses a prefetch register must not include the member gathers below
                 issue_slab(nmid, n_tot, n_piv, last ? 0 : k0 + DS);
+                if (last) issue_members(nmid, n_tot, n_piv);
                 if (last && v_nx2 >= 0) { rc_n = plan[v_nx2]; rid_n = load_slot(v_nx2); }
             }
             // ---- C: all Gram tiles of the point for this slab
