@@ -71,6 +71,10 @@ __device__ __forceinline__ float dist_group8(const float* __restrict__ a, const 
 constexpr int SIG_WORDS = 8;
 // orders one wavefront's own LDS accesses (they execute in order; this keeps the compiler from
 // moving them and makes returned data available) -- enough for wavefront-private LDS regions
+#ifndef KNNG_REV_MULT
+#define KNNG_REV_MULT 2          // reverse buckets per point and kind, in units of s
+#endif
+constexpr uint32_t EMPTY_REV = 0xffffffffu;            // an empty reverse bucket
 __device__ __forceinline__ void wave_lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 // The bit an id maps to changes with the iteration (salt), so a false positive does not
 // shadow the same candidate for good.
@@ -102,13 +106,17 @@ template <int METRIC>
 __global__ void __launch_bounds__(256)
 k_init(const float* __restrict__ pts, int64_t n, int d, int K, int C, u64 seed,
        const int32_t* __restrict__ init_ids, u64* __restrict__ G, u64* __restrict__ cand,
-       int32_t* __restrict__ cnt, float* __restrict__ worst)
+       int32_t* __restrict__ cnt, float* __restrict__ worst, uint32_t* __restrict__ rev, int B)
 {
     const int lane = lane_id();
     const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (v >= n) return;
     for (int j = lane; j < C; j += WAVE) cand[v * C + j] = EMPTY_KEY;
-    if (lane < 4) cnt[v * 4 + lane] = 0;
+    if (lane < 2) cnt[v * 2 + lane] = 0;
+    for (int j = lane; j < B; j += WAVE) {           // reverse buckets of the first iteration
+        rev[v * B + j] = EMPTY_REV;
+        rev[(n + v) * B + j] = EMPTY_REV;
+    }
 
     const bool active = lane < K;
     const uint32_t un = (uint32_t)n;
@@ -169,16 +177,26 @@ k_init(const float* __restrict__ pts, int64_t n, int d, int K, int C, u64 seed,
 // registers: up to s new-flagged entries (a cyclic window of the flagged ones from a random
 // start, so every flagged entry is equally likely) become the forward new sample and lose
 // their flag; up to s unflagged entries the forward old sample.  Each forward edge v->u also
-// puts v into u's reverse sample: an atomic counter hands out the first s slots, later
-// arrivals replace a random slot with probability s/(arrivals so far).
-// Lists: NEW[v] = [fwd 0..s) [rev s..2s), OLD likewise; cnt[v] = {fwd new, fwd old, rev new,
-// rev old}.  The row's signature for this iteration is rebuilt here as well.
+// enters v into u's reverse sample: u owns B buckets per kind, v falls into bucket
+// hash(v) mod B and the bucket keeps the arrival with the smallest random priority (one 32-bit
+// atomic min, nothing comes back to the wavefront).  A bucket thus holds a uniformly random one
+// of its arrivals, whatever order they came in; k_plan turns the buckets into the reverse list.
+// What is stored is hash32(v ^ salt(u)): the priority and, hash32 being a bijection, also v.
+// rev[parity][kind][point][bucket]: this launch fills parity iter&1 and resets the point's own
+// buckets of the other parity for the next iteration.
+// Lists: NEW[v] = [fwd 0..s) [rev s..2s), OLD likewise; cnt[v] = {fwd new, fwd old}.  The
+// row's signature for this iteration is rebuilt here as well.
 // ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t rev_salt(u64 seed, uint32_t iter)
+{
+    return hash32((uint32_t)seed ^ (uint32_t)(seed >> 32) * 0x85ebca6bu ^ (iter * 0x9e3779b9u + 0x68e31da4u));
+}
+
 __global__ void __launch_bounds__(256)
 k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
          u64* __restrict__ G, u64* __restrict__ cand, int32_t* __restrict__ newl, int32_t* __restrict__ oldl,
          int32_t* __restrict__ cnt, uint32_t* __restrict__ sig, float* __restrict__ worst,
-         u64* __restrict__ updates)
+         u64* __restrict__ updates, uint32_t* __restrict__ rev, int B)
 {
     __shared__ u64 rowbuf[4][WAVE];
     __shared__ uint32_t sigbuf[4][SIG_WORDS];
@@ -190,12 +208,20 @@ k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
     const uint32_t tag = 0x200u + 4u * iter;
     u64 accepted = 0;
 
+    const uint32_t saltp = rev_salt(seed, iter);
+    const uint32_t salts = hash32(saltp + 0x3c6ef372u);
+    uint32_t* rev_cur = rev + (int64_t)(iter & 1u) * 2 * n * B;          // [kind][point][bucket]
+    uint32_t* rev_nxt = rev + (int64_t)((iter & 1u) ^ 1u) * 2 * n * B;
+
     int64_t v = (int64_t)blockIdx.x * 4 + w;
     u64 lk_n = EMPTY_KEY, ck_n = EMPTY_KEY;
     if (v < n) {
         if (lane < K) lk_n = G[v * K + lane];
         if (lane < C) ck_n = cand[v * C + lane];
     }
+    // The first row is waited for here, so that inside the loop the compiler knows the working
+    // registers are settled and does not wait for the prefetch it has just issued.
+    __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
     for (; v < n; v += nwaves) {
         u64 row = lk_n;                              // lane < K: entry `lane` of the row
         const u64 ck = ck_n;
@@ -250,46 +276,36 @@ k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
         // ---- sample for the next join
         const bool active = lane < K;
         const bool isnew = active && (row & 1ull);
-        const bool isold = active && !(row & 1ull);
         const int id = key_id(row);
-        const u64 newmask = __ballot(isnew), oldmask = __ballot(isold);
+        const u64 newmask = __ballot(isnew), oldmask = __ballot(active && !isnew);
         const int cn = __popcll(newmask), co_ = __popcll(oldmask);
         const int64_t base = v * 2 * (int64_t)s;
         bool cleared = false;
-        if (isnew) {
-            int off = (int)below(rnd32(seed, tag, (uint32_t)v, 0u), (uint32_t)cn);
-            int p = __popcll(newmask & lt) - off;
-            if (p < 0) p += cn;
-            if (p < s) {
-                newl[base + p] = id;
-                row &= ~1ull;
-                cleared = true;
-                int pos = atomicAdd(&cnt[(int64_t)id * 4 + 2], 1);
-                if (pos < s) newl[(int64_t)id * 2 * s + s + pos] = (int32_t)v;
-                else {
-                    int r = (int)below(rnd32(seed, tag + 2u, (uint32_t)v, (uint32_t)lane), (uint32_t)pos + 1u);
-                    if (r < s) newl[(int64_t)id * 2 * s + s + r] = (int32_t)v;
-                }
+        {
+            // one code path for both kinds: an entry is either flagged or not
+            const int off_n = (int)below(rnd32(seed, tag, (uint32_t)v, 0u), (uint32_t)cn);
+            const int off_o = (int)below(rnd32(seed, tag + 1u, (uint32_t)v, 0u), (uint32_t)co_);
+            const int cm = isnew ? cn : co_;
+            int p = __popcll((isnew ? newmask : oldmask) & lt) - (isnew ? off_n : off_o);
+            if (p < 0) p += cm;
+            const bool sampled = active && p < s;
+            if (sampled) {
+                (isnew ? newl : oldl)[base + p] = id;
+                if (isnew) { row &= ~1ull; cleared = true; }
+                const uint32_t mix = saltp ^ ((uint32_t)id * 0x85ebca6bu);  // per target: independent draws
+                const uint32_t bucket = below(hash32((uint32_t)v * 0x9e3779b1u + (mix ^ salts)), (uint32_t)B);
+                atomicMin(&rev_cur[((isnew ? 0 : n) + (int64_t)id) * B + bucket], hash32((uint32_t)v ^ mix));
             }
-        }
-        if (isold) {
-            int off = (int)below(rnd32(seed, tag + 1u, (uint32_t)v, 0u), (uint32_t)co_);
-            int p = __popcll(oldmask & lt) - off;
-            if (p < 0) p += co_;
-            if (p < s) {
-                oldl[base + p] = id;
-                int pos = atomicAdd(&cnt[(int64_t)id * 4 + 3], 1);
-                if (pos < s) oldl[(int64_t)id * 2 * s + s + pos] = (int32_t)v;
-                else {
-                    int r = (int)below(rnd32(seed, tag + 3u, (uint32_t)v, (uint32_t)lane), (uint32_t)pos + 1u);
-                    if (r < s) oldl[(int64_t)id * 2 * s + s + r] = (int32_t)v;
-                }
-            }
+            // the point's own buckets of the other parity: empty for the next iteration
+            const int q = lane & 31;
+            if (4 * q < B)
+                *reinterpret_cast<uint4*>(rev_nxt + ((lane < 32 ? 0 : n) + v) * B + 4 * q) =
+                    uint4{EMPTY_REV, EMPTY_REV, EMPTY_REV, EMPTY_REV};
         }
         if (active && (changed || cleared)) G[v * K + lane] = row;
         if (lane == 0) {
-            cnt[v * 4 + 0] = cn < s ? cn : s;
-            cnt[v * 4 + 1] = co_ < s ? co_ : s;
+            cnt[v * 2 + 0] = cn < s ? cn : s;
+            cnt[v * 2 + 1] = co_ < s ? co_ : s;
         }
         // ---- signature of the row for this iteration: OR of one bit per entry, through LDS
         if (lane < SIG_WORDS) sigbuf[w][lane] = 0u;
@@ -311,43 +327,92 @@ k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
 }
 
 // ------------------------------------------------------------------------------------------
-// k_plan: after sampling, fix each point's four list lengths for the join (reverse counts
-// clamped to s), hand the atomic reverse counters back at zero, append the points that have
-// anything new around them to the active list, and count the vectors the join will gather.
-// ctr[1] += vectors, ctr[2] += active points.
+// k_plan: after sampling, turn every point's reverse buckets into its reverse lists (the
+// non-empty buckets in bucket order, decoded, at most s: a random subset, since bucket numbers
+// are hashes), fix the four list lengths for the join, append the points that have anything new
+// around them to the active list, and count the vectors the join will gather.
+// A block owns PLAN_CHUNK consecutive points: it takes its share of the active list with one
+// atomic.  ctr[1] += vectors, ctr[2] += active points.
+// A wavefront reads whole 16-byte pieces: LPL lanes per list, 64/LPL lists (both kinds of
+// 32/LPL points) per step.
 // ------------------------------------------------------------------------------------------
+constexpr int PLAN_CHUNK = 512;
 __global__ void __launch_bounds__(256)
-k_plan(int64_t n, int s, int32_t* __restrict__ cnt, int4* __restrict__ plan,
-       int32_t* __restrict__ active, u64* __restrict__ ctr)
+k_plan(int64_t n, int s, int B, u64 seed, uint32_t iter, const uint32_t* __restrict__ rev_cur,
+       const int2* __restrict__ cnt, int32_t* __restrict__ newl, int32_t* __restrict__ oldl,
+       int4* __restrict__ plan, int32_t* __restrict__ active, u64* __restrict__ ctr)
 {
-    __shared__ u64 part[4];
+    __shared__ unsigned char actf[PLAN_CHUNK];
+    __shared__ u64 wrows[4];
+    __shared__ int wcnt[4];
+    __shared__ u64 s_base;
+    const uint32_t saltp = rev_salt(seed, iter);
     const int lane = lane_id();
+    const int w = (int)(threadIdx.x >> 6);
+    const int q4 = B / 4;                            // 16-byte pieces per list (B % 4 == 0, B <= 128)
+    int LPL = 1;
+    while (LPL < q4) LPL <<= 1;                      // lanes per list, <= 32
+    const int pps = 32 / LPL;                        // points per wavefront step
+    const int g = lane / LPL, j = lane & (LPL - 1);
+    const int kind = g & 1;
+    const int64_t p0 = (int64_t)blockIdx.x * PLAN_CHUNK;
+    const int npts = (int)((n - p0) < PLAN_CHUNK ? (n - p0) : PLAN_CHUNK);
+    const u64 gm = ((1ull << LPL) - 1ull) << (g * LPL);
+    const u64 ltg = gm & lanemask_lt();
     u64 rows = 0;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    const int64_t nround = (n + stride - 1) / stride * stride;      // whole wavefronts stay in the loop
-    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nround; v += stride) {
-        bool act = false;
-        if (v < n) {
-            int4 c = reinterpret_cast<const int4*>(cnt)[v];
-            c.z = c.z < s ? c.z : s;
-            c.w = c.w < s ? c.w : s;
-            plan[v] = c;
-            if (c.z | c.w) reinterpret_cast<int2*>(cnt)[2 * v + 1] = int2{0, 0};
-            act = (c.x + c.z) > 0;
-            if (act) rows += (u64)(c.x + c.y + c.z + c.w);
-        }
-        const u64 m = __ballot(act);
-        if (m) {
-            unsigned long long base = 0;
-            if (lane == 0) base = atomicAdd(ctr + 2, (u64)__popcll(m));
-            base = bcast64(base, 0);
-            if (act) active[base + __popcll(m & lanemask_lt())] = (int32_t)v;
+    auto load_piece = [&](int base) {
+        const int pl = base + (g >> 1);
+        uint4 key = uint4{EMPTY_REV, EMPTY_REV, EMPTY_REV, EMPTY_REV};
+        if (pl < npts && j < q4)
+            key = *reinterpret_cast<const uint4*>(rev_cur + ((kind ? n : 0) + p0 + pl) * B + 4 * j);
+        return key;
+    };
+    uint4 key_n = load_piece(w * pps);
+    for (int base = w * pps; base < npts; base += 4 * pps) {
+        const int pl = base + (g >> 1);
+        const bool pin = pl < npts;
+        const int64_t p = p0 + pl;
+        const uint4 key = key_n;
+        key_n = load_piece(base + 4 * pps);          // in flight while this step is written out
+        const bool v0 = key.x != EMPTY_REV, v1 = key.y != EMPTY_REV, v2 = key.z != EMPTY_REV, v3 = key.w != EMPTY_REV;
+        const u64 b0 = __ballot(v0), b1 = __ballot(v1), b2 = __ballot(v2), b3 = __ballot(v3);
+        int r = __popcll(b0 & ltg) + __popcll(b1 & ltg) + __popcll(b2 & ltg) + __popcll(b3 & ltg);
+        const int total = __popcll(b0 & gm) + __popcll(b1 & gm) + __popcll(b2 & gm) + __popcll(b3 & gm);
+        int32_t* dst = (kind ? oldl : newl) + p * 2 * (int64_t)s + s;
+        const uint32_t mix = saltp ^ ((uint32_t)p * 0x85ebca6bu);
+        if (v0) { if (r < s) dst[r] = (int32_t)(unhash32(key.x) ^ mix); ++r; }
+        if (v1) { if (r < s) dst[r] = (int32_t)(unhash32(key.y) ^ mix); ++r; }
+        if (v2) { if (r < s) dst[r] = (int32_t)(unhash32(key.z) ^ mix); ++r; }
+        if (v3) { if (r < s) dst[r] = (int32_t)(unhash32(key.w) ^ mix); ++r; }
+        const int mine = total < s ? total : s;
+        const int other = __shfl(mine, lane ^ LPL);  // the same point's list of the other kind
+        if (pin && j == 0 && kind == 0) {
+            const int2 c = cnt[p];
+            plan[p] = int4{c.x, c.y, mine, other};
+            const bool act = (c.x + mine) > 0;
+            actf[pl] = act ? 1 : 0;
+            if (act) rows += (u64)(c.x + c.y + mine + other);
         }
     }
     for (int o = 32; o > 0; o >>= 1) rows += __shfl_xor(rows, o);
-    if (lane == 0) part[threadIdx.x >> 6] = rows;
     __syncthreads();
-    if (threadIdx.x == 0) atomicAdd(ctr + 1, part[0] + part[1] + part[2] + part[3]);
+    const int t = (int)threadIdx.x;
+    const bool a0 = t < npts && actf[t] != 0;
+    const bool a1 = t + 256 < npts && actf[t + 256] != 0;
+    const u64 m0 = __ballot(a0), m1 = __ballot(a1);
+    if (lane == 0) { wcnt[w] = __popcll(m0) + __popcll(m1); wrows[w] = rows; }
+    __syncthreads();
+    if (t == 0) {
+        const int tot = wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
+        s_base = tot ? atomicAdd(ctr + 2, (u64)tot) : 0ull;
+        const u64 rt = wrows[0] + wrows[1] + wrows[2] + wrows[3];
+        if (rt) atomicAdd(ctr + 1, rt);
+    }
+    __syncthreads();
+    u64 at = s_base;
+    for (int i = 0; i < w; ++i) at += (u64)wcnt[i];
+    if (a0) active[at + __popcll(m0 & lanemask_lt())] = (int32_t)(p0 + t);
+    if (a1) active[at + __popcll(m0) + __popcll(m1 & lanemask_lt())] = (int32_t)(p0 + t + 256);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -773,9 +838,9 @@ k_finalize(const float* __restrict__ pts, int64_t n, int d, int K, int k,
 // host side
 // ------------------------------------------------------------------------------------------
 struct BuildPlan {
-    int K, C, s, S16, max_iters;
+    int K, C, s, B, S16, max_iters;
     float rho, delta;
-    uint64_t off_G, off_cand, off_new, off_old, off_cnt, off_plan, off_active, off_worst, off_sig, off_ctr, total;
+    uint64_t off_G, off_cand, off_new, off_old, off_rev, off_cnt, off_plan, off_active, off_worst, off_sig, off_ctr, total;
 };
 
 static bool make_plan(int64_t n, int32_t d, int32_t k, const knng_params_t* p, BuildPlan* bp)
@@ -794,6 +859,7 @@ static bool make_plan(int64_t n, int32_t d, int32_t k, const knng_params_t* p, B
     if (s < 1) s = 1;
     if (s > K) s = K;
     bp->K = K; bp->C = C; bp->s = s; bp->rho = rho; bp->delta = delta; bp->max_iters = max_iters;
+    bp->B = (KNNG_REV_MULT * s + 3) & ~3; if (bp->B > 128) bp->B = 128;              // reverse buckets per point and kind (>= 2s, % 4 == 0)
     bp->S16 = (2 * s <= 16) ? 1 : (2 * s <= 32) ? 2 : (2 * s <= 64) ? 4 : 8;
     uint64_t off = 0;
     auto take = [&](uint64_t bytes) { uint64_t o = off; off = (off + bytes + 255) & ~255ull; return o; };
@@ -801,7 +867,8 @@ static bool make_plan(int64_t n, int32_t d, int32_t k, const knng_params_t* p, B
     bp->off_cand = take((uint64_t)n * C * 8);
     bp->off_new = take((uint64_t)n * 2 * s * 4);
     bp->off_old = take((uint64_t)n * 2 * s * 4);
-    bp->off_cnt = take((uint64_t)n * 16);
+    bp->off_rev = take((uint64_t)n * 4 * bp->B * 4);   // [parity][kind][point][bucket]
+    bp->off_cnt = take((uint64_t)n * 8);
     bp->off_plan = take((uint64_t)n * 16);
     bp->off_active = take((uint64_t)n * 4);
     bp->off_worst = take((uint64_t)n * 4);
@@ -920,6 +987,7 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
     int32_t* newl = reinterpret_cast<int32_t*>(ws + bp.off_new);
     int32_t* oldl = reinterpret_cast<int32_t*>(ws + bp.off_old);
     int32_t* cnt = reinterpret_cast<int32_t*>(ws + bp.off_cnt);
+    uint32_t* rev = reinterpret_cast<uint32_t*>(ws + bp.off_rev);
     int4* plan = reinterpret_cast<int4*>(ws + bp.off_plan);
     int32_t* active = reinterpret_cast<int32_t*>(ws + bp.off_active);
     float* worst = reinterpret_cast<float*>(ws + bp.off_worst);
@@ -958,10 +1026,10 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
     HIPCHK(hipMemsetAsync(ctr, 0, 256, st));
     if (metric == 0)
         hipLaunchKernelGGL(k_init<0>, dim3(row_blocks), dim3(256), 0, st, points_dev, n, d, bp.K, bp.C,
-                           params->seed, params->init_ids_dev, G, cand, cnt, worst);
+                           params->seed, params->init_ids_dev, G, cand, cnt, worst, rev, bp.B);
     else
         hipLaunchKernelGGL(k_init<1>, dim3(row_blocks), dim3(256), 0, st, points_dev, n, d, bp.K, bp.C,
-                           params->seed, params->init_ids_dev, G, cand, cnt, worst);
+                           params->seed, params->init_ids_dev, G, cand, cnt, worst, rev, bp.B);
     HIPCHK(hipGetLastError());
     if (stats) HIPCHK(hipEventRecord(ev[1], st));
 
@@ -973,7 +1041,7 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
         if (it == 0 && !more) break;
         const bool rec = stats && it < max_rec;
         hipLaunchKernelGGL(k_update, dim3(upd_blocks), dim3(256), 0, st, n, bp.K, bp.C, bp.s, params->seed,
-                           (uint32_t)it, more ? 1 : 0, G, cand, newl, oldl, cnt, sig, worst, ctr);
+                           (uint32_t)it, more ? 1 : 0, G, cand, newl, oldl, cnt, sig, worst, ctr, rev, bp.B);
         HIPCHK(hipGetLastError());
         if (rec) HIPCHK(hipEventRecord(ev[2 + 4 * it], st));
         if (stats && !more) HIPCHK(hipEventRecord(ev[n_ev - 2], st));
@@ -988,7 +1056,9 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
             if ((double)host_ctr[0] < stop_below) { converged = 1; break; }
         }
         if (!more) break;
-        hipLaunchKernelGGL(k_plan, dim3(1024), dim3(256), 0, st, n, bp.s, cnt, plan, active, ctr);
+        hipLaunchKernelGGL(k_plan, dim3((unsigned)((n + PLAN_CHUNK - 1) / PLAN_CHUNK)), dim3(256), 0, st, n, bp.s, bp.B,
+                           params->seed, (uint32_t)it, rev + (int64_t)(it & 1) * 2 * n * bp.B,
+                           reinterpret_cast<const int2*>(cnt), newl, oldl, plan, active, ctr);
         HIPCHK(hipGetLastError());
         if (rec) HIPCHK(hipEventRecord(ev[3 + 4 * it], st));
         {

@@ -33,6 +33,14 @@ __device__ __forceinline__ uint32_t hash32(uint32_t x)
     x ^= x >> 16;
     return x;
 }
+// hash32 is a bijection of the 32-bit integers; this is its inverse
+__device__ __forceinline__ uint32_t unhash32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x43021123u;
+    x ^= (x >> 15) ^ (x >> 30); x *= 0x1d69e2a5u;
+    x ^= x >> 16;
+    return x;
+}
 __device__ __forceinline__ uint32_t rnd32(u64 seed, uint32_t tag, uint32_t row, uint32_t slot)
 {
     // (seed, tag) and usually row are uniform across a wavefront, so the first two rounds run on

@@ -45,7 +45,7 @@ template <int S16> struct WaveCfg {
     static constexpr int NL = NCOLS * (DS / 4) / 64;  // 16-byte pieces per lane and slab
     static constexpr int NTILES = (3 * S16 * S16 + 3 * S16) / 2;  // upper triangle rows<S16 + extra diagonals
     static constexpr int XBYTES = NCOLS * LD * 4 > MROWS * LDD * 4 ? NCOLS * LD * 4 : MROWS * LDD * 4;
-    // X/D | mid[2][NCOLS] | nrm[NCOLS] | sg[NCOLS+1][8]
+    // X/D | mid[2][NCOLS] | nrm[NCOLS] | sg[8][NCOLS+1]
     static constexpr int WBYTES = ((XBYTES + NCOLS * (8 + 4) + (NCOLS + 1) * 4 * SIG_WORDS) + 255) & ~255;
 };
 
@@ -77,7 +77,8 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
     float* X = reinterpret_cast<float*>(wbase);                 // [NCOLS][LD], later D [MROWS][LDD]
     int* midbuf = reinterpret_cast<int*>(wbase + Cfg::XBYTES);  // [2][NCOLS] member ids, double-buffered
     float* nrm = reinterpret_cast<float*>(midbuf + 2 * NCOLS);  // [NCOLS] |x_m - x_v|^2
-    uint32_t* sg = reinterpret_cast<uint32_t*>(nrm + NCOLS);    // [NCOLS + 1][SIG_WORDS], slot nTot = pivot
+    uint32_t* sg = reinterpret_cast<uint32_t*>(nrm + NCOLS);    // [SIG_WORDS][NCOLS + 1], column nTot = pivot
+    constexpr int SGLD = NCOLS + 1;
 
     const int r16 = lane & 15, kq = lane >> 4;
     const int64_t nact = (int64_t)*nactive_ptr;
@@ -150,6 +151,22 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
     int rid_n = 0;
     if (v_nx >= 0) { rc_n = plan[v_nx]; rid_n = load_slot(v_nx); }
 
+    // offers of the previous point, not yet sent (pend_pid < 0: none)
+    int pend_id = 0, pend_pid[OFFERS_PER_MEMBER];
+    uint32_t pend_l[OFFERS_PER_MEMBER];
+#pragma unroll
+    for (int u = 0; u < OFFERS_PER_MEMBER; ++u) { pend_pid[u] = -1; pend_l[u] = 0u; }
+    auto send_offers = [&]() {
+#pragma unroll
+        for (int u = 0; u < OFFERS_PER_MEMBER; ++u) {
+            if (pend_pid[u] >= 0) {
+                const uint32_t slot = below(hash32((uint32_t)pend_pid[u]), (uint32_t)C);
+                atomicMin(&cand[(int64_t)pend_id * C + slot], pack_key(__uint_as_float(pend_l[u]), pend_pid[u], 1));
+            }
+            pend_pid[u] = -1;
+        }
+    };
+
     for (;;) {
         const int* mid = midbuf + cur * NCOLS;
         const int nNew = P.nNew, nTot = P.nTot, nfn = P.nfn, nfo = P.nfo;
@@ -161,32 +178,39 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
         const uint32_t my_thr = __float_as_uint(thr_r);
         const uint32_t my_hb = sig_bit(my_id, iter);
         if (lane <= nTot) {                                     // slot nTot <= NCOLS exists
-            reinterpret_cast<uint4*>(sg)[2 * lane] = sg_r0;
-            reinterpret_cast<uint4*>(sg)[2 * lane + 1] = sg_r1;
+            // word-major: lanes that read one word of their own signatures hit different banks
+            sg[0 * SGLD + lane] = sg_r0.x; sg[1 * SGLD + lane] = sg_r0.y;
+            sg[2 * SGLD + lane] = sg_r0.z; sg[3 * SGLD + lane] = sg_r0.w;
+            sg[4 * SGLD + lane] = sg_r1.x; sg[5 * SGLD + lane] = sg_r1.y;
+            sg[6 * SGLD + lane] = sg_r1.z; sg[7 * SGLD + lane] = sg_r1.w;
         }
 
         floatx4 acc[NTILES];
 #pragma unroll
         for (int q = 0; q < NTILES; ++q) acc[q] = floatx4{0, 0, 0, 0};
 
+        // ---- A: registers -> LDS (rows up to the end of the last loaded group of 8)
+        auto store_slab = [&](int k0) {
+            float* xdst = X + rsub * LD + 4 * c4;
+            const bool inb = !VEC || k0 + 4 * c4 < d;
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                if (RPW * i < nTot) {                           // uniform
+                    float4 x = buf[i];
+                    x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w;
+                    if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
+                    *reinterpret_cast<float4*>(xdst + RPW * i * LD) = x;
+                }
+            }
+        };
+        store_slab(0);
+        // everything prefetched for this point has now been used: the previous point's offers go
+        // out before the next loads are issued
+        send_offers();
         for (int k0 = 0; k0 < d; k0 += DS) {
             const bool last = k0 + DS >= d;
             const int len = (d - k0) < DS ? (d - k0) : DS;
             const int len16 = (len + 15) & ~15;
-            // ---- A: registers -> LDS (rows up to the end of the last loaded group of 8)
-            {
-                float* xdst = X + rsub * LD + 4 * c4;
-                const bool inb = !VEC || k0 + 4 * c4 < d;
-#pragma unroll
-                for (int i = 0; i < NL; ++i) {
-                    if (RPW * i < nTot) {                       // uniform
-                        float4 x = buf[i];
-                        x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w;
-                        if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
-                        *reinterpret_cast<float4*>(xdst + RPW * i * LD) = x;
-                    }
-                }
-            }
             if (last && v_nx >= 0) {                            // next point's member ids
                 const int m = member_of_slot(lane, s, rc_n);
                 if (m >= 0) midbuf[(cur ^ 1) * NCOLS + m] = rid_n;
@@ -234,6 +258,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 }
             }
             wave_lds_sync();
+            if (!last) store_slab(k0 + DS);
         }
 
         // ---- member norms from the diagonal tiles: lane (r16, kq) holds rows 4kq..4kq+3 of
@@ -294,7 +319,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 float l = nrm[m];
                 if (METRIC == 1) l *= 0.5f;
                 l = nonneg(l);
-                const uint32_t vw = sg[nTot * SIG_WORDS + (my_hb >> 5)];
+                const uint32_t vw = sg[(my_hb >> 5) * SGLD + nTot];
                 if (__float_as_uint(l) < pthr && !((vw >> (my_hb & 31u)) & 1u)) {
                     const uint32_t slot = below(hash32((uint32_t)my_id), (uint32_t)C);
                     atomicMin(&cand[v * C + slot], pack_key(l, my_id, 1));
@@ -315,7 +340,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             uint32_t bl[NCLS], bj[NCLS];
 #pragma unroll
             for (int u = 0; u < NCLS; ++u) { bl[u] = ismem ? my_thr : 0u; bj[u] = 0xffffffffu; }
-            const uint32_t* msig = sg + m * SIG_WORDS;
+            const uint32_t* msig = sg + m;
             const int nNew4 = (nNew + 3) & ~3, nTot4 = (nTot + 3) & ~3;
             // four partners per step: their distances are read together, a wavefront-wide vote
             // skips groups in which nobody improves, then the four signature words are read
@@ -334,7 +359,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         hj[u] = (uint32_t)__builtin_amdgcn_readlane((int)my_hb, j0 + u);
-                        wv[u] = msig[hj[u] >> 5];
+                        wv[u] = msig[(hj[u] >> 5) * SGLD];
                     }
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
@@ -357,14 +382,16 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             // OLD partners: NEW members only
             if (nTot4 > nNew4)
                 scan(nNew4, nTot4, isnew ? m * LDD + nNew4 : INF_CELL, isnew ? 1 : 0);
+            // the offers are kept in registers and sent while the next point's first slab is
+            // multiplied: atomics and loads share one in-flight counter, so offers sent here
+            // would make the next point's first use of its prefetched data wait for them
 #pragma unroll
             for (int u = 0; u < NCLS; ++u) {
                 const int pid = __shfl(my_id, (int)(bj[u] & 63u)); // all lanes take part in the shuffle
-                if (bj[u] != 0xffffffffu) {
-                    const uint32_t slot = below(hash32((uint32_t)pid), (uint32_t)C);
-                    atomicMin(&cand[(int64_t)my_id * C + slot], pack_key(__uint_as_float(bl[u]), pid, 1));
-                }
+                pend_pid[u] = bj[u] != 0xffffffffu ? pid : -1;
+                pend_l[u] = bl[u];
             }
+            pend_id = my_id;
         }
         // ---- advance
         if (v_nx < 0) break;
@@ -376,6 +403,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
         P = Pn;
         cur ^= 1;
     }
+    send_offers();
 }
 
 }  // namespace knng

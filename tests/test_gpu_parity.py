@@ -218,6 +218,21 @@ def test_build_candidate_capacity_and_heavy_contention():
     _check_build(x, w.k, w.metric, ids, dists, exact, min_recall=0.9)
 
 
+def test_build_is_reproducible_run_to_run():
+    # every cross-point write of the build is an atomic min (candidate slots, reverse buckets):
+    # the result does not depend on the order the wavefronts ran in
+    for idx, n, kb, rho in ((0, 20_000, 32, 0.5), (2, 9_000, 24, 1.0)):
+        x, w = workloads.make(idx, n=n)
+        xg = _gpu(x)
+        k = min(w.k, kb)
+        a_i, a_d, a_st = knng.knng_build_knn_graph(xg, k, w.metric, k_build=kb, rho=rho, seed=11)
+        b_i, b_d, b_st = knng.knng_build_knn_graph(xg, k, w.metric, k_build=kb, rho=rho, seed=11)
+        assert torch.equal(a_i, b_i) and torch.equal(a_d, b_d)
+        assert a_st["updates"] == b_st["updates"]
+        c_i, _, _ = knng.knng_build_knn_graph(xg, k, w.metric, k_build=kb, rho=rho, seed=12)
+        assert not torch.equal(a_i, c_i)              # the seed does matter
+
+
 def test_build_small_distances_keep_their_precision():
     # tight unit-norm clusters: true cosine distances around 1e-5 (paper Sec. 5.3.2: a library
     # that mishandles such small distances collapses)
