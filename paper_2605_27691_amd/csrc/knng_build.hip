@@ -238,25 +238,29 @@ k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
             const u64 lo = key_order(row);
             const u64 co = key_order(ck);
             const u64 last = bcast64(lo, K - 1);
-            bool valid = ck != EMPTY_KEY && co < last;
-            const int cid = key_id(ck), lid = key_id(row);
-            if (__ballot(valid) != 0ull) {
-                for (int i = 0; i < K; ++i) {
-                    int li = (int)bcast32((uint32_t)lid, i);
-                    if (li == cid) valid = false;
-                }
+            // No test against the row's ids: the join only offers ids that fail the row's
+            // signature, which holds every id of the row (no false negatives), and an id always
+            // lands in the same slot, so the candidates are distinct from the row and each other.
+            const bool valid = ck != EMPTY_KEY && co < last;
+            {
                 const u64 vm = __ballot(valid);
                 if (vm != 0ull) {
-                    // ranks in the union of the row and the accepted candidates
+                    // ranks in the union of the row and the accepted candidates: one pass over
+                    // the candidates; candidate j learns how many row entries precede it from
+                    // the vote of the row's lanes
+                    const u64 rowmask = K >= 64 ? ~0ull : ((1ull << K) - 1ull);
                     int rl = lane;                   // the row is ascending already
-                    int rc = 0;
+                    int rc = 0, rrow = 0;
                     for (u64 m = vm; m; m &= m - 1) {
-                        int j = __ffsll((long long)m) - 1;
-                        u64 cj = bcast64(co, j);
-                        rl += (cj < lo) ? 1 : 0;
+                        const int j = __ffsll((long long)m) - 1;
+                        const u64 cj = bcast64(co, j);
+                        const bool before = cj < lo;
+                        rl += before ? 1 : 0;
                         rc += (cj < co) ? 1 : 0;
+                        const int nrow = K - __popcll(__ballot(before) & rowmask);
+                        rrow = lane == j ? nrow : rrow;
                     }
-                    for (int i = 0; i < K; ++i) rc += (bcast64(lo, i) < co) ? 1 : 0;
+                    rc += rrow;
                     const bool in = valid && rc < K;
                     if (lane < K && rl < K) rowbuf[w][rl] = row;
                     if (in) rowbuf[w][rc] = ck | 1ull;
