@@ -787,52 +787,61 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
 }
 
 // ------------------------------------------------------------------------------------------
-// k_finalize: one wavefront per point, 4 points per workgroup.  The K neighbour vectors are
-// staged slab by slab in LDS (coalesced), then lane i walks neighbour i's slab in index order
-// with the fp64 recipe, so the value written equals a sequential fp64 evaluation bit for bit.
-// Rows are then ranked by (distance, id) and the first k written as ids / distances.
+// k_finalize: lane i of a group of Kp = pow2 >= K lanes owns neighbour i of one point, 64/Kp
+// points per wavefront.  The lane walks its neighbour's vector and the point's own (the same
+// address across the group: one fetch) in index order with the fp64 recipe, so the value
+// written equals a sequential fp64 evaluation bit for bit.  A lane's 16-byte loads run along
+// one row, the next ones hit the lines the first brought in.  Rows are then ranked by
+// (distance, id) and the first k written as ids / distances.
 // ------------------------------------------------------------------------------------------
-constexpr int FIN_SL = 32;                        // slab length (floats)
-constexpr int FIN_LD = FIN_SL + 1;                // odd stride: lanes on distinct banks
-
-template <int METRIC>
+template <int METRIC, bool VEC>
 __global__ void __launch_bounds__(256)
-k_finalize(const float* __restrict__ pts, int64_t n, int d, int K, int k,
+k_finalize(const float* __restrict__ pts, int64_t n, int d, int K, int Kp, int k,
            const u64* __restrict__ G, int32_t* __restrict__ ids_out, float* __restrict__ dists_out)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int lane = lane_id(), w = threadIdx.x >> 6;
-    float* X = reinterpret_cast<float*>(smem) + w * (K + 1) * FIN_LD;   // [K+1][FIN_LD], row K = x_v
-    int64_t v = (int64_t)blockIdx.x * 4 + w;
-    const bool live = v < n;
-    if (!live) v = n - 1;                         // keep every wavefront in the barriers
-    const u64 key = lane < K ? G[v * K + lane] : EMPTY_KEY;
-    const int id = lane < K ? key_id(key) : (int)v;
+    const int sub = lane / Kp, i = lane & (Kp - 1);
+    const int64_t v = ((int64_t)blockIdx.x * 4 + w) * (WAVE / Kp) + sub;
+    const bool live = v < n && i < K;
+    const int64_t vv = v < n ? v : n - 1;
+    const u64 key = live ? G[vv * K + i] : EMPTY_KEY;
+    const int id = live ? key_id(key) : (int)vv;
+    const float* __restrict__ a = pts + vv * d;
+    const float* __restrict__ b = pts + (int64_t)id * d;
     double acc = 0.0;
-    for (int k0 = 0; k0 < d; k0 += FIN_SL) {
-        const int len = (d - k0) < FIN_SL ? (d - k0) : FIN_SL;
-        __syncthreads();
-        // 32 consecutive lanes read one row's 128-byte slab
-        for (int base = 0; base < (K + 1) * FIN_SL; base += WAVE) {   // uniform trip count
-            const int idx = base + lane;
-            const bool ok = idx < (K + 1) * FIN_SL;
-            const int row = ok ? idx / FIN_SL : 0, t = idx - row * FIN_SL;
-            const int src = __shfl(id, row < K ? row : 0);
-            const int rid = row < K ? src : (int)v;
-            if (ok && t < len) X[row * FIN_LD + t] = pts[(int64_t)rid * d + k0 + t];
+    if (VEC) {
+        int t = 0;
+        for (; t + 16 <= d; t += 16) {
+            float4 av[4], bv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                av[q] = *reinterpret_cast<const float4*>(a + t + 4 * q);
+                bv[q] = *reinterpret_cast<const float4*>(b + t + 4 * q);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                acc = exact_step<METRIC>(acc, av[q].x, bv[q].x);
+                acc = exact_step<METRIC>(acc, av[q].y, bv[q].y);
+                acc = exact_step<METRIC>(acc, av[q].z, bv[q].z);
+                acc = exact_step<METRIC>(acc, av[q].w, bv[q].w);
+            }
         }
-        __syncthreads();
-        if (lane < K) {
-            const float* xr = X + lane * FIN_LD;
-            const float* xp = X + K * FIN_LD;
-            for (int t = 0; t < len; ++t) acc = exact_step<METRIC>(acc, xp[t], xr[t]);
+        for (; t < d; t += 4) {
+            const float4 av = *reinterpret_cast<const float4*>(a + t);
+            const float4 bv = *reinterpret_cast<const float4*>(b + t);
+            acc = exact_step<METRIC>(acc, av.x, bv.x);
+            acc = exact_step<METRIC>(acc, av.y, bv.y);
+            acc = exact_step<METRIC>(acc, av.z, bv.z);
+            acc = exact_step<METRIC>(acc, av.w, bv.w);
         }
+    } else {
+        for (int t = 0; t < d; ++t) acc = exact_step<METRIC>(acc, a[t], b[t]);
     }
     const float dist = exact_finish<METRIC>(acc);
-    const u64 fk = lane < K ? pack_key(dist, id, 0) : EMPTY_KEY;
+    const u64 fk = live ? pack_key(dist, id, 0) : EMPTY_KEY;
     int rank = 0;
-    for (int j = 0; j < K; ++j) rank += (bcast64(fk, j) < fk) ? 1 : 0;
-    if (live && lane < K && rank < k) {
+    for (int j = 0; j < K; ++j) rank += ((u64)__shfl((unsigned long long)fk, sub * Kp + j) < fk) ? 1 : 0;
+    if (live && rank < k) {
         ids_out[v * k + rank] = id;
         dists_out[v * k + rank] = dist;
     }
@@ -1075,13 +1084,15 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
         iters = it + 1;
     }
     {
-        const int lds = 4 * (bp.K + 1) * FIN_LD * 4;
-        if (metric == 0)
-            hipLaunchKernelGGL(k_finalize<0>, dim3(row_blocks), dim3(256), lds, st, points_dev, n, d, bp.K, k,
-                               G, ids_out_dev, dists_out_dev);
-        else
-            hipLaunchKernelGGL(k_finalize<1>, dim3(row_blocks), dim3(256), lds, st, points_dev, n, d, bp.K, k,
-                               G, ids_out_dev, dists_out_dev);
+        int Kp = 1;
+        while (Kp < bp.K) Kp <<= 1;
+        const int64_t per_block = 4 * (WAVE / Kp);
+        const dim3 grid((unsigned)((n + per_block - 1) / per_block)), block(256);
+#define KNNG_FIN(M, V) hipLaunchKernelGGL((k_finalize<M, V>), grid, block, 0, st, points_dev, n, d, bp.K, Kp, k, \
+                                          G, ids_out_dev, dists_out_dev)
+        if (metric == 0) { if (vec) KNNG_FIN(0, true); else KNNG_FIN(0, false); }
+        else { if (vec) KNNG_FIN(1, true); else KNNG_FIN(1, false); }
+#undef KNNG_FIN
         HIPCHK(hipGetLastError());
     }
     if (stats) HIPCHK(hipEventRecord(ev[n_ev - 1], st));
