@@ -955,8 +955,6 @@ static hipError_t launch_join(hipStream_t st, bool vec, int S16, const JoinArgs&
 #define KNNG_JOIN_CASE(S, DSV)                                                      \
     return vec ? launch_join_k<METRIC, S, DSV, true>(st, a) : launch_join_k<METRIC, S, DSV, false>(st, a)
     switch (S16) {
-    case 1: KNNG_JOIN_CASE(1, KNNG_JOIN_DS);
-    case 2: KNNG_JOIN_CASE(2, KNNG_JOIN_DS);
     case 4: KNNG_JOIN_CASE(4, 64);
     default: KNNG_JOIN_CASE(8, 32);
     }

@@ -151,21 +151,29 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
     int rid_n = 0;
     if (v_nx >= 0) { rc_n = plan[v_nx]; rid_n = load_slot(v_nx); }
 
-    // offers of the previous point, not yet sent (pend_pid < 0: none)
-    int pend_id = 0, pend_pid[OFFERS_PER_MEMBER];
+    // Offers of the previous point, sent one point late: right after the last Gram pass, so
+    // that their round trip to memory runs under the norm / distance-block / scan work, which
+    // never waits for memory.  (Sent right after the scan they would be waited for at the very
+    // next use of prefetched data: loads and atomics share one in-order counter.)
+    // pend_id: the previous point's member id per lane; pend_j: partner lane per class, 0xff none.
+    int pend_id = 0;
+    uint32_t pend_j = 0xffffffffu;
     uint32_t pend_l[OFFERS_PER_MEMBER];
 #pragma unroll
-    for (int u = 0; u < OFFERS_PER_MEMBER; ++u) { pend_pid[u] = -1; pend_l[u] = 0u; }
+    for (int u = 0; u < OFFERS_PER_MEMBER; ++u) pend_l[u] = 0u;
     auto send_offers = [&]() {
 #pragma unroll
         for (int u = 0; u < OFFERS_PER_MEMBER; ++u) {
-            if (pend_pid[u] >= 0) {
-                const uint32_t slot = below(hash32((uint32_t)pend_pid[u]), (uint32_t)C);
-                atomicMin(&cand[(int64_t)pend_id * C + slot], pack_key(__uint_as_float(pend_l[u]), pend_pid[u], 1));
+            const uint32_t j = (pend_j >> (8 * u)) & 0xffu;
+            const int pid = __shfl(pend_id, (int)(j & 63u));   // all lanes take part in the shuffle
+            if (j != 0xffu) {
+                const uint32_t slot = below(hash32((uint32_t)pid), (uint32_t)C);
+                atomicMin(&cand[(int64_t)pend_id * C + slot], pack_key(__uint_as_float(pend_l[u]), pid, 1));
             }
-            pend_pid[u] = -1;
         }
+        pend_j = 0xffffffffu;
     };
+    static_assert(OFFERS_PER_MEMBER <= 4, "pend_j packs one byte per class");
 
     for (;;) {
         const int* mid = midbuf + cur * NCOLS;
@@ -204,9 +212,6 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             }
         };
         store_slab(0);
-        // everything prefetched for this point has now been used: the previous point's offers go
-        // out before the next loads are issued
-        send_offers();
         for (int k0 = 0; k0 < d; k0 += DS) {
             const bool last = k0 + DS >= d;
             const int len = (d - k0) < DS ? (d - k0) : DS;
@@ -259,6 +264,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             }
             wave_lds_sync();
             if (!last) store_slab(k0 + DS);
+            else send_offers();                                 // the previous point's
         }
 
         // ---- member norms from the diagonal tiles: lane (r16, kq) holds rows 4kq..4kq+3 of
@@ -363,8 +369,10 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                     }
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
+                        // bitwise, not short-circuit: no branches around the signature words
                         const int idj = __builtin_amdgcn_readlane(my_id, j0 + u);
-                        const bool ok = (l[u] < bl[u % NCLS]) && idj != my_id && ((wv[u] >> (hj[u] & 31u)) & 1u) == 0u;
+                        const uint32_t known = __builtin_amdgcn_ubfe(wv[u], hj[u] & 31u, 1u);
+                        const bool ok = (l[u] < bl[u % NCLS]) & (idj != my_id) & (known == 0u);
                         bl[u % NCLS] = ok ? l[u] : bl[u % NCLS];
                         bj[u % NCLS] = ok ? (uint32_t)(j0 + u) : bj[u % NCLS];
                     }
@@ -382,16 +390,15 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             // OLD partners: NEW members only
             if (nTot4 > nNew4)
                 scan(nNew4, nTot4, isnew ? m * LDD + nNew4 : INF_CELL, isnew ? 1 : 0);
-            // the offers are kept in registers and sent while the next point's first slab is
-            // multiplied: atomics and loads share one in-flight counter, so offers sent here
-            // would make the next point's first use of its prefetched data wait for them
+            pend_id = my_id;
+            pend_j = 0u;
 #pragma unroll
             for (int u = 0; u < NCLS; ++u) {
-                const int pid = __shfl(my_id, (int)(bj[u] & 63u)); // all lanes take part in the shuffle
-                pend_pid[u] = bj[u] != 0xffffffffu ? pid : -1;
                 pend_l[u] = bl[u];
+                pend_j |= (bj[u] & 0xffu) << (8 * u);
             }
-            pend_id = my_id;
+#pragma unroll
+            for (int u = NCLS; u < 4; ++u) pend_j |= 0xffu << (8 * u);
         }
         // ---- advance
         if (v_nx < 0) break;
