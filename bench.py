@@ -31,8 +31,8 @@ SIG_BYTES = 32          # row signature read per gathered member
 # HBM-side bytes per join launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each
 # scaled by what a plain 1 GiB device copy reads: 2.0 and 1.0 KiB per count), averaged over the same
 # launch mix as the timed region.  Only measured for the default workload and parameters
-# (profiles/k_join_config1_1m_d128_hbm_traffic.txt: 18.32 GB fetched + 1.77 GB written).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("u8gmm1024_1m_d128_l2", 32, 0.5): 20.09e9}
+# (profiles/k_join_config1_1m_d128_hbm_traffic.txt: 18.47 GB fetched + 1.73 GB written).
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("u8gmm1024_1m_d128_l2", 32, 0.5): 20.20e9}
 
 
 def parse():
@@ -47,7 +47,7 @@ def parse():
     ap.add_argument("--delta", type=float, default=0.0)
     ap.add_argument("--recall-rows", type=int, default=20000)
     ap.add_argument("--oracle-rows", type=int, default=128)
-    ap.add_argument("--cpu-n", type=int, default=60000, help="points of the CPU-baseline sample (0 = skip)")
+    ap.add_argument("--cpu-n", type=int, default=250000, help="points of the CPU-baseline sample (0 = skip)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (counter calibration under rocprofv3 --pmc)")
     return ap.parse_args()

@@ -791,7 +791,7 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
 // points per wavefront.  The lane walks its neighbour's vector and the point's own (the same
 // address across the group: one fetch) in index order with the fp64 recipe, so the value
 // written equals a sequential fp64 evaluation bit for bit.  A lane's 16-byte loads run along
-// one row, the next ones hit the lines the first brought in.  Rows are then ranked by
+// one row and rely on the caches for the rest of each line.  Rows are then ranked by
 // (distance, id) and the first k written as ids / distances.
 // ------------------------------------------------------------------------------------------
 template <int METRIC, bool VEC>
