@@ -92,12 +92,28 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- what a plain device copy reaches on this machine (the practical HBM ceiling, same process)
+    cp_src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()      # 1 GiB
+    cp_dst = torch.empty_like(cp_src)
+    cp_dst.copy_(cp_src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        cp_dst.copy_(cp_src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * cp_src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del cp_src, cp_dst
+
     # ---- roofline of the dominant kernel (local join), over the timed region
     join_ms = sum(sum(s["join_ms"]) for s in stats)
     launches = sum(len(s["join_ms"]) for s in stats)
     rows = sum(sum(s["join_rows"]) for s in stats)
     alg_bytes = rows * (4 * d + 4 + 4 + SIG_BYTES) + launches * n * 16
     achieved = alg_bytes / (join_ms * 1e-3) / 1e9 if join_ms > 0 else 0.0
+    pairs = sum(s["pairs"] for s in stats)                    # pairs the joins had to evaluate
+    offers = sum(s["offers"] for s in stats)                  # atomic mins sent to candidate slots
+    needed_tflops = 2.0 * d * pairs / (join_ms * 1e-3) / 1e12 if join_ms > 0 else 0.0
     last = stats[-1]
 
     # ---- quality, outside the timed region
@@ -147,7 +163,10 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((w.name, a.k_build or k, a.rho or 0.5)),
                      "launches": launches, "avg_launch_ms": join_ms / max(launches, 1),
-                     "alg_bytes_per_launch": alg_bytes / max(launches, 1)},
+                     "alg_bytes_per_launch": alg_bytes / max(launches, 1),
+                     "device_copy_gbs": copy_gbs, "frac_of_device_copy": achieved / copy_gbs,
+                     "needed_pair_tflops": needed_tflops, "frac_of_fp32_mfma_peak": needed_tflops / 157.3,
+                     "offers_per_launch": offers / max(launches, 1)},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

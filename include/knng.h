@@ -59,7 +59,9 @@ typedef struct knng_stats {
     uint64_t join_rows[KNNG_STATS_MAX_ITERS]; /* vectors gathered by that launch    */
     float ms_init, ms_sample, ms_join, ms_merge, ms_finalize; /* summed kernel ms   */
     float ms_total;            /* first enqueue to last completion                  */
-    uint64_t offers;           /* candidates offered to candidate lists (atomics)   */
+    uint64_t offers;           /* candidates offered to candidate lists (atomics), whole build */
+    uint64_t pairs;            /* pairs the local joins had to evaluate (new x new unordered
+                                  plus new x old per joined point), whole build      */
 } knng_stats_t;
 
 /*

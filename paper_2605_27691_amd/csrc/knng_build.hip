@@ -336,7 +336,7 @@ k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
 // are hashes), fix the four list lengths for the join, append the points that have anything new
 // around them to the active list, and count the vectors the join will gather.
 // A block owns PLAN_CHUNK consecutive points: it takes its share of the active list with one
-// atomic.  ctr[1] += vectors, ctr[2] += active points.
+// atomic.  ctr[1] += vectors, ctr[2] += active points, ctr[3] += pairs to evaluate.
 // A wavefront reads whole 16-byte pieces: LPL lanes per list, 64/LPL lists (both kinds of
 // 32/LPL points) per step.
 // ------------------------------------------------------------------------------------------
@@ -347,7 +347,7 @@ k_plan(int64_t n, int s, int B, u64 seed, uint32_t iter, const uint32_t* __restr
        int4* __restrict__ plan, int32_t* __restrict__ active, u64* __restrict__ ctr)
 {
     __shared__ unsigned char actf[PLAN_CHUNK];
-    __shared__ u64 wrows[4];
+    __shared__ u64 wrows[4], wpairs[4];
     __shared__ int wcnt[4];
     __shared__ u64 s_base;
     const uint32_t saltp = rev_salt(seed, iter);
@@ -363,7 +363,7 @@ k_plan(int64_t n, int s, int B, u64 seed, uint32_t iter, const uint32_t* __restr
     const int npts = (int)((n - p0) < PLAN_CHUNK ? (n - p0) : PLAN_CHUNK);
     const u64 gm = ((1ull << LPL) - 1ull) << (g * LPL);
     const u64 ltg = gm & lanemask_lt();
-    u64 rows = 0;
+    u64 rows = 0, pairs = 0;
     auto load_piece = [&](int base) {
         const int pl = base + (g >> 1);
         uint4 key = uint4{EMPTY_REV, EMPTY_REV, EMPTY_REV, EMPTY_REV};
@@ -395,22 +395,28 @@ k_plan(int64_t n, int s, int B, u64 seed, uint32_t iter, const uint32_t* __restr
             plan[p] = int4{c.x, c.y, mine, other};
             const bool act = (c.x + mine) > 0;
             actf[pl] = act ? 1 : 0;
-            if (act) rows += (u64)(c.x + c.y + mine + other);
+            if (act) {
+                rows += (u64)(c.x + c.y + mine + other);
+                const int nn = c.x + mine, no = c.y + other;
+                pairs += (u64)(nn * (nn - 1) / 2 + nn * no);
+            }
         }
     }
-    for (int o = 32; o > 0; o >>= 1) rows += __shfl_xor(rows, o);
+    for (int o = 32; o > 0; o >>= 1) { rows += __shfl_xor(rows, o); pairs += __shfl_xor(pairs, o); }
     __syncthreads();
     const int t = (int)threadIdx.x;
     const bool a0 = t < npts && actf[t] != 0;
     const bool a1 = t + 256 < npts && actf[t + 256] != 0;
     const u64 m0 = __ballot(a0), m1 = __ballot(a1);
-    if (lane == 0) { wcnt[w] = __popcll(m0) + __popcll(m1); wrows[w] = rows; }
+    if (lane == 0) { wcnt[w] = __popcll(m0) + __popcll(m1); wrows[w] = rows; wpairs[w] = pairs; }
     __syncthreads();
     if (t == 0) {
         const int tot = wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
         s_base = tot ? atomicAdd(ctr + 2, (u64)tot) : 0ull;
         const u64 rt = wrows[0] + wrows[1] + wrows[2] + wrows[3];
         if (rt) atomicAdd(ctr + 1, rt);
+        const u64 pt = wpairs[0] + wpairs[1] + wpairs[2] + wpairs[3];
+        if (pt) atomicAdd(ctr + 3, pt);
     }
     __syncthreads();
     u64 at = s_base;
@@ -531,9 +537,11 @@ __global__ void __launch_bounds__(256) KNNG_JOIN_WAVES
 k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
        const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl, const int4* __restrict__ plan,
        const int32_t* __restrict__ active, const u64* __restrict__ nactive_ptr,
-       const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand)
+       const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand,
+       u64* __restrict__ offers_ctr)
 {
     using Cfg = JoinCfg<S16, DS_>;
+    uint32_t n_offers = 0;                                     // this thread's, summed per wavefront at exit
     constexpr int DS = Cfg::DS, LD = Cfg::LD, LDD = Cfg::LDD, NT = Cfg::NT, NL = Cfg::NL, NCOLS = Cfg::NCOLS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float* X = reinterpret_cast<float*>(smem);                 // [NCOLS][LD], later D [MROWS][LDD]
@@ -722,6 +730,7 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 const uint32_t vw = sg[NCOLS * SIG_WORDS + (h >> 5)];
                 if (l < thr_v[0] && !((vw >> (h & 31u)) & 1u)) {
                     const uint32_t slot = below(hash32((uint32_t)me.x), (uint32_t)C);
+                    ++n_offers;
                     atomicMin(&cand[v * C + slot], pack_key(l, me.x, 1));
                 }
             }
@@ -771,6 +780,7 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             if (best_l != 0xffffffffu) {
                 const int pid = mh[best_j].x;
                 const uint32_t slot = below(hash32((uint32_t)pid), (uint32_t)C);
+                ++n_offers;
                 atomicMin(&cand[(int64_t)myid * C + slot], pack_key(__uint_as_float(best_l), pid, 1));
             }
         }
@@ -784,6 +794,8 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
         P = Pn;
         cur ^= 1;
     }
+    for (int o = 32; o > 0; o >>= 1) n_offers += __shfl_xor(n_offers, o);
+    if ((tid & 63) == 0 && n_offers) atomicAdd(offers_ctr, (u64)n_offers);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -898,7 +910,7 @@ namespace knng {
 struct JoinArgs {
     const float* pts; int d; int C; int s; uint32_t iter;
     const int32_t* newl; const int32_t* oldl; const int4* plan; const int32_t* active;
-    const u64* nactive; const float* worst; const uint32_t* sig; u64* cand;
+    const u64* nactive; const float* worst; const uint32_t* sig; u64* cand; u64* offers;
     int num_cu; int64_t n;
 };
 
@@ -920,7 +932,7 @@ static hipError_t launch_join_k(hipStream_t st, const JoinArgs& a)
     int64_t grid = (int64_t)a.num_cu * blocks_per_cu;
     if (grid > a.n) grid = a.n;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a.pts, a.d, a.C, a.s, a.iter, a.newl,
-                       a.oldl, a.plan, a.active, a.nactive, a.worst, a.sig, a.cand);
+                       a.oldl, a.plan, a.active, a.nactive, a.worst, a.sig, a.cand, a.offers);
     return hipGetLastError();
 }
 
@@ -942,7 +954,7 @@ static hipError_t launch_join_w(hipStream_t st, const JoinArgs& a)
     int64_t grid = (int64_t)a.num_cu * blocks_per_cu;
     if (grid > (a.n + 3) / 4) grid = (a.n + 3) / 4;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a.pts, a.d, a.C, a.s, a.iter, a.newl,
-                       a.oldl, a.plan, a.active, a.nactive, a.worst, a.sig, a.cand);
+                       a.oldl, a.plan, a.active, a.nactive, a.worst, a.sig, a.cand, a.offers);
     return hipGetLastError();
 }
 
@@ -1003,7 +1015,7 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
     int32_t* active = reinterpret_cast<int32_t*>(ws + bp.off_active);
     float* worst = reinterpret_cast<float*>(ws + bp.off_worst);
     uint32_t* sig = reinterpret_cast<uint32_t*>(ws + bp.off_sig);
-    u64* ctr = reinterpret_cast<u64*>(ws + bp.off_ctr);      // [0] updates, [1] rows gathered
+    u64* ctr = reinterpret_cast<u64*>(ws + bp.off_ctr);      // [0] updates [1] rows gathered [2] active [3] pairs [4] offers
     knng_stats_t* stats = params->stats_host;
     const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(points_dev) & 15u) == 0);
     const unsigned row_blocks = (unsigned)((n + 3) / 4);
@@ -1057,13 +1069,14 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
         if (rec) HIPCHK(hipEventRecord(ev[2 + 4 * it], st));
         if (stats && !more) HIPCHK(hipEventRecord(ev[n_ev - 2], st));
         if (it > 0) {
-            HIPCHK(hipMemcpyAsync(host_ctr, ctr, 24, hipMemcpyDeviceToHost, st));
-            HIPCHK(hipMemsetAsync(ctr, 0, 24, st));
+            HIPCHK(hipMemcpyAsync(host_ctr, ctr, 40, hipMemcpyDeviceToHost, st));
+            HIPCHK(hipMemsetAsync(ctr, 0, 40, st));
             HIPCHK(hipStreamSynchronize(st));
             if (stats && it - 1 < max_rec) {
                 stats->updates[it - 1] = host_ctr[0];
                 stats->join_rows[it - 1] = host_ctr[1];
             }
+            if (stats) { stats->pairs += host_ctr[3]; stats->offers += host_ctr[4]; }
             if ((double)host_ctr[0] < stop_below) { converged = 1; break; }
         }
         if (!more) break;
@@ -1074,7 +1087,7 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
         if (rec) HIPCHK(hipEventRecord(ev[3 + 4 * it], st));
         {
             JoinArgs ja{points_dev, d, bp.C, bp.s, (uint32_t)it, newl, oldl, plan, active, ctr + 2,
-                        worst, sig, cand, num_cu, n};
+                        worst, sig, cand, ctr + 4, num_cu, n};
             if (metric == 0) HIPCHK(launch_join<0>(st, vec, bp.S16, ja));
             else HIPCHK(launch_join<1>(st, vec, bp.S16, ja));
         }

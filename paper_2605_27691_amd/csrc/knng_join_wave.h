@@ -64,7 +64,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(KNNG_W
 k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl, const int4* __restrict__ plan,
             const int32_t* __restrict__ active, const u64* __restrict__ nactive_ptr,
-            const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand)
+            const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand,
+            u64* __restrict__ offers_ctr)
 {
     using Cfg = WaveCfg<S16>;
     constexpr int NCOLS = Cfg::NCOLS, CT = Cfg::CT, DS = Cfg::DS, LD = Cfg::LD, LDD = Cfg::LDD,
@@ -161,11 +162,13 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
     uint32_t pend_l[OFFERS_PER_MEMBER];
 #pragma unroll
     for (int u = 0; u < OFFERS_PER_MEMBER; ++u) pend_l[u] = 0u;
+    uint32_t n_offers = 0;                                     // wavefront total (uniform)
     auto send_offers = [&]() {
 #pragma unroll
         for (int u = 0; u < OFFERS_PER_MEMBER; ++u) {
             const uint32_t j = (pend_j >> (8 * u)) & 0xffu;
             const int pid = __shfl(pend_id, (int)(j & 63u));   // all lanes take part in the shuffle
+            n_offers += (uint32_t)__popcll(__ballot(j != 0xffu));
             if (j != 0xffu) {
                 const uint32_t slot = below(hash32((uint32_t)pid), (uint32_t)C);
                 atomicMin(&cand[(int64_t)pend_id * C + slot], pack_key(__uint_as_float(pend_l[u]), pid, 1));
@@ -321,15 +324,19 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             const int m = lane;
             const bool rev = m < nTot && ((m >= nfn && m < nNew) || (m >= nNew + nfo));
             const uint32_t pthr = nTot < 64 ? (uint32_t)__builtin_amdgcn_readlane((int)my_thr, nTot & 63) : 0u;
+            float l = 0.0f;
+            uint32_t vw = 0xffffffffu;
             if (rev) {
-                float l = nrm[m];
+                l = nrm[m];
                 if (METRIC == 1) l *= 0.5f;
                 l = nonneg(l);
-                const uint32_t vw = sg[(my_hb >> 5) * SGLD + nTot];
-                if (__float_as_uint(l) < pthr && !((vw >> (my_hb & 31u)) & 1u)) {
-                    const uint32_t slot = below(hash32((uint32_t)my_id), (uint32_t)C);
-                    atomicMin(&cand[v * C + slot], pack_key(l, my_id, 1));
-                }
+                vw = sg[(my_hb >> 5) * SGLD + nTot];
+            }
+            const bool go = rev && __float_as_uint(l) < pthr && !((vw >> (my_hb & 31u)) & 1u);
+            n_offers += (uint32_t)__popcll(__ballot(go));
+            if (go) {
+                const uint32_t slot = below(hash32((uint32_t)my_id), (uint32_t)C);
+                atomicMin(&cand[v * C + slot], pack_key(l, my_id, 1));
             }
         }
         wave_lds_sync();
@@ -411,6 +418,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
         cur ^= 1;
     }
     send_offers();
+    if (lane == 0 && n_offers) atomicAdd(offers_ctr, (u64)n_offers);
 }
 
 }  // namespace knng

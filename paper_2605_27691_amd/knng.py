@@ -28,7 +28,8 @@ class Stats(ctypes.Structure):
                 ("ms_init", ctypes.c_float), ("ms_sample", ctypes.c_float),
                 ("ms_join", ctypes.c_float), ("ms_merge", ctypes.c_float),
                 ("ms_finalize", ctypes.c_float), ("ms_total", ctypes.c_float),
-                ("offers", ctypes.c_uint64)]
+                ("offers", ctypes.c_uint64),
+                ("pairs", ctypes.c_uint64)]
 
 
 class Params(ctypes.Structure):
@@ -169,7 +170,8 @@ def knng_build_knn_graph(points, k, metric=L2SQ, *, k_build=0, rho=0.0, delta=0.
                  "updates": list(st.updates[:it]), "join_ms": list(st.join_ms[:it]),
                  "join_rows": list(st.join_rows[:it]), "ms_init": st.ms_init,
                  "ms_sample": st.ms_sample, "ms_join": st.ms_join, "ms_merge": st.ms_merge,
-                 "ms_finalize": st.ms_finalize, "ms_total": st.ms_total}
+                 "ms_finalize": st.ms_finalize, "ms_total": st.ms_total,
+                 "offers": int(st.offers), "pairs": int(st.pairs)}
     return ids_out, dists_out, stats
 
 

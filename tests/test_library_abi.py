@@ -32,7 +32,7 @@ def test_struct_layouts_match_the_header_sizes():
     # params: u32 i32 f32 f32 i32 i32 u64 ptr ptr ptr u64 ptr = 72 bytes on LP64
     assert ctypes.sizeof(knng.Params) == 72
     # stats: 2*i32 + 128*u64 + 128*f32 + 128*u64 + 6*f32 + u64 (8-byte aligned)
-    assert ctypes.sizeof(knng.Stats) == 8 + 1024 + 512 + 1024 + 24 + 8
+    assert ctypes.sizeof(knng.Stats) == 8 + 1024 + 512 + 1024 + 24 + 8 + 8
 
 
 def test_workspace_queries_are_host_only_and_validate():
