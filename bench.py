@@ -27,6 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+FP32_MFMA_PEAK_TFLOPS = 157.3
 SIG_BYTES = 32          # row signature read per gathered member
 # HBM-side bytes per join launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each
 # scaled by what a plain 1 GiB device copy reads: 2.0 and 1.0 KiB per count), averaged over the same
@@ -115,6 +116,14 @@ def main():
     offers = sum(s["offers"] for s in stats)                  # atomic mins sent to candidate slots
     needed_tflops = 2.0 * d * pairs / (join_ms * 1e-3) / 1e12 if join_ms > 0 else 0.0
     last = stats[-1]
+    # the join is priced against HBM (a gather) unless its Gram blocks are the larger fraction of
+    # their own peak (large samples: s = 32 does four times the pair work per gathered byte)
+    if needed_tflops / FP32_MFMA_PEAK_TFLOPS > achieved / HBM_PEAK_GBS:
+        bound = {"bound": "mfma", "achieved": needed_tflops, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                 "frac": needed_tflops / FP32_MFMA_PEAK_TFLOPS, "hbm_gbs": achieved, "frac_of_hbm_peak": achieved / HBM_PEAK_GBS}
+    else:
+        bound = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                 "frac": achieved / HBM_PEAK_GBS}
 
     # ---- quality, outside the timed region
     rows_s = workloads.sample_rows(n, a.recall_rows)
@@ -159,13 +168,12 @@ def main():
                          "graph_violations": int(sum(viol.values()))},
         "kernel_ms": {"init": last["ms_init"], "sample": last["ms_sample"], "join": last["ms_join"],
                       "merge": last["ms_merge"], "finalize": last["ms_finalize"], "total": last["ms_total"]},
-        "roofline": {"kernel": "k_join", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+        "roofline": {"kernel": "k_join", **bound,
                      "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((w.name, a.k_build or k, a.rho or 0.5)),
                      "launches": launches, "avg_launch_ms": join_ms / max(launches, 1),
                      "alg_bytes_per_launch": alg_bytes / max(launches, 1),
                      "device_copy_gbs": copy_gbs, "frac_of_device_copy": achieved / copy_gbs,
-                     "needed_pair_tflops": needed_tflops, "frac_of_fp32_mfma_peak": needed_tflops / 157.3,
+                     "needed_pair_tflops": needed_tflops, "frac_of_fp32_mfma_peak": needed_tflops / FP32_MFMA_PEAK_TFLOPS,
                      "offers_per_launch": offers / max(launches, 1)},
         "cpu_baseline": cpu,
     }

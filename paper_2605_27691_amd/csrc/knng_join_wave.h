@@ -233,8 +233,6 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 // the slab first: whatever the compiler makes the wavefront wait for before it
                 // reuses a prefetch register must not include the member gathers below
                 issue_slab(nmid, n_tot, n_piv, last ? 0 : k0 + DS);
-                if (last) issue_members(nmid, n_tot, n_piv);
-                if (last && v_nx2 >= 0) { rc_n = plan[v_nx2]; rid_n = load_slot(v_nx2); }
             }
             // ---- C: all Gram tiles of the point for this slab
                         for (int kk = 0; kk < len16; kk += 16) {
@@ -267,8 +265,16 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             }
             wave_lds_sync();
             if (!last) store_slab(k0 + DS);
-            else send_offers();                                 // the previous point's
         }
+        // After the last Gram pass, when the accumulators are the only big thing left in
+        // registers: the next point's thresholds and signatures, the list record of the point after
+        // next, and the previous point's offers.  All of it completes under the norm /
+        // distance-block / scan work below, which never waits for memory.
+        if (v_nx >= 0) {
+            issue_members(midbuf + (cur ^ 1) * NCOLS, Pn.nTot, v_nx);
+            if (v_nx2 >= 0) { rc_n = plan[v_nx2]; rid_n = load_slot(v_nx2); }
+        }
+        send_offers();                                          // the previous point's
 
         // ---- member norms from the diagonal tiles: lane (r16, kq) holds rows 4kq..4kq+3 of
         // column r16, so the diagonal element sits in the lanes with r16 / 4 == kq
