@@ -34,6 +34,8 @@ def lib():
         L.oracle_nn_descent.restype = ctypes.c_int
         L.oracle_nn_descent.argtypes = [P, c_i64, c_i32, c_i32, c_i32, c_i32, c_f64, c_f64,
                                         c_i32, c_i32, c_u64, P, P, P]
+        L.oracle_merge_rows.restype = ctypes.c_int
+        L.oracle_merge_rows.argtypes = [P, P, c_i32, P, P, c_i32, c_i64, c_i32, P, P]
         _lib = L
     return _lib
 
@@ -88,6 +90,20 @@ def graph_recall(test_ids, test_dists, ref_ids, ref_dists, at_k, mode=0) -> floa
     if r < 0:
         raise ValueError("oracle_graph_recall: bad arguments")
     return float(r)
+
+
+def merge_rows(ids_a, dists_a, ids_b, dists_b, k_out):
+    """Rows of graph A updated with the candidates B (same number of rows).  -> (ids i32, dists f32)."""
+    ia, da, ib, db = _i32(ids_a), _f32(dists_a), _i32(ids_b), _f32(dists_b)
+    n = ia.shape[0]
+    assert ia.shape == da.shape and ib.shape == db.shape and ib.shape[0] == n
+    ids = np.empty((n, k_out), dtype=np.int32)
+    dists = np.empty((n, k_out), dtype=np.float32)
+    rc = lib().oracle_merge_rows(_p(ia), _p(da), ia.shape[1], _p(ib), _p(db), ib.shape[1], n, k_out,
+                                 _p(ids), _p(dists))
+    if rc != 0:
+        raise ValueError("oracle_merge_rows: bad arguments")
+    return ids, dists
 
 
 VIOLATION_NAMES = ("id_range", "self_loop", "duplicate_id", "not_ascending",

@@ -14,6 +14,7 @@
  *   oracle_check_graph   row invariants of a k-NN graph                (Sec. 2.1)
  *   oracle_nn_descent    NN-Descent with candidate lists and a
  *                        single-owner merge, step by step              (Sec. 3.1, 3.1.1)
+ *   oracle_merge_rows    a graph's rows updated with search results R  (Sec. 4.3 step 4, 4.4)
  *
  * Pin status: every function is pinned by tests that do not go through this
  * file (closed forms, exhaustive enumeration in numpy on tiny inputs, integer
@@ -524,5 +525,51 @@ int oracle_nn_descent(const float *points, int64_t n, int32_t d, int32_t k, int3
     free(newf); free(oldf); free(newf_cnt); free(oldf_cnt);
     free(NEW); free(OLD); free(NEW_cnt); free(OLD_cnt);
     free(rev_off); free(rev_src); free(pa); free(pb); free(pl);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Update of a k-NN graph's rows with neighbour candidates found elsewhere   */
+/* (Sec. 4.3 step 4: a rank "updates G_{i->i} accordingly" with the k        */
+/* candidates per point found on a remote graph; Sec. 4.4: G_{0->0} becomes  */
+/* G_{0->0:1} "using R_{0->1}").  R has the layout of a graph: ids and       */
+/* distances per query point (Sec. 4.4).                                     */
+/* Row i of the result = the k_out smallest entries under (distance, id) of  */
+/* row i of A and row i of B taken together, one entry per id (of several    */
+/* entries with one id the smallest stays); entries with id < 0 are padding  */
+/* and ignored; missing entries are written as id -1, distance +inf.         */
+/* Plain statement: concatenate, selection sort, skip repeated ids.          */
+/* Returns 0, or -1 on bad arguments.                                        */
+/* ------------------------------------------------------------------------ */
+int oracle_merge_rows(const int32_t *ids_a, const float *dists_a, int32_t ka,
+                      const int32_t *ids_b, const float *dists_b, int32_t kb,
+                      int64_t n, int32_t k_out, int32_t *ids_out, float *dists_out)
+{
+    if (n < 0 || ka < 0 || kb < 0 || k_out < 1 || ka + kb < 1) return -1;
+    if ((ka && (!ids_a || !dists_a)) || (kb && (!ids_b || !dists_b)) || !ids_out || !dists_out) return -1;
+    int32_t m = ka + kb;
+    int32_t *id = (int32_t *)malloc((size_t)m * sizeof(int32_t));
+    float *ds = (float *)malloc((size_t)m * sizeof(float));
+    char *used = (char *)malloc((size_t)m);
+    if (!id || !ds || !used) { free(id); free(ds); free(used); return -1; }
+    for (int64_t i = 0; i < n; ++i) {
+        for (int32_t j = 0; j < ka; ++j) { id[j] = ids_a[i * ka + j]; ds[j] = dists_a[i * ka + j]; }
+        for (int32_t j = 0; j < kb; ++j) { id[ka + j] = ids_b[i * kb + j]; ds[ka + j] = dists_b[i * kb + j]; }
+        for (int32_t j = 0; j < m; ++j) used[j] = id[j] < 0;
+        int32_t w = 0;
+        while (w < k_out) {
+            int32_t best = -1;
+            for (int32_t j = 0; j < m; ++j)
+                if (!used[j] && (best < 0 || key_less(ds[j], id[j], ds[best], id[best]))) best = j;
+            if (best < 0) break;
+            ids_out[i * k_out + w] = id[best];
+            dists_out[i * k_out + w] = ds[best];
+            ++w;
+            for (int32_t j = 0; j < m; ++j)          /* every other entry with this id is larger */
+                if (id[j] == id[best]) used[j] = 1;
+        }
+        for (; w < k_out; ++w) { ids_out[i * k_out + w] = -1; dists_out[i * k_out + w] = INFINITY; }
+    }
+    free(id); free(ds); free(used);
     return 0;
 }

@@ -357,3 +357,70 @@ def test_nn_descent_fixed_size_candidate_lists_drop():
     # far better than the random start (about k/n)
     assert 0.5 <= rec[4] <= rec[0] + 0.01
     assert rec[4] <= rec[64] + 0.01 and rec[64] >= rec[0] - 0.05
+
+
+# ------------------------------------------------------------------ merge_rows (Sec. 4.3 step 4, 4.4)
+def test_merge_rows_hand_example_padding_and_repeated_ids():
+    ia = np.array([[4, 9, 2], [7, -1, -1]], np.int32)
+    da = np.array([[0.5, 1.0, 3.0], [2.0, 0.0, 0.0]], np.float32)
+    ib = np.array([[9, 1], [7, 3]], np.int32)
+    db = np.array([[1.0, 0.75], [1.5, 2.0]], np.float32)
+    oi, od = oracle.merge_rows(ia, da, ib, db, 4)
+    # row 0: id 9 appears in both with the same distance -> once; order by (distance, id)
+    assert oi[0].tolist() == [4, 1, 9, 2] and od[0].tolist() == [0.5, 0.75, 1.0, 3.0]
+    # row 1: id 7 twice with different distances -> the smaller one; padding ids ignored;
+    # the row has only two distinct ids -> filled with -1 / +inf
+    assert oi[1].tolist() == [7, 3, -1, -1]
+    assert od[1, :2].tolist() == [1.5, 2.0] and np.all(np.isinf(od[1, 2:]))
+    # truncation
+    oi2, od2 = oracle.merge_rows(ia, da, ib, db, 2)
+    assert oi2[0].tolist() == [4, 1] and oi2[1].tolist() == [7, 3]
+    # ties in distance go by id
+    oi3, _ = oracle.merge_rows(np.array([[8, 5]], np.int32), np.array([[1.0, 1.0]], np.float32),
+                               np.array([[6]], np.int32), np.array([[1.0]], np.float32), 3)
+    assert oi3[0].tolist() == [5, 6, 8]
+
+
+def test_merge_rows_of_two_partitions_is_the_exact_graph_of_the_union():
+    # the exact neighbours of every point inside each half of the data, merged row by row, are
+    # the exact neighbours in the whole set (what the refinement step relies on, Sec. 4.3)
+    rng = np.random.default_rng(5)
+    n, d, k = 60, 6, 7
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    half = [np.arange(0, 31), np.arange(31, n)]
+    dist = np.array([[float(oracle.distance(x[i], x[j], 0)) for j in range(n)] for i in range(n)],
+                    np.float32)
+    parts = []
+    for base in half:
+        ids = np.empty((n, k), np.int32)
+        dd = np.empty((n, k), np.float32)
+        for i in range(n):
+            cand = sorted((dist[i, j], int(j)) for j in base if j != i)[:k]
+            ids[i] = [c[1] for c in cand]
+            dd[i] = [c[0] for c in cand]
+        parts.append((ids, dd))
+    mi, md = oracle.merge_rows(parts[0][0], parts[0][1], parts[1][0], parts[1][1], k)
+    ei, ed = oracle.brute_knn(x, k, 0)
+    assert np.array_equal(mi, ei) and np.array_equal(md, ed)
+    # merging a graph with itself changes nothing
+    si, sd = oracle.merge_rows(ei, ed, ei, ed, k)
+    assert np.array_equal(si, ei) and np.array_equal(sd, ed)
+
+
+def test_merge_rows_against_a_python_statement_on_random_lists():
+    rng = np.random.default_rng(17)
+    n, ka, kb, ko = 200, 9, 5, 11
+    ia = rng.integers(-1, 30, (n, ka)).astype(np.int32)
+    ib = rng.integers(-1, 30, (n, kb)).astype(np.int32)
+    da = rng.integers(0, 6, (n, ka)).astype(np.float32)          # many equal distances
+    db = rng.integers(0, 6, (n, kb)).astype(np.float32)
+    oi, od = oracle.merge_rows(ia, da, ib, db, ko)
+    for i in range(n):
+        best = {}
+        for idv, dv in list(zip(ia[i], da[i])) + list(zip(ib[i], db[i])):
+            if idv >= 0 and (idv not in best or dv < best[idv]):
+                best[int(idv)] = float(dv)
+        want = sorted((dv, idv) for idv, dv in best.items())[:ko]
+        got = [(float(a), int(b)) for a, b in zip(od[i], oi[i]) if b >= 0]
+        assert got == want
+        assert all(b == -1 for b in oi[i, len(want):])
