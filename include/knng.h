@@ -150,6 +150,29 @@ int knng_graph_recall(const int32_t *test_ids_dev, const float *test_dists_dev, 
                       int64_t rows, int32_t at_k, int32_t mode,
                       double *recall_out_host, void *stream);
 
+/*
+ * Update of a graph's rows with neighbour candidates found elsewhere: the local
+ * half of the refinement step (Sec. 4.3 step 4: a rank updates its graph with the
+ * candidates per point found on a remote graph; Sec. 4.4: G_{0->0} becomes
+ * G_{0->0:1} using the search results R_{0->1}, which have the layout of a graph:
+ * an id matrix and a distance matrix, one row per query point).
+ *
+ * Row i of the result = the k_out smallest entries under (distance, id) of row i
+ * of A and row i of B taken together, one entry per id (of several entries with
+ * one id the smallest stays).  Entries with id < 0 are padding and ignored; a row
+ * with fewer than k_out distinct ids is filled with id -1 / distance +inf.
+ * Distances are non-negative (as everywhere in this library).
+ *
+ * ids_a_dev/dists_a_dev [n][ka], ids_b_dev/dists_b_dev [n][kb], outputs
+ * [n][k_out] (all device; outputs must not overlap inputs).  0 <= ka, kb <=
+ * KNNG_MAX_K, ka + kb >= 1, 1 <= k_out <= 2*KNNG_MAX_K.  Asynchronous on `stream`;
+ * allocates nothing.  Errors: KNNG_EINVAL, KNNG_EHIP.
+ */
+int knng_merge_graphs(const int32_t *ids_a_dev, const float *dists_a_dev, int32_t ka,
+                      const int32_t *ids_b_dev, const float *dists_b_dev, int32_t kb,
+                      int64_t n, int32_t k_out, int32_t *ids_out_dev, float *dists_out_dev,
+                      void *stream);
+
 /* Text for a return code; for KNNG_EHIP the text of the last HIP failure on this thread. */
 const char *knng_strerror(int code);
 

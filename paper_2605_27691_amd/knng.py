@@ -48,7 +48,7 @@ class Params(ctypes.Structure):
 
 
 EXPORTS = ("knng_build_workspace_bytes", "knng_build_knn_graph", "knng_brute_workspace_bytes",
-           "knng_brute_knn", "knng_graph_recall", "knng_strerror", "knng_version")
+           "knng_brute_knn", "knng_graph_recall", "knng_merge_graphs", "knng_strerror", "knng_version")
 
 _lib = None
 
@@ -77,6 +77,8 @@ def load():
     L.knng_graph_recall.restype = ctypes.c_int
     L.knng_graph_recall.argtypes = [_P, _P, i32, _P, _P, i32, i64, i32, i32,
                                     ctypes.POINTER(ctypes.c_double), _P]
+    L.knng_merge_graphs.restype = ctypes.c_int
+    L.knng_merge_graphs.argtypes = [_P, _P, i32, _P, _P, i32, i64, i32, _P, _P, _P]
     L.knng_strerror.restype = ctypes.c_char_p
     L.knng_strerror.argtypes = [ctypes.c_int]
     L.knng_version.restype = ctypes.c_int
@@ -215,3 +217,25 @@ def knng_graph_recall(test_ids, test_dists, ref_ids, ref_dists, at_k, mode=0) ->
                                _ptr(ref_dists), r.shape[1], t.shape[0], at_k, mode,
                                ctypes.byref(out), _stream()))
     return float(out.value)
+
+
+def knng_merge_graphs(ids_a, dists_a, ids_b, dists_b, k_out, ids_out=None, dists_out=None):
+    """Rows of graph A updated with the candidates B: the k_out nearest distinct ids of both."""
+    L = load()
+    ids_a = _dev(ids_a, torch.int32, "ids_a")
+    dists_a = _dev(dists_a, torch.float32, "dists_a")
+    ids_b = _dev(ids_b, torch.int32, "ids_b")
+    dists_b = _dev(dists_b, torch.float32, "dists_b")
+    if ids_a is None or ids_b is None or dists_a is None or dists_b is None:
+        raise KnngError(-1)
+    if ids_a.shape != dists_a.shape or ids_b.shape != dists_b.shape or ids_a.shape[0] != ids_b.shape[0]:
+        raise KnngError(-1)
+    n = ids_a.shape[0]
+    if ids_out is None:
+        ids_out = torch.empty((n, k_out), dtype=torch.int32, device=ids_a.device)
+    if dists_out is None:
+        dists_out = torch.empty((n, k_out), dtype=torch.float32, device=ids_a.device)
+    _check(L.knng_merge_graphs(_ptr(ids_a), _ptr(dists_a), ids_a.shape[1], _ptr(ids_b), _ptr(dists_b),
+                               ids_b.shape[1], n, k_out, _ptr(_dev(ids_out, torch.int32, "ids_out")),
+                               _ptr(_dev(dists_out, torch.float32, "dists_out")), _stream()))
+    return ids_out, dists_out

@@ -311,3 +311,78 @@ def test_full_size_config3_gist_shape():
 
 def test_full_size_config4_twenty_million():
     _full_size_case(4, dict(k_build=64), oracle_rows=8, recall_rows=4000)
+
+
+# ------------------------------------------------------------------ merge_graphs (Sec. 4.3 step 4, 4.4)
+@pytest.mark.parametrize("n,ka,kb,ko,nid", [(1, 1, 0, 1, 5), (257, 64, 64, 128, 90), (1000, 32, 32, 32, 50),
+                                            (513, 9, 5, 11, 30), (130, 0, 7, 7, 9), (300, 64, 3, 40, 1000)])
+def test_merge_rows_bit_exact_against_the_oracle(n, ka, kb, ko, nid):
+    rng = np.random.default_rng(n * 7 + ka)
+    ia = rng.integers(-1, nid, (n, ka)).astype(np.int32)         # repeated ids, padding (-1)
+    ib = rng.integers(-1, nid, (n, kb)).astype(np.int32)
+    da = (rng.integers(0, 8, (n, ka)) * 0.25).astype(np.float32)  # many equal distances
+    db = (rng.integers(0, 8, (n, kb)) * 0.25).astype(np.float32)
+    oi, od = oracle.merge_rows(ia, da, ib, db, ko)
+    gi, gd = knng.knng_merge_graphs(_gpu(ia), _gpu(da), _gpu(ib), _gpu(db), ko)
+    assert np.array_equal(gi.cpu().numpy(), oi)
+    assert np.array_equal(gd.cpu().numpy().view(np.uint32), od.view(np.uint32))
+
+
+def test_merge_rows_argument_errors():
+    z_i = torch.zeros((4, 3), dtype=torch.int32, device=DEV)
+    z_d = torch.zeros((4, 3), dtype=torch.float32, device=DEV)
+    with pytest.raises(knng.KnngError):
+        knng.knng_merge_graphs(z_i, z_d, z_i, z_d, 0)
+    with pytest.raises(knng.KnngError):
+        knng.knng_merge_graphs(z_i, z_d, z_i, z_d, 129)
+    with pytest.raises(knng.KnngError):
+        knng.knng_merge_graphs(z_i, z_d, z_i[:3].contiguous(), z_d[:3].contiguous(), 3)
+    big_i = torch.zeros((4, 65), dtype=torch.int32, device=DEV)
+    big_d = torch.zeros((4, 65), dtype=torch.float32, device=DEV)
+    with pytest.raises(knng.KnngError):
+        knng.knng_merge_graphs(big_i, big_d, z_i, z_d, 3)
+
+
+def test_merge_of_two_partitions_then_warm_started_refinement():
+    # one level of the refinement scheme without the network (Sec. 4.4): every point's exact
+    # neighbours inside the *other* half of the data play the search results R; merged into the
+    # graph each half built on its own they give the graph of the whole set, and a warm-started
+    # build over the whole set keeps or improves it
+    x, w = workloads.make(0, n=8000)
+    n, k = w.n, w.k
+    xg = _gpu(x)
+    exact = oracle.brute_knn(x, k, w.metric)
+    half = n // 2
+    parts = []
+    for lo, hi in ((0, half), (half, n)):
+        ids, dists, _ = knng.knng_build_knn_graph(xg[lo:hi].contiguous(), k, w.metric, k_build=32, seed=5)
+        parts.append((ids + lo, dists))                           # local ids -> ids in the whole set
+    g_i = torch.cat([p[0] for p in parts]).contiguous()
+    g_d = torch.cat([p[1] for p in parts]).contiguous()
+    rec_local = oracle.graph_recall(g_i.cpu().numpy(), g_d.cpu().numpy(), exact[0], exact[1], k, 0)
+    # R: neighbours of each point in the other half (exact rows from the other half's points)
+    r_i = torch.empty((n, k), dtype=torch.int32, device=DEV)
+    r_d = torch.empty((n, k), dtype=torch.float32, device=DEV)
+    for (lo, hi), (olo, ohi) in (((0, half), (half, n)), ((half, n), (0, half))):
+        # brute force over [other half ; one query point at a time is too slow]: score the other
+        # half against these queries with the exact rows of the concatenation, queries last
+        both = torch.cat([xg[olo:ohi], xg[lo:hi]]).contiguous()
+        q = torch.arange(ohi - olo, ohi - olo + (hi - lo), dtype=torch.int32, device=DEV)
+        bi, bd = knng.knng_brute_knn(both, 2 * k, w.metric, q)
+        # keep only neighbours that lie in the other half (index < its size), first k of them
+        keep = bi < (ohi - olo)
+        order = torch.argsort((~keep).to(torch.int8), dim=1, stable=True)[:, :k]
+        sel_i = torch.gather(bi, 1, order)
+        sel_d = torch.gather(bd, 1, order)
+        ok = torch.gather(keep, 1, order)
+        r_i[lo:hi] = torch.where(ok, sel_i + olo, torch.full_like(sel_i, -1))
+        r_d[lo:hi] = torch.where(ok, sel_d, torch.zeros_like(sel_d))
+    m_i, m_d = knng.knng_merge_graphs(g_i, g_d, r_i.contiguous(), r_d.contiguous(), k)
+    oi, od = oracle.merge_rows(g_i.cpu().numpy(), g_d.cpu().numpy(), r_i.cpu().numpy(), r_d.cpu().numpy(), k)
+    assert np.array_equal(m_i.cpu().numpy(), oi) and np.array_equal(m_d.cpu().numpy(), od)
+    rec_merged = _check_build(x, k, w.metric, m_i, m_d, exact, min_recall=0.9)
+    assert rec_merged > rec_local + 0.2                           # half of the true neighbours were out of reach
+    # warm start from the merged graph: a short refinement over the whole set
+    f_i, f_d, st = knng.knng_build_knn_graph(xg, k, w.metric, k_build=k, init_ids=m_i, seed=5)
+    rec_final = _check_build(x, k, w.metric, f_i, f_d, exact, min_recall=0.9)
+    assert rec_final >= rec_merged - 0.01
