@@ -78,7 +78,7 @@ typedef struct knng_params {
                                  default 1e-4; negative = never stop early (Sec. 3.1)          */
     int32_t max_iters;        /* default 100 (Sec. 5.3.1); negative = 0 iterations             */
     int32_t cand_cap;         /* slots of each point's fixed-size candidate list
-                                 (Sec. 3.1.1), 1..KNNG_MAX_K; default K                        */
+                                 (Sec. 3.1.1), 1..KNNG_MAX_K; default min(2K, KNNG_MAX_K)      */
     uint64_t seed;
     const int32_t *init_ids_dev; /* optional warm start [n][K] (device); entries that are out
                                  of range, self or repeated are replaced by random ids; NULL =

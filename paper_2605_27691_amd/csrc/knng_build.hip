@@ -878,7 +878,7 @@ static bool make_plan(int64_t n, int32_t d, int32_t k, const knng_params_t* p, B
     if (max_iters < 0) max_iters = 0;
     if (K < k || K > KNNG_MAX_K || (int64_t)K > n - 1) return false;
     if (!(rho > 0.0f) || rho > 1.0f) return false;
-    int C = (p && p->cand_cap) ? p->cand_cap : K;
+    int C = (p && p->cand_cap) ? p->cand_cap : (2 * K < KNNG_MAX_K ? 2 * K : KNNG_MAX_K);
     if (C < 1 || C > KNNG_MAX_K) return false;
     int s = (int)ceil((double)rho * (double)K);
     if (s < 1) s = 1;
