@@ -484,6 +484,15 @@ __device__ __forceinline__ float4 load_piece(const float* __restrict__ row, int 
     return x;
 }
 
+// 16-byte piece at t; VEC: the caller keeps t inside the row, so the load is unconditional (a
+// zero fill before a predicated load would make the compiler wait for every load in flight)
+template <bool VEC>
+__device__ __forceinline__ float4 load_piece_inside(const float* __restrict__ row, int t, int d)
+{
+    if (VEC) return *reinterpret_cast<const float4*>(row + t);
+    return load_piece<false>(row, t, d);
+}
+
 // Workgroup barrier that orders LDS accesses only: outstanding global loads stay in flight.
 __device__ __forceinline__ void lds_barrier()
 {
@@ -597,21 +606,30 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             sg_r1 = sp[1];
         }
     };
+    // All member ids are read from LDS before the first load is issued (one LDS round trip per
+    // slab); a group of RP rows is loaded whole (rows past the last member repeat it) or not at
+    // all; VEC pieces past the end of the row come from its last piece and are zeroed at the store.
     auto issue_slab = [&](const int* mid, int nTot, int64_t pivot_row, int k0) {
         const SlabMap sm = slab_map(d, k0, DS, tid);
-        const int t = k0 + 4 * sm.c4;
-        pv = float4{0, 0, 0, 0};
-        if (sm.col_ok && nTot > 0) pv = load_piece<VEC>(pts + pivot_row * d, t, d);
+        int t = k0 + 4 * sm.c4;
+        if (VEC) t = t < d ? t : d - 4;
+        if (nTot > 0) {                                         // uniform
+            int rowid[NL];
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int row = sm.rsub + i * sm.RP;
-            buf[i] = float4{0, 0, 0, 0};
-            if (sm.col_ok && row < nTot) buf[i] = load_piece<VEC>(pts + (int64_t)mid[row] * d, t, d);
+            for (int i = 0; i < NL; ++i) {
+                const int row = sm.rsub + i * sm.RP;
+                rowid[i] = mid[row < nTot ? row : nTot - 1];
+            }
+            pv = load_piece_inside<VEC>(pts + pivot_row * d, t, d);
+#pragma unroll
+            for (int i = 0; i < NL; ++i)
+                if (i * sm.RP < nTot)                           // uniform
+                    buf[i] = load_piece_inside<VEC>(pts + (int64_t)rowid[i] * d, t, d);
         }
     };
 
-    issue_members(midbuf, P.nTot, v);
     issue_slab(midbuf, P.nTot, v, 0);
+    issue_members(midbuf, P.nTot, v);
     int4 rc_n = int4{0, 0, 0, 0};
     int rid_n = 0;
     if (v_nx >= 0) { rc_n = plan[v_nx]; rid_n = load_slot(v_nx); }
@@ -662,11 +680,15 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             }
             if (sm.col_ok) {
                 float* xdst = X + sm.rsub * LD + 4 * sm.c4;
+                const bool inb = !VEC || k0 + 4 * sm.c4 < d;
 #pragma unroll
                 for (int i = 0; i < NL; ++i) {
-                    float4 x = buf[i];
-                    x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w;
-                    if (sm.rsub + i * sm.RP < nTot) *reinterpret_cast<float4*>(xdst + i * sm.RP * LD) = x;
+                    if (i * sm.RP < nTot) {                     // uniform: the group was loaded
+                        float4 x = buf[i];
+                        x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w;
+                        if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
+                        if (sm.rsub + i * sm.RP < nTot) *reinterpret_cast<float4*>(xdst + i * sm.RP * LD) = x;
+                    }
                 }
             }
             if (last && v_nx >= 0) {                       // next point's member ids
@@ -681,8 +703,8 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 const int* nmid = to_next ? midbuf + (cur ^ 1) * NCOLS : mid;
                 const int n_tot = to_next ? (v_nx >= 0 ? Pn.nTot : 0) : nTot;
                 const int64_t n_piv = to_next ? (v_nx >= 0 ? v_nx : v) : v;
-                if (to_next && v_nx >= 0) issue_members(nmid, n_tot, n_piv);
                 issue_slab(nmid, n_tot, n_piv, to_next ? 0 : k0 + DS);
+                if (to_next && v_nx >= 0) issue_members(nmid, n_tot, n_piv);
                 if (to_next && v_nx2 >= 0) { rc_n = plan[v_nx2]; rid_n = load_slot(v_nx2); }
             }
             // ---- C: Gram tiles of this slab

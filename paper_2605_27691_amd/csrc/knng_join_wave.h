@@ -52,13 +52,6 @@ template <int S16> struct WaveCfg {
 #ifndef KNNG_WAVE_OCC
 #define KNNG_WAVE_OCC 3
 #endif
-// 16-byte piece at t; VEC: the caller keeps t inside the row, so the load is unconditional
-template <bool VEC>
-__device__ __forceinline__ float4 load_piece_inside(const float* __restrict__ row, int t, int d)
-{
-    if (VEC) return *reinterpret_cast<const float4*>(row + t);
-    return load_piece<false>(row, t, d);
-}
 template <int METRIC, int S16, bool VEC>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(KNNG_WAVE_OCC, KNNG_WAVE_OCC)))
 k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
