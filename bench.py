@@ -32,8 +32,8 @@ SIG_BYTES = 32          # row signature read per gathered member
 # HBM-side bytes per join launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each
 # scaled by what a plain 1 GiB device copy reads: 2.0 and 1.0 KiB per count), averaged over the same
 # launch mix as the timed region.  Only measured for the default workload and parameters
-# (profiles/k_join_config1_1m_d128_hbm_traffic.txt: 18.47 GB fetched + 1.73 GB written).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("u8gmm1024_1m_d128_l2", 32, 0.5): 20.20e9}
+# (profiles/k_join_config1_1m_d128_hbm_traffic.txt: 17.28 GB fetched + 1.47 GB written).
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("u8gmm1024_1m_d128_l2", 32, 0.5): 18.75e9}
 
 
 def parse():
