@@ -69,33 +69,21 @@ __device__ __forceinline__ float dist_group8(const float* __restrict__ a, const 
 // k_update rebuilds every row's signature each iteration, right before the join reads it.
 // ------------------------------------------------------------------------------------------
 constexpr int SIG_WORDS = 8;
-// orders one wavefront's own LDS accesses (they execute in order; this keeps the compiler from
-// moving them and makes returned data available) -- enough for wavefront-private LDS regions
-#ifndef KNNG_REV_MULT
-#define KNNG_REV_MULT 2          // reverse buckets per point and kind, in units of s
-#endif
-constexpr uint32_t EMPTY_REV = 0xffffffffu;            // an empty reverse bucket
-__device__ __forceinline__ void wave_lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 // The bit an id maps to changes with the iteration (salt), so a false positive does not
 // shadow the same candidate for good.
 __device__ __forceinline__ uint32_t sig_bit(int id, uint32_t salt)
 {
     return hash32((uint32_t)id ^ (salt * 0x9e3779b9u + 0x5bd1e995u)) & 255u;
 }
-// every lane contributes id (if has); lane w < 8 writes word w of the OR
-__device__ __forceinline__ void store_signature(uint32_t* __restrict__ dst, int id, bool has, uint32_t salt)
-{
-    const uint32_t h = sig_bit(id, salt);
-    uint32_t mine = 0;
-#pragma unroll
-    for (int w = 0; w < SIG_WORDS; ++w) {
-        uint32_t x = (has && (h >> 5) == (uint32_t)w) ? (1u << (h & 31u)) : 0u;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) x |= __shfl_xor(x, o);
-        if (lane_id() == w) mine = x;
-    }
-    if (lane_id() < SIG_WORDS) dst[lane_id()] = mine;
-}
+
+// Orders one wavefront's own LDS accesses (they execute in order; this keeps the compiler from
+// moving them and makes returned data available): enough for wavefront-private LDS regions.
+__device__ __forceinline__ void wave_lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+#ifndef KNNG_REV_MULT
+#define KNNG_REV_MULT 2          // reverse buckets per point and kind, in units of s
+#endif
+constexpr uint32_t EMPTY_REV = 0xffffffffu;            // an empty reverse bucket
 
 // ------------------------------------------------------------------------------------------
 // k_init: one wavefront per point.  K distinct ids != v (random, or the caller's warm start
@@ -447,9 +435,6 @@ k_plan(int64_t n, int s, int B, u64 seed, uint32_t iter, const uint32_t* __restr
 #ifndef KNNG_OFFERS_PER_MEMBER
 #define KNNG_OFFERS_PER_MEMBER 4
 #endif
-#ifndef KNNG_JOIN_WAVES
-#define KNNG_JOIN_WAVES
-#endif
 #ifndef KNNG_JOIN_DS
 #define KNNG_JOIN_DS 64       // slab length for s <= 16 (the paper's default parameters)
 #endif
@@ -542,7 +527,7 @@ __device__ __forceinline__ int member_of_slot(int t, int s, int4 c)
 }
 
 template <int METRIC, int S16, int DS_, bool VEC>
-__global__ void __launch_bounds__(256) KNNG_JOIN_WAVES
+__global__ void __launch_bounds__(256)
 k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
        const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl, const int4* __restrict__ plan,
        const int32_t* __restrict__ active, const u64* __restrict__ nactive_ptr,
