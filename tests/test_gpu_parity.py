@@ -174,6 +174,21 @@ def test_build_full_degree_is_the_exact_graph(metric):
         assert np.array_equal(dists.cpu().numpy(), od)
 
 
+@pytest.mark.parametrize("n,d,k,kb,rho", [(2, 1, 1, 1, 1.0), (3, 2, 2, 2, 0.5), (5, 3, 1, 4, 0.3),
+                                          (33, 5, 4, 7, 0.1), (100, 7, 5, 64, 1.0), (65, 4, 64, 64, 0.5),
+                                          (1000, 128, 1, 1, 1.0), (257, 12, 3, 33, 0.52)])
+def test_build_smallest_and_largest_parameter_corners(n, d, k, kb, rho):
+    rng = np.random.default_rng(n * 31 + d)
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    exact = oracle.brute_knn(x, k, 0)
+    ids, dists, st = knng.knng_build_knn_graph(_gpu(x), k, 0, k_build=kb, rho=rho, seed=4)
+    rec = _check_build(x, k, 0, ids, dists, exact)
+    assert 0 < st["iterations"] <= 100
+    if kb == n - 1:                                   # the row holds every other point: exact
+        assert rec == 1.0
+        assert np.array_equal(ids.cpu().numpy(), exact[0])
+
+
 def test_build_random_start_and_monotone_refinement():
     x, w = workloads.make(0, n=4000)
     k = 10
