@@ -11,29 +11,26 @@
 
 namespace knng {
 
+// orders one wavefront's own LDS accesses (wavefront-private regions)
+__device__ __forceinline__ void wave_lds_sync_merge() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 // One wavefront per row, 4 rows per workgroup.  Lane l holds entry l of row A and entry l of row
 // B as one 64-bit word (fp32 distance bits, then the id): unsigned order = (distance, id) order.
-// Pass 1 drops every entry that has the same id as an entry that sorts before it (or an equal one
-// at a lower position); pass 2 ranks the rest by counting.  Both walk the other entries with
-// v_readlane broadcasts.
-__global__ void __launch_bounds__(256)
-k_merge_rows(const int32_t* __restrict__ ids_a, const float* __restrict__ dists_a, int ka,
-             const int32_t* __restrict__ ids_b, const float* __restrict__ dists_b, int kb,
-             int64_t n, int k_out, int32_t* __restrict__ ids_out, float* __restrict__ dists_out)
+//
+// Rows as graphs and searches produce them -- each list ascending, padding only at its end, an
+// id shared by the two lists carrying the same distance in both -- take the short way: the rank
+// of an entry in the union is its own position plus a binary search in the other list, and an
+// entry of B equal to one of A is dropped.  That the ids really are distinct otherwise is
+// checked exactly with a small hash set in LDS; if that or the ordering fails, the row takes
+// the general way below.
+//
+// General way: pass 1 drops every entry that has the same id as an entry that sorts before it
+// (or an equal one at a lower position); pass 2 ranks the rest by counting.  Both walk the other
+// entries with v_readlane broadcasts: (ka + kb)^2 compares per row.
+constexpr int MSET = 256;                         // hash-set slots per wavefront (>= 2 * 128 entries)
+
+__device__ __forceinline__ void merge_general(u64 key[2], int ka, int kb, int lane, int rank[2])
 {
-    const int lane = lane_id();
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= n) return;
-    u64 key[2] = {EMPTY_KEY, EMPTY_KEY};
-    if (lane < ka) {
-        const int id = ids_a[row * ka + lane];
-        if (id >= 0) key[0] = ((u64)__float_as_uint(dists_a[row * ka + lane]) << 32) | (uint32_t)id;
-    }
-    if (lane < kb) {
-        const int id = ids_b[row * kb + lane];
-        if (id >= 0) key[1] = ((u64)__float_as_uint(dists_b[row * kb + lane]) << 32) | (uint32_t)id;
-    }
-    // pass 1: repeated ids.  Entry positions: A entries 0..ka-1, then B entries.
     bool drop[2] = {false, false};
 #pragma unroll
     for (int src = 0; src < 2; ++src) {
@@ -52,8 +49,7 @@ k_merge_rows(const int32_t* __restrict__ ids_a, const float* __restrict__ dists_
     }
     if (drop[0]) key[0] = EMPTY_KEY;
     if (drop[1]) key[1] = EMPTY_KEY;
-    // pass 2: ranks among the survivors (their words are distinct: distinct ids)
-    int rank[2] = {0, 0};
+    rank[0] = rank[1] = 0;
 #pragma unroll
     for (int src = 0; src < 2; ++src) {
         const int cnt = src == 0 ? ka : kb;
@@ -62,6 +58,80 @@ k_merge_rows(const int32_t* __restrict__ ids_a, const float* __restrict__ dists_
             rank[0] += kf < key[0] ? 1 : 0;
             rank[1] += kf < key[1] ? 1 : 0;
         }
+    }
+}
+
+__global__ void __launch_bounds__(256)
+k_merge_rows(const int32_t* __restrict__ ids_a, const float* __restrict__ dists_a, int ka,
+             const int32_t* __restrict__ ids_b, const float* __restrict__ dists_b, int kb,
+             int64_t n, int k_out, int32_t* __restrict__ ids_out, float* __restrict__ dists_out)
+{
+    __shared__ u64 keys_s[4][2][WAVE];            // the two lists of each wavefront's row
+    __shared__ int set_s[4][MSET];                // id hash set
+    const int lane = lane_id(), w = threadIdx.x >> 6;
+    const int64_t row = (int64_t)blockIdx.x * 4 + w;
+    if (row >= n) return;
+    u64 key[2] = {EMPTY_KEY, EMPTY_KEY};
+    if (lane < ka) {
+        const int id = ids_a[row * ka + lane];
+        if (id >= 0) key[0] = ((u64)__float_as_uint(dists_a[row * ka + lane]) << 32) | (uint32_t)id;
+    }
+    if (lane < kb) {
+        const int id = ids_b[row * kb + lane];
+        if (id >= 0) key[1] = ((u64)__float_as_uint(dists_b[row * kb + lane]) << 32) | (uint32_t)id;
+    }
+    int rank[2];
+    // ---- the short way: ordering first
+    u64* KA = keys_s[w][0];
+    u64* KB = keys_s[w][1];
+    KA[lane] = key[0];
+    KB[lane] = key[1];
+    for (int i = lane; i < MSET; i += WAVE) set_s[w][i] = -1;
+    wave_lds_sync_merge();
+    bool bad = false;
+    if (lane > 0) {
+        const u64 pa = KA[lane - 1], pb = KB[lane - 1];
+        bad = !(pa < key[0] || key[0] == EMPTY_KEY) || !(pb < key[1] || key[1] == EMPTY_KEY);
+    }
+    bool fast = __ballot(bad) == 0ull;
+    bool dupb = false;
+    int less_in_b = 0, less_in_a = 0;
+    if (fast) {
+        // entries of the other list that sort before mine (both lists ascending, EMPTY last)
+        int lo = 0, hi = WAVE;                    // first position of B with KB[pos] >= key[0]
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if (KB[mid] < key[0]) lo = mid + 1; else hi = mid; }
+        less_in_b = lo;
+        lo = 0; hi = WAVE;                        // first position of A with KA[pos] >= key[1]
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if (KA[mid] < key[1]) lo = mid + 1; else hi = mid; }
+        less_in_a = lo;
+        dupb = key[1] != EMPTY_KEY && lo < WAVE && KA[lo] == key[1];   // the same entry sits in A
+        // every remaining id once?  insert into the hash set; meeting one's own id means no
+        bool clash = false;
+#pragma unroll
+        for (int me = 0; me < 2; ++me) {
+            const bool mine = key[me] != EMPTY_KEY && !(me == 1 && dupb);
+            const int id = (int)(uint32_t)key[me];
+            uint32_t h = hash32((uint32_t)id) & (MSET - 1);
+            bool pending = mine;
+            while (__ballot(pending) != 0ull) {
+                if (pending) {
+                    const int old = atomicCAS(&set_s[w][h], -1, id);
+                    if (old == -1) pending = false;
+                    else if (old == id) { clash = true; pending = false; }
+                    else h = (h + 1) & (MSET - 1);
+                }
+            }
+        }
+        fast = __ballot(clash) == 0ull;
+    }
+    if (fast) {
+        const u64 dm = __ballot(dupb);            // dropped entries of B, by position
+        const u64 below_b = less_in_b >= 64 ? ~0ull : ((1ull << less_in_b) - 1ull);
+        rank[0] = lane + less_in_b - __popcll(dm & below_b);
+        rank[1] = lane + less_in_a - __popcll(dm & lanemask_lt());
+        if (dupb) key[1] = EMPTY_KEY;
+    } else {
+        merge_general(key, ka, kb, lane, rank);
     }
     const int total = __popcll(__ballot(key[0] != EMPTY_KEY)) + __popcll(__ballot(key[1] != EMPTY_KEY));
 #pragma unroll

@@ -343,6 +343,34 @@ def test_merge_rows_bit_exact_against_the_oracle(n, ka, kb, ko, nid):
     assert np.array_equal(gd.cpu().numpy().view(np.uint32), od.view(np.uint32))
 
 
+def test_merge_rows_of_sorted_graph_rows_with_shared_entries():
+    # what graphs and searches hand over: each list ascending, padding at the end, an id in both
+    # lists with one distance; a few rows break each assumption and must still come out right
+    rng = np.random.default_rng(77)
+    n, ka, kb, ko = 3000, 32, 24, 32
+    ia = np.empty((n, ka), np.int32); da = np.empty((n, ka), np.float32)
+    ib = np.empty((n, kb), np.int32); db = np.empty((n, kb), np.float32)
+    for i in range(n):
+        pool = rng.choice(5000, 48, replace=False)
+        dist = {int(p): np.float32(rng.integers(0, 40) * 0.5) for p in pool}     # ties in distance
+        a = sorted(((dist[int(p)], int(p)) for p in pool[:ka]))
+        b = sorted(((dist[int(p)], int(p)) for p in pool[ka - 8:ka - 8 + kb]))   # 8 shared ids
+        ia[i] = [t[1] for t in a]; da[i] = [t[0] for t in a]
+        ib[i] = [t[1] for t in b]; db[i] = [t[0] for t in b]
+        if i % 7 == 3:                                   # padding at the end of B
+            ib[i, -5:] = -1
+        if i % 50 == 11:                                 # an id in both lists with two distances
+            ib[i, 0] = ia[i, 20]; db[i, 0] = 0.0
+        if i % 50 == 12:                                 # an unordered list
+            ia[i, [3, 9]] = ia[i, [9, 3]]; da[i, [3, 9]] = da[i, [9, 3]]
+        if i % 50 == 13:                                 # a repeated id inside one list
+            ia[i, 5] = ia[i, 4]
+    oi, od = oracle.merge_rows(ia, da, ib, db, ko)
+    gi, gd = knng.knng_merge_graphs(_gpu(ia), _gpu(da), _gpu(ib), _gpu(db), ko)
+    assert np.array_equal(gi.cpu().numpy(), oi)
+    assert np.array_equal(gd.cpu().numpy().view(np.uint32), od.view(np.uint32))
+
+
 def test_merge_rows_argument_errors():
     z_i = torch.zeros((4, 3), dtype=torch.int32, device=DEV)
     z_d = torch.zeros((4, 3), dtype=torch.float32, device=DEV)
