@@ -11,6 +11,15 @@
 // ids, filtered against the query's current k-th key and queued in LDS; one wavefront per 16
 // queries merges the queues into the sorted per-query lists by rank counting.
 // k_brute_reduce: merges the lists of the base ranges and writes ids / distances.
+//
+// k_brute_mfma (rows with d % 4 == 0): the same walk, but a tile is first screened with an fp32
+// Gram block on the matrix cores (v_mfma_f32_16x16x4_f32: |q|^2 + |b|^2 - 2<q,b>, or 1 - <q,b>).
+// The fp32 value differs from the true distance by at most E = (d + 16) 2^-23 (|q|^2 + |b|^2)
+// (more than twice the textbook bound of a length-d fp32 dot product plus the roundings around
+// it), so a pair whose screened value minus E lies above the query's current k-th distance cannot
+// enter the list and is skipped; every other pair is evaluated in the exact fp64 recipe, and only
+// exact values are ever stored or compared.  The result is the same bit for bit; after the first
+// tiles almost every pair is skipped.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -159,6 +168,228 @@ k_brute(const float* __restrict__ pts, int64_t n, int d, int k,
     }
 }
 
+// |x_i|^2 of every point, fp64 sum rounded once (8 lanes per row)
+__global__ void __launch_bounds__(256)
+k_row_norms(const float* __restrict__ pts, int64_t n, int d, float* __restrict__ nrm)
+{
+    const int sub = threadIdx.x & 7;
+    const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 3;
+    double acc = 0.0;
+    if (row < n)
+        for (int t = sub; t < d; t += 8) { const double x = (double)pts[row * d + t]; acc = fma(x, x, acc); }
+    acc += __shfl_xor(acc, 1);
+    acc += __shfl_xor(acc, 2);
+    acc += __shfl_xor(acc, 4);
+    if (row < n && sub == 0) nrm[row] = (float)acc;
+}
+
+constexpr int MLD = BDC + 4;      // row stride of a row-major slab: conflict-free 16-byte reads
+
+constexpr int SQCAP = BT * BT + 256;   // survivor queue: one whole tile on top of what may wait
+
+template <int METRIC>
+__global__ void __launch_bounds__(256)
+k_brute_mfma(const float* __restrict__ pts, const float* __restrict__ nrm, int64_t n, int d, int k,
+             const int32_t* __restrict__ query_rows, int64_t nq, int64_t base_chunk, int nsplit,
+             u64* __restrict__ part)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float* QS = reinterpret_cast<float*>(smem);            // [BT][MLD] query slab
+    float* BS = QS + BT * MLD;                             // [BT][MLD] base slab
+    u64* sq = reinterpret_cast<u64*>(BS + BT * MLD);       // [SQCAP] survivors of the screen: query << 32 | base id
+    u64* list = sq + SQCAP;                                // [BT][k] ascending
+    u64* thr = list + BT * k;                              // [BT] current k-th key
+    u64* rk = thr + BT;                                    // [256] exact keys of one round (EMPTY: not better)
+    int* rq = reinterpret_cast<int*>(rk + 256);            // [256] their queries
+    int* qrow = rq + 256;                                  // [BT] source point of each query
+    float* qn = reinterpret_cast<float*>(qrow + BT);       // [BT] |q|^2
+    float* bn = qn + BT;                                   // [BT] |b|^2 of the current tile
+    float* thrd = bn + BT;                                 // [BT] k-th distance, +inf while the list is short
+    int* qcount = reinterpret_cast<int*>(thrd + BT);       // survivors waiting in sq
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int r16 = lane & 15, kq = lane >> 4;
+    const int64_t q0 = (int64_t)blockIdx.x * BT;
+    const int64_t b_begin = (int64_t)blockIdx.y * base_chunk;
+    const int64_t b_end = (b_begin + base_chunk) < n ? (b_begin + base_chunk) : n;
+    const float inf = __uint_as_float(0x7f800000u);
+    const float epsd = (float)(d + 16) * 1.1920929e-7f;    // (d + 16) 2^-23
+
+    if (tid < BT) {
+        const int64_t q = q0 + tid;
+        int r = -1;
+        if (q < nq) r = query_rows ? query_rows[q] : (int)q;
+        qrow[tid] = r;
+        qn[tid] = r >= 0 ? nrm[r] : 0.0f;
+        thr[tid] = EMPTY_KEY;
+        thrd[tid] = inf;
+    }
+    if (tid == 0) *qcount = 0;
+    for (int i = tid; i < BT * k; i += 256) list[i] = EMPTY_KEY;
+    __syncthreads();
+
+    // The slabs are software-pipelined: while the matrix cores work on one slab, the 16-byte
+    // pieces of the next one (the next 32 coordinates, or the first 32 of the next base tile) are
+    // in flight into registers.
+    const int srow = tid >> 3, spc = tid & 7;              // staging: rows srow and srow + 32, piece spc
+    const int sq0 = qrow[srow], sq1 = qrow[srow + 32];
+    float4 pq[2], pb[2];
+    auto issue = [&](int64_t b0, int k0) {
+        const int t = k0 + 4 * spc;
+        pq[0] = pq[1] = pb[0] = pb[1] = float4{0, 0, 0, 0};
+        if (t < d) {
+            if (sq0 >= 0) pq[0] = *reinterpret_cast<const float4*>(pts + (int64_t)sq0 * d + t);
+            if (sq1 >= 0) pq[1] = *reinterpret_cast<const float4*>(pts + (int64_t)sq1 * d + t);
+            if (b0 + srow < b_end) pb[0] = *reinterpret_cast<const float4*>(pts + (b0 + srow) * d + t);
+            if (b0 + srow + 32 < b_end) pb[1] = *reinterpret_cast<const float4*>(pts + (b0 + srow + 32) * d + t);
+        }
+    };
+    if (b_begin < b_end) issue(b_begin, 0);
+
+    for (int64_t b0 = b_begin; b0 < b_end; b0 += BT) {
+        floatx4 acc[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] = floatx4{0, 0, 0, 0};
+        for (int k0 = 0; k0 < d; k0 += BDC) {
+            __syncthreads();                               // the previous slab has been multiplied
+            if (k0 == 0 && tid < BT) bn[tid] = (b0 + tid < b_end) ? nrm[b0 + tid] : 0.0f;
+            *reinterpret_cast<float4*>(QS + srow * MLD + 4 * spc) = pq[0];
+            *reinterpret_cast<float4*>(QS + (srow + 32) * MLD + 4 * spc) = pq[1];
+            *reinterpret_cast<float4*>(BS + srow * MLD + 4 * spc) = pb[0];
+            *reinterpret_cast<float4*>(BS + (srow + 32) * MLD + 4 * spc) = pb[1];
+            __syncthreads();
+            if (k0 + BDC < d) issue(b0, k0 + BDC);
+            else if (b0 + BT < b_end) issue(b0 + BT, 0);
+#pragma unroll
+            for (int kk = 0; kk < BDC; kk += 16) {
+                const float4 a = *reinterpret_cast<const float4*>(QS + (16 * w + r16) * MLD + 4 * kq + kk);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float4 b = *reinterpret_cast<const float4*>(BS + (16 * c + r16) * MLD + 4 * kq + kk);
+                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc[c], 0, 0, 0);
+                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc[c], 0, 0, 0);
+                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc[c], 0, 0, 0);
+                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc[c], 0, 0, 0);
+                }
+            }
+        }
+        // lane (r16, kq) holds <q, b> for queries 16w + 4kq + r and base points b0 + 16c + r16.
+        // Screen: pairs the bound cannot rule out are queued (one LDS counter bump per vote).
+        {
+            float na[4], td[4];
+            int qrr[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int qi = 16 * w + 4 * kq + r;
+                na[r] = qn[qi]; td[r] = thrd[qi] * 1.000001f; qrr[r] = qrow[qi];
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int64_t b = b0 + 16 * c + r16;
+                const float nb = bn[16 * c + r16];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float l, e;
+                    if (METRIC == 0) { l = na[r] + nb - 2.0f * acc[c][r]; e = epsd * (na[r] + nb); }
+                    else { l = 1.0f - acc[c][r]; e = epsd * (0.5f * (na[r] + nb) + 1.0f); }
+                    const bool pass = qrr[r] >= 0 && b < b_end && b != (int64_t)qrr[r] && !(l - e > td[r]);
+                    const u64 m = __ballot(pass);
+                    if (m != 0ull) {
+                        int base = 0;
+                        if (lane == 0) base = atomicAdd(qcount, __popcll(m));
+                        base = (int)bcast32((uint32_t)base, 0);
+                        if (pass)
+                            sq[base + __popcll(m & lanemask_lt())] =
+                                ((u64)(uint32_t)(16 * w + 4 * kq + r) << 32) | (uint32_t)b;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        // The queued pairs get their exact distance once enough of them wait (or the range ends):
+        // 256 at a time, one per thread; then each wavefront folds the ones of its 16 queries into
+        // their lists.
+        const int waiting = *qcount;
+        if (waiting > 256 || (waiting > 0 && b0 + BT >= b_end)) {
+            for (int base = 0; base < waiting; base += 256) {
+                u64 key = EMPTY_KEY;
+                int qi = -1;
+                if (base + tid < waiting) {
+                    const u64 ent = sq[base + tid];
+                    qi = (int)(ent >> 32);
+                    const int64_t b = (int64_t)(uint32_t)ent;
+                    const float* xq = pts + (int64_t)qrow[qi] * d;
+                    const float* xb = pts + b * d;
+                    double sacc = 0.0;
+                    int t = 0;
+                    for (; t + 16 <= d; t += 16) {
+                        float4 x[4], y[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            x[u] = *reinterpret_cast<const float4*>(xq + t + 4 * u);
+                            y[u] = *reinterpret_cast<const float4*>(xb + t + 4 * u);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            sacc = exact_step<METRIC>(sacc, x[u].x, y[u].x);
+                            sacc = exact_step<METRIC>(sacc, x[u].y, y[u].y);
+                            sacc = exact_step<METRIC>(sacc, x[u].z, y[u].z);
+                            sacc = exact_step<METRIC>(sacc, x[u].w, y[u].w);
+                        }
+                    }
+                    for (; t < d; t += 4) {
+                        const float4 x = *reinterpret_cast<const float4*>(xq + t);
+                        const float4 y = *reinterpret_cast<const float4*>(xb + t);
+                        sacc = exact_step<METRIC>(sacc, x.x, y.x);
+                        sacc = exact_step<METRIC>(sacc, x.y, y.y);
+                        sacc = exact_step<METRIC>(sacc, x.z, y.z);
+                        sacc = exact_step<METRIC>(sacc, x.w, y.w);
+                    }
+                    key = pack_key(exact_finish<METRIC>(sacc), (int)b, 0);
+                    if (!(key < thr[qi])) key = EMPTY_KEY;
+                }
+                rk[tid] = key;
+                rq[tid] = qi;
+                __syncthreads();
+                for (int qq = 0; qq < 16; ++qq) {          // wavefront w owns queries 16w .. 16w+15
+                    const int mq = 16 * w + qq;
+                    for (int ch = 0; ch < 4; ++ch) {       // the round's keys, 64 at a time
+                        const u64 ck = rq[64 * ch + lane] == mq ? rk[64 * ch + lane] : EMPTY_KEY;
+                        const u64 cm = __ballot(ck != EMPTY_KEY);
+                        if (cm == 0ull) continue;
+                        const u64 lk = lane < k ? list[mq * k + lane] : EMPTY_KEY;
+                        int rl = lane, rc = 0;
+                        for (u64 mm = cm; mm; mm &= mm - 1) {
+                            const u64 cj = bcast64(ck, __ffsll((long long)mm) - 1);
+                            rl += (cj < lk) ? 1 : 0;
+                            rc += (cj < ck) ? 1 : 0;
+                        }
+                        for (int i = 0; i < k; ++i) rc += (bcast64(lk, i) < ck) ? 1 : 0;
+                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                        if (lane < k && rl < k) list[mq * k + rl] = lk;
+                        if (ck != EMPTY_KEY && rc < k) list[mq * k + rc] = ck;
+                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    }
+                    if (lane == 0) {
+                        const u64 t = list[mq * k + (k - 1)];
+                        thr[mq] = t;
+                        thrd[mq] = t == EMPTY_KEY ? inf : key_dist(t);
+                    }
+                }
+                __syncthreads();
+            }
+            if (tid == 0) *qcount = 0;
+            __syncthreads();
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < BT * k; i += 256) {
+        const int qi = i / k, e = i - qi * k;
+        const int64_t q = q0 + qi;
+        if (q < nq) part[(q * nsplit + blockIdx.y) * k + e] = list[i];
+    }
+}
+
 // one wavefront per query: fold the nsplit sorted partial lists, write ids and distances
 __global__ void __launch_bounds__(256)
 k_brute_reduce(int64_t nq, int k, int nsplit, const u64* __restrict__ part,
@@ -213,8 +444,9 @@ using namespace knng;
 extern "C" __attribute__((visibility("default"))) uint64_t knng_brute_workspace_bytes(int64_t n, int32_t d, int32_t k, int64_t nq)
 {
     if (n < 2 || d < 1 || k < 1 || k > KNNG_MAX_K || (int64_t)k > n - 1 || nq < 0) return 0;
-    const uint64_t b = (uint64_t)nq * (uint64_t)brute_nsplit(n, nq) * (uint64_t)k * 8u;
-    return b < 256 ? 256 : b;
+    uint64_t b = (uint64_t)nq * (uint64_t)brute_nsplit(n, nq) * (uint64_t)k * 8u;
+    b = (b + 255u) & ~255ull;                     // partial lists, then |x|^2 of every point
+    return b + (((uint64_t)n * 4u + 255u) & ~255ull);
 }
 
 extern "C" __attribute__((visibility("default"))) int knng_brute_knn(const float* points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,
@@ -239,7 +471,27 @@ extern "C" __attribute__((visibility("default"))) int knng_brute_knn(const float
     const int lds = 2 * BDC * BLD * 4 + BT * BT * 8 + BT * k * 8 + BT * 8 + BT * 4 + BT * 4;
     u64* part = static_cast<u64*>(workspace_dev);
     hipError_t e;
-    if (metric == 0) {
+    const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(points_dev) & 15u) == 0);
+    if (vec) {
+        const uint64_t part_bytes = ((uint64_t)nq * (uint64_t)nsplit * (uint64_t)k * 8u + 255u) & ~255ull;
+        float* nrm = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace_dev) + part_bytes);
+        hipLaunchKernelGGL(k_row_norms, dim3((unsigned)((n * 8 + 255) / 256)), dim3(256), 0, st, points_dev, n, d, nrm);
+        if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e, "k_row_norms launch");
+        const int mlds = 2 * BT * MLD * 4 + SQCAP * 8 + BT * k * 8 + BT * 8 + 256 * 8 + 256 * 4 + 4 * BT * 4 + 16;
+        if (metric == 0) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_brute_mfma<0>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, mlds);
+            if (e != hipSuccess) return set_hip_error(e, "hipFuncSetAttribute(k_brute_mfma)");
+            hipLaunchKernelGGL(k_brute_mfma<0>, dim3(qtiles, (unsigned)nsplit), dim3(256), mlds, st, points_dev, nrm,
+                               n, d, k, query_rows_dev, nq, chunk, nsplit, part);
+        } else {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_brute_mfma<1>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, mlds);
+            if (e != hipSuccess) return set_hip_error(e, "hipFuncSetAttribute(k_brute_mfma)");
+            hipLaunchKernelGGL(k_brute_mfma<1>, dim3(qtiles, (unsigned)nsplit), dim3(256), mlds, st, points_dev, nrm,
+                               n, d, k, query_rows_dev, nq, chunk, nsplit, part);
+        }
+    } else if (metric == 0) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_brute<0>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return set_hip_error(e, "hipFuncSetAttribute(k_brute)");

@@ -63,6 +63,22 @@ def test_brute_ties_are_broken_by_id():
     assert np.array_equal(gi, oi) and np.array_equal(gd, od)
 
 
+def test_brute_far_from_the_origin_and_near_duplicates():
+    # norms dwarf the distances: the fp32 screen cannot rule anything out and everything falls
+    # through to the exact recipe; and clouds of near-duplicates, where fp32 Gram values cancel
+    rng = np.random.default_rng(3)
+    x = (1000.0 + rng.standard_normal((1500, 16)) * 0.01).astype(np.float32)
+    gi, gd, oi, od = _brute_both(x, 10, 0)
+    assert np.array_equal(gi, oi) and np.array_equal(gd.view(np.uint32), od.view(np.uint32))
+    c = rng.standard_normal((30, 64)).astype(np.float32) * 50.0
+    y = (c[rng.integers(0, 30, 3000)] + rng.standard_normal((3000, 64)).astype(np.float32) * 1e-3).astype(np.float32)
+    gi, gd, oi, od = _brute_both(y, 24, 0)
+    assert np.array_equal(gi, oi) and np.array_equal(gd.view(np.uint32), od.view(np.uint32))
+    u = (y / np.linalg.norm(y, axis=1, keepdims=True)).astype(np.float32)
+    gi, gd, oi, od = _brute_both(u, 24, 1)
+    assert np.array_equal(gi, oi) and np.array_equal(gd.view(np.uint32), od.view(np.uint32))
+
+
 def test_brute_integer_valued_data_config1_shape():
     x, w = workloads.make(1, n=30_000)                     # many exact ties at integer distances
     rows = workloads.sample_rows(30_000, 1500)
