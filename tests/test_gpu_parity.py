@@ -38,7 +38,8 @@ def test_brute_config0_full_bit_exact():
 
 @pytest.mark.parametrize("n,d,k,metric", [
     (2, 1, 1, 0), (65, 3, 64, 0), (130, 33, 7, 0), (1000, 128, 32, 0), (4133, 96, 32, 1),
-    (777, 50, 20, 1), (300, 960, 16, 0), (129, 4, 1, 0)])
+    (777, 50, 20, 1), (300, 960, 16, 0), (129, 4, 1, 0), (200, 8, 64, 0), (5000, 4, 64, 1),
+    (66, 12, 65 - 1, 0)])
 def test_brute_ragged_shapes_bit_exact(n, d, k, metric):
     rng = np.random.default_rng(n * 131 + d)
     x = rng.standard_normal((n, d)).astype(np.float32)
