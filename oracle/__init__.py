@@ -41,6 +41,8 @@ def lib():
 
 
 def _f32(a):
+    # Compact element types (uint8 / float16 point storage) are taken at their values: both
+    # convert to fp32 without rounding, so the functions below define the result for them too.
     a = np.ascontiguousarray(a, dtype=np.float32)
     return a
 

@@ -60,6 +60,30 @@ def test_distance_integer_data_is_exact():
         assert float(got) == float(want)
 
 
+def test_uint8_points_are_taken_at_their_values_with_one_final_rounding():
+    # integer enumeration in int64, independent of the oracle: ids by (distance, id), distances
+    # the exact integer rounded once to fp32 (d = 960 puts them above 2^24)
+    rng = np.random.default_rng(12)
+    for n, d, k in [(300, 128, 8), (60, 960, 59)]:
+        x = rng.integers(0, 256, (n, d), dtype=np.uint8)
+        if d == 960:                                       # two far groups: cross distances > 2^24
+            x[: n // 2] = x[: n // 2] // 5
+            x[n // 2:] = 204 + x[n // 2:] // 5
+        if d == 128:
+            x[17] = x[3]                                   # a duplicate: distance 0, tie on the id
+        xi = x.astype(np.int64)
+        ids, dists = oracle.brute_knn(x, k, oracle.L2SQ)
+        big = False
+        for v in range(n):
+            dd = ((xi - xi[v]) ** 2).sum(axis=1)
+            order = sorted((int(dd[u]), u) for u in range(n) if u != v)[:k]
+            assert [u for _, u in order] == ids[v].tolist()
+            assert [np.float32(np.float64(l)) for l, _ in order] == dists[v].tolist()
+            big = big or order[-1][0] > 2 ** 24
+        assert big == (d == 960)
+    assert oracle.distance(x[0], x[1], oracle.L2SQ) == np.float32(np.float64(((xi[0] - xi[1]) ** 2).sum()))
+
+
 def test_distance_is_asymmetric_in_nothing_and_clamps():
     a = np.array([1.0, 0.5, 0.0], np.float32)
     b = np.array([1.0, 0.5, 0.25], np.float32)
