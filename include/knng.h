@@ -115,6 +115,21 @@ uint64_t knng_build_workspace_bytes(int64_t n, int32_t d, int32_t k, const knng_
 int knng_build_knn_graph(const float *points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,
                          const knng_params_t *params, int32_t *ids_out_dev, float *dists_out_dev);
 
+/*
+ * The same build for points stored as uint8 (Sec. 5.2, dataset table: the SIFT sets the paper scales
+ * to are 8-bit; a quarter of the bytes the joins gather).  points_dev [n][d] uint8
+ * (device, read-only, 4-byte aligned; rows are 16-byte pieces when d % 16 == 0 and
+ * the pointer is 16-byte aligned, else 4-byte words).  The values are taken as they
+ * are: every distance is the exact integer sum of squared differences, rounded once
+ * to fp32, which is what the fp64 recipe gives on the same values stored as fp32 --
+ * the result obeys the same definition as knng_build_knn_graph on that fp32 copy.
+ * Workspace: knng_build_workspace_bytes (the same).  Everything else as above.
+ * Additional KNNG_EINVAL cases: metric other than KNNG_METRIC_L2SQ, d % 4 != 0,
+ * d > 65536 (32-bit integer sums), pointer not 4-byte aligned.
+ */
+int knng_build_knn_graph_u8(const uint8_t *points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,
+                            const knng_params_t *params, int32_t *ids_out_dev, float *dists_out_dev);
+
 /* Device scratch needed by knng_brute_knn (0 on bad arguments). */
 uint64_t knng_brute_workspace_bytes(int64_t n, int32_t d, int32_t k, int64_t nq);
 

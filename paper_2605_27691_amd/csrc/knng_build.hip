@@ -62,6 +62,39 @@ __device__ __forceinline__ float dist_group8(const float* __restrict__ a, const 
 }
 
 // ------------------------------------------------------------------------------------------
+// uint8 rows (squared L2): sum of (a_i - b_i)^2 over four packed bytes as a.a + b.b - 2 a.b with
+// unsigned dot products.  Sums are exact in 32 bits for d <= 65536 (65536 * 255^2 < 2^32).
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t sqdiff4_u8(uint32_t a, uint32_t b)
+{
+    const uint32_t nn = __builtin_amdgcn_udot4(a, a, __builtin_amdgcn_udot4(b, b, 0u, false), false);
+    return nn - 2u * __builtin_amdgcn_udot4(a, b, 0u, false);
+}
+__device__ __forceinline__ uint32_t sqdiff16_u8(uint4 a, uint4 b)
+{
+    return sqdiff4_u8(a.x, b.x) + sqdiff4_u8(a.y, b.y) + sqdiff4_u8(a.z, b.z) + sqdiff4_u8(a.w, b.w);
+}
+// distance by a group of 8 lanes, as dist_group8; d % 4 == 0, rows 4-byte aligned
+__device__ __forceinline__ float dist_group8_u8(const unsigned char* __restrict__ a,
+                                                const unsigned char* __restrict__ b, int d, int sub)
+{
+    uint32_t acc = 0u;
+    if ((d & 15) == 0) {
+        const uint4* a4 = reinterpret_cast<const uint4*>(a);
+        const uint4* b4 = reinterpret_cast<const uint4*>(b);
+        for (int t = sub; t < (d >> 4); t += 8) acc += sqdiff16_u8(a4[t], b4[t]);
+    } else {
+        const uint32_t* a1 = reinterpret_cast<const uint32_t*>(a);
+        const uint32_t* b1 = reinterpret_cast<const uint32_t*>(b);
+        for (int t = sub; t < (d >> 2); t += 8) acc += sqdiff4_u8(a1[t], b1[t]);
+    }
+    acc += (uint32_t)__shfl_xor((int)acc, 1);
+    acc += (uint32_t)__shfl_xor((int)acc, 2);
+    acc += (uint32_t)__shfl_xor((int)acc, 4);
+    return (float)acc;
+}
+
+// ------------------------------------------------------------------------------------------
 // Row signature: a 256-bit Bloom-style set of the ids in a point's row (bit hash(id) & 255).
 // The join uses it to skip partners a member most likely already holds: such offers would be
 // rejected by the merge anyway, cost an atomic each, and would shadow real candidates in the
@@ -90,7 +123,8 @@ constexpr uint32_t EMPTY_REV = 0xffffffffu;            // an empty reverse bucke
 // with bad entries redrawn), their distances, row sorted by (distance, id), all flagged new.
 // Also puts the point's candidate slots, counters and threshold into their start state.
 // ------------------------------------------------------------------------------------------
-template <int METRIC>
+// ELEM 1: pts points at uint8 rows of d bytes.
+template <int METRIC, int ELEM>
 __global__ void __launch_bounds__(256)
 k_init(const float* __restrict__ pts, int64_t n, int d, int K, int C, u64 seed,
        const int32_t* __restrict__ init_ids, u64* __restrict__ G, u64* __restrict__ cand,
@@ -139,7 +173,13 @@ k_init(const float* __restrict__ pts, int64_t n, int d, int K, int C, u64 seed,
     for (int pass = 0; pass * 8 < K; ++pass) {
         int e = pass * 8 + grp;
         int uid = __shfl(id, e < K ? e : 0);
-        float val = dist_group8<METRIC>(xv, pts + (int64_t)uid * d, d, sub);
+        float val;
+        if constexpr (ELEM == 1) {
+            const unsigned char* p8 = reinterpret_cast<const unsigned char*>(pts);
+            val = dist_group8_u8(p8 + v * (int64_t)d, p8 + (int64_t)uid * d, d, sub);
+        } else {
+            val = dist_group8<METRIC>(xv, pts + (int64_t)uid * d, d, sub);
+        }
         float mine = __shfl(val, (lane & 7) * 8);
         if ((lane >> 3) == pass) dist = mine;
     }
@@ -440,7 +480,7 @@ k_plan(int64_t n, int s, int B, u64 seed, uint32_t iter, const uint32_t* __restr
 #endif
 constexpr int OFFERS_PER_MEMBER = KNNG_OFFERS_PER_MEMBER;
 
-template <int S16, int DS_> struct JoinCfg {
+template <int S16, int DS_, int ELEM = 0> struct JoinCfg {
     static constexpr int MROWS = 16 * S16;            // max |NEW|
     static constexpr int NCOLS = 32 * S16;            // max |NEW| + |OLD|
     static constexpr int DS = DS_;
@@ -449,7 +489,9 @@ template <int S16, int DS_> struct JoinCfg {
     static constexpr int NT = (3 * S16 * S16 + 3 * S16 + 7) / 8; // 16x16 tiles per wavefront (upper bound)
     static constexpr int NL = NCOLS * (DS / 4) / 256; // 16-byte pieces a thread gathers per slab
     static constexpr int XBYTES = NCOLS * LD * 4 > MROWS * LDD * 4 ? NCOLS * LD * 4 : MROWS * LDD * 4;
-    static constexpr int LDS_BYTES = XBYTES + NCOLS * (8 + 8 + 8 + 4 * SIG_WORDS) + 16 + 4 * SIG_WORDS;
+    // ELEM 1 (uint8 rows): + the pivot's row and a row of zeros [2][LD], pivot distances [NCOLS]
+    static constexpr int LDS_BYTES = XBYTES + NCOLS * (8 + 8 + 8 + 4 * SIG_WORDS) + 16 + 4 * SIG_WORDS +
+                                     (ELEM ? 2 * LD * 4 + NCOLS * 4 : 0);
 };
 
 // 16-byte piece [t, t+4) of a row, zero beyond d.  VEC: d % 4 == 0 and rows 16-byte aligned, so
@@ -526,7 +568,10 @@ __device__ __forceinline__ int member_of_slot(int t, int s, int4 c)
     return -1;
 }
 
-template <int METRIC, int S16, int DS_, bool VEC>
+// ELEM 1: uint8 rows handled as d 32-bit words, signed bytes x - 128 in LDS, integer Gram tiles
+// (v_mfma_i32_16x16x64_i8) -- see knng_join_wave.h; here wavefront w also owns the products of
+// the pivot with the member tiles w, w + 4, ... (one accumulator, a column per tile).
+template <int METRIC, int S16, int DS_, bool VEC, int ELEM = 0>
 __global__ void __launch_bounds__(256)
 k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
        const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl, const int4* __restrict__ plan,
@@ -534,17 +579,23 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
        const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand,
        u64* __restrict__ offers_ctr)
 {
-    using Cfg = JoinCfg<S16, DS_>;
+    static_assert(ELEM == 0 || METRIC == 0, "uint8 rows: squared L2 only");
+    using Cfg = JoinCfg<S16, DS_, ELEM>;
+    using accv = typename std::conditional<ELEM == 1, intx4, floatx4>::type;
     uint32_t n_offers = 0;                                     // this thread's, summed per wavefront at exit
     constexpr int DS = Cfg::DS, LD = Cfg::LD, LDD = Cfg::LDD, NT = Cfg::NT, NL = Cfg::NL, NCOLS = Cfg::NCOLS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float* X = reinterpret_cast<float*>(smem);                 // [NCOLS][LD], later D [MROWS][LDD]
     int* midbuf = reinterpret_cast<int*>(smem + Cfg::XBYTES);  // [2][NCOLS] member ids, double-buffered
     int2* mh = reinterpret_cast<int2*>(midbuf + 2 * NCOLS);    // [NCOLS] {member id, its signature bit}
-    float* nrm = reinterpret_cast<float*>(mh + NCOLS);         // [NCOLS] |x_m - x_v|^2
-    float* thr = nrm + NCOLS;                                  // [NCOLS] farthest-neighbour distance
+    // [NCOLS] bits of |x_m - x_v|^2 (fp32); ELEM 1: of |x_m - 128|^2 (integer)
+    uint32_t* nrm = reinterpret_cast<uint32_t*>(mh + NCOLS);
+    float* thr = reinterpret_cast<float*>(nrm + NCOLS);        // [NCOLS] farthest-neighbour distance
     uint32_t* sg = reinterpret_cast<uint32_t*>(thr + NCOLS);   // [NCOLS + 1][SIG_WORDS] row signatures
-    float* thr_v = reinterpret_cast<float*>(sg + (NCOLS + 1) * SIG_WORDS);  // [4] the pivot's threshold
+    float* thr_v = reinterpret_cast<float*>(sg + (NCOLS + 1) * SIG_WORDS);  // [0] the pivot's threshold, [1] ELEM 1: its norm
+    float* PZ = thr_v + 4;                                     // ELEM 1: [2][LD] pivot row, zeros
+    float* dpv = PZ + 2 * LD;                                  // ELEM 1: [NCOLS] |x_m - x_v|^2
+    if (ELEM == 1 && threadIdx.x < LD) PZ[LD + threadIdx.x] = 0.0f;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);    // wavefront index, kept scalar
@@ -630,11 +681,12 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
         const int nrt = (nNew + 15) >> 4, nct = (nTot + 15) >> 4;
         const int ntm = nrt * nct - nrt * (nrt - 1) / 2;
         const int ntiles = ntm + (nct - nrt);
-        floatx4 acc[NT];
+        accv acc[NT];
+        intx4 accp = intx4{0, 0, 0, 0};                     // ELEM 1: <member, pivot> of this wavefront's tiles
         int trow[NT], tcol[NT];
 #pragma unroll
         for (int q = 0; q < NT; ++q) {
-            acc[q] = floatx4{0, 0, 0, 0};
+            acc[q] = accv{0, 0, 0, 0};
             int rem = w + 4 * q, rt = 0;
             if (rem < ntm) {
                 while (rem >= nct - rt) { rem -= nct - rt; ++rt; }
@@ -644,6 +696,13 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             } else { trow[q] = -1; tcol[q] = 0; }
         }
         PointPlan Pn = make_point(rc_n);
+        // uint8 -> signed bytes x - 128; words past the end of the row stay zero
+        auto enc_u8 = [&](float4 f, int t0) -> float4 {
+            uint32_t wd[4] = {__float_as_uint(f.x), __float_as_uint(f.y), __float_as_uint(f.z), __float_as_uint(f.w)};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wd[j] = (VEC || t0 + j < d) ? (wd[j] ^ 0x80808080u) : 0u;
+            return float4{__uint_as_float(wd[0]), __uint_as_float(wd[1]), __uint_as_float(wd[2]), __uint_as_float(wd[3])};
+        };
 
         for (int k0 = 0; k0 < d; k0 += DS) {
             const bool first = k0 == 0, last = k0 + DS >= d;
@@ -670,10 +729,16 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 for (int i = 0; i < NL; ++i) {
                     if (i * sm.RP < nTot) {                     // uniform: the group was loaded
                         float4 x = buf[i];
-                        x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w;
+                        if (ELEM == 1) x = enc_u8(x, k0 + 4 * sm.c4);
+                        else { x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w; }
                         if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
                         if (sm.rsub + i * sm.RP < nTot) *reinterpret_cast<float4*>(xdst + i * sm.RP * LD) = x;
                     }
+                }
+                if (ELEM == 1 && sm.rsub == 0) {                // the pivot's own row
+                    float4 x = enc_u8(pv, k0 + 4 * sm.c4);
+                    if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
+                    *reinterpret_cast<float4*>(PZ + 4 * sm.c4) = x;
                 }
             }
             if (last && v_nx >= 0) {                       // next point's member ids
@@ -699,12 +764,33 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                     const float* xa = X + (trow[q] * 16 + r16) * LD + 4 * kq;
                     const float* xb = X + (tcol[q] * 16 + r16) * LD + 4 * kq;
                     for (int kk = 0; kk < sm.len16; kk += 16) {
-                        const float4 a = *reinterpret_cast<const float4*>(xa + kk);
-                        const float4 b = *reinterpret_cast<const float4*>(xb + kk);
-                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc[q], 0, 0, 0);
-                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc[q], 0, 0, 0);
-                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc[q], 0, 0, 0);
-                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc[q], 0, 0, 0);
+                        if constexpr (ELEM == 1) {
+                            const intx4 a = *reinterpret_cast<const intx4*>(xa + kk);
+                            const intx4 b = *reinterpret_cast<const intx4*>(xb + kk);
+                            acc[q] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[q], 0, 0, 0);
+                        } else {
+                            const float4 a = *reinterpret_cast<const float4*>(xa + kk);
+                            const float4 b = *reinterpret_cast<const float4*>(xb + kk);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc[q], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+            if constexpr (ELEM == 1) {
+                // column c of accp: member tile w + 4c against the pivot; wavefront 0, column 4:
+                // the pivot against itself
+#pragma unroll
+                for (int c = 0; c < 5; ++c) {
+                    const int ct = w + 4 * c;
+                    if (c < 4 ? ct < nct : w == 0) {            // uniform
+                        const float* xa = c < 4 ? X + (ct * 16 + r16) * LD + 4 * kq : PZ + 4 * kq;
+                        const float* xb = PZ + (r16 == c ? 0 : LD) + 4 * kq;
+                        for (int kk = 0; kk < sm.len16; kk += 16)
+                            accp = __builtin_amdgcn_mfma_i32_16x16x64_i8(*reinterpret_cast<const intx4*>(xa + kk),
+                                                                         *reinterpret_cast<const intx4*>(xb + kk), accp, 0, 0, 0);
                     }
                 }
             }
@@ -715,21 +801,22 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 for (int q = 0; q < NT; ++q) {
                     if (trow[q] >= 0 && trow[q] == tcol[q] && (r16 >> 2) == kq) {
                         const int e = r16 & 3;
-                        const float dv = e == 0 ? acc[q][0] : e == 1 ? acc[q][1] : e == 2 ? acc[q][2] : acc[q][3];
-                        nrm[trow[q] * 16 + r16] = dv;
+                        nrm[trow[q] * 16 + r16] = acc_bits(e == 0 ? acc[q][0] : e == 1 ? acc[q][1] : e == 2 ? acc[q][2] : acc[q][3]);
                     }
                 }
+                if (ELEM == 1 && w == 0 && lane == 4) thr_v[1] = __uint_as_float((uint32_t)accp[0]);
             }
             lds_barrier();                                 // slab consumed by every wavefront
         }
 
         // The pivot's reverse members hold v in their rows, so |x_m - x_v|^2 is already known:
         // offer them to v itself (closes v<-m edges into v->m without an extra distance).
-        if (tid < nTot) {
+        auto reverse_offers = [&]() {
+          if (tid < nTot) {
             const int m = tid;
             const bool rev = (m >= nfn && m < nNew) || (m >= nNew + nfo);
             if (rev) {
-                float l = nrm[m];
+                float l = ELEM == 1 ? dpv[m] : __uint_as_float(nrm[m]);
                 if (METRIC == 1) l *= 0.5f;
                 l = nonneg(l);
                 const int2 me = mh[m];
@@ -742,25 +829,48 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 }
             }
         }
+        };
+        if (ELEM == 0) reverse_offers();
         // distance block D[row][col] over the slab storage
         float* D = X;
 #pragma unroll
         for (int q = 0; q < NT; ++q) {
             if (trow[q] >= 0 && trow[q] < nrt) {           // norm-only diagonal tiles have no D rows
                 const int col = tcol[q] * 16 + r16;
-                const float nc = nrm[col];
-                const float4 nr = *reinterpret_cast<const float4*>(nrm + trow[q] * 16 + 4 * kq);
-                const float nra[4] = {nr.x, nr.y, nr.z, nr.w};
+                const uint32_t nc = nrm[col];
+                const uint4 nr = *reinterpret_cast<const uint4*>(nrm + trow[q] * 16 + 4 * kq);
+                const uint32_t nra[4] = {nr.x, nr.y, nr.z, nr.w};
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int row = trow[q] * 16 + 4 * kq + r;
-                    float l = nra[r] + nc - 2.0f * acc[q][r];
-                    if (METRIC == 1) l *= 0.5f;            // unit rows: 1 - <a,b> = |a-b|^2 / 2
-                    D[row * LDD + col] = nonneg(l);
+                    float l;
+                    if constexpr (ELEM == 1) {
+                        l = (float)(nra[r] + nc - 2u * (uint32_t)acc[q][r]);   // exact, >= 0
+                    } else {
+                        l = __uint_as_float(nra[r]) + __uint_as_float(nc) - 2.0f * acc[q][r];
+                        if (METRIC == 1) l *= 0.5f;        // unit rows: 1 - <a,b> = |a-b|^2 / 2
+                        l = nonneg(l);
+                    }
+                    D[row * LDD + col] = l;
                 }
             }
         }
+        if constexpr (ELEM == 1) {
+            // lane (c, kq), c < 4, holds <member 16 (w + 4c) + 4kq + r, pivot> in accp[r]
+            const int ct = w + 4 * r16;
+            if (r16 < 4 && ct < nct) {
+                const uint32_t npiv = __float_as_uint(thr_v[1]);
+                const uint4 nm = *reinterpret_cast<const uint4*>(nrm + ct * 16 + 4 * kq);
+                float4 o;
+                o.x = (float)(nm.x + npiv - 2u * (uint32_t)accp[0]);
+                o.y = (float)(nm.y + npiv - 2u * (uint32_t)accp[1]);
+                o.z = (float)(nm.z + npiv - 2u * (uint32_t)accp[2]);
+                o.w = (float)(nm.w + npiv - 2u * (uint32_t)accp[3]);
+                *reinterpret_cast<float4*>(dpv + ct * 16 + 4 * kq) = o;
+            }
+        }
         lds_barrier();
+        if (ELEM == 1) reverse_offers();
         // per-member candidates: LPM lanes per member, each lane scans the partners of one
         // residue class (partner index mod LPM) and offers the closest of its class that beats
         // the member's threshold and is not in the member's signature (branch-free scan)
@@ -813,7 +923,9 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
 // one row and rely on the caches for the rest of each line.  Rows are then ranked by
 // (distance, id) and the first k written as ids / distances.
 // ------------------------------------------------------------------------------------------
-template <int METRIC, bool VEC>
+// ELEM 1 (uint8 rows of d bytes): the sum of squared differences is an integer below 2^32,
+// evaluated exactly and rounded once to fp32 -- what the fp64 recipe gives on these values.
+template <int METRIC, bool VEC, int ELEM>
 __global__ void __launch_bounds__(256)
 k_finalize(const float* __restrict__ pts, int64_t n, int d, int K, int Kp, int k,
            const u64* __restrict__ G, int32_t* __restrict__ ids_out, float* __restrict__ dists_out)
@@ -825,6 +937,31 @@ k_finalize(const float* __restrict__ pts, int64_t n, int d, int K, int Kp, int k
     const int64_t vv = v < n ? v : n - 1;
     const u64 key = live ? G[vv * K + i] : EMPTY_KEY;
     const int id = live ? key_id(key) : (int)vv;
+    float dist;
+    if constexpr (ELEM == 1) {
+        const unsigned char* __restrict__ a = reinterpret_cast<const unsigned char*>(pts) + vv * d;
+        const unsigned char* __restrict__ b = reinterpret_cast<const unsigned char*>(pts) + (int64_t)id * d;
+        uint32_t acc = 0u;
+        if (VEC) {                                   // d % 16 == 0
+            int t = 0;
+            for (; t + 64 <= d; t += 64) {
+                uint4 av[4], bv[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    av[q] = *reinterpret_cast<const uint4*>(a + t + 16 * q);
+                    bv[q] = *reinterpret_cast<const uint4*>(b + t + 16 * q);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc += sqdiff16_u8(av[q], bv[q]);
+            }
+            for (; t < d; t += 16)
+                acc += sqdiff16_u8(*reinterpret_cast<const uint4*>(a + t), *reinterpret_cast<const uint4*>(b + t));
+        } else {                                     // d % 4 == 0
+            for (int t = 0; t < d; t += 4)
+                acc += sqdiff4_u8(*reinterpret_cast<const uint32_t*>(a + t), *reinterpret_cast<const uint32_t*>(b + t));
+        }
+        dist = (float)acc;
+    } else {
     const float* __restrict__ a = pts + vv * d;
     const float* __restrict__ b = pts + (int64_t)id * d;
     double acc = 0.0;
@@ -856,7 +993,8 @@ k_finalize(const float* __restrict__ pts, int64_t n, int d, int K, int Kp, int k
     } else {
         for (int t = 0; t < d; ++t) acc = exact_step<METRIC>(acc, a[t], b[t]);
     }
-    const float dist = exact_finish<METRIC>(acc);
+    dist = exact_finish<METRIC>(acc);
+    }
     const u64 fk = live ? pack_key(dist, id, 0) : EMPTY_KEY;
     int rank = 0;
     for (int j = 0; j < K; ++j) rank += ((u64)__shfl((unsigned long long)fk, sub * Kp + j) < fk) ? 1 : 0;
@@ -921,11 +1059,11 @@ struct JoinArgs {
     int num_cu; int64_t n;
 };
 
-template <int METRIC, int S16, int DS, bool VEC>
+template <int METRIC, int S16, int DS, bool VEC, int ELEM = 0>
 static hipError_t launch_join_k(hipStream_t st, const JoinArgs& a)
 {
-    const int lds = JoinCfg<S16, DS>::LDS_BYTES;
-    auto kern = k_join<METRIC, S16, DS, VEC>;
+    const int lds = JoinCfg<S16, DS, ELEM>::LDS_BYTES;
+    auto kern = k_join<METRIC, S16, DS, VEC, ELEM>;
     static int blocks_per_cu = 0;            // per instantiation: resident workgroups per CU
     if (blocks_per_cu == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -943,11 +1081,11 @@ static hipError_t launch_join_k(hipStream_t st, const JoinArgs& a)
     return hipGetLastError();
 }
 
-template <int METRIC, int S16, bool VEC>
+template <int METRIC, int S16, bool VEC, int ELEM = 0>
 static hipError_t launch_join_w(hipStream_t st, const JoinArgs& a)
 {
-    const int lds = 4 * WaveCfg<S16>::WBYTES;
-    auto kern = k_join_wave<METRIC, S16, VEC>;
+    const int lds = 4 * WaveCfg<S16, ELEM>::WBYTES;
+    auto kern = k_join_wave<METRIC, S16, VEC, ELEM>;
     static int blocks_per_cu = 0;            // per instantiation: resident workgroups per CU
     if (blocks_per_cu == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -963,6 +1101,15 @@ static hipError_t launch_join_w(hipStream_t st, const JoinArgs& a)
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a.pts, a.d, a.C, a.s, a.iter, a.newl,
                        a.oldl, a.plan, a.active, a.nactive, a.worst, a.sig, a.cand, a.offers);
     return hipGetLastError();
+}
+
+// uint8 rows, squared L2; a.d counts 32-bit words
+static hipError_t launch_join_u8(hipStream_t st, bool vec, int S16, const JoinArgs& a)
+{
+    if (S16 == 1) return vec ? launch_join_w<0, 1, true, 1>(st, a) : launch_join_w<0, 1, false, 1>(st, a);
+    if (S16 == 2) return vec ? launch_join_w<0, 2, true, 1>(st, a) : launch_join_w<0, 2, false, 1>(st, a);
+    if (S16 == 4) return vec ? launch_join_k<0, 4, 64, true, 1>(st, a) : launch_join_k<0, 4, 64, false, 1>(st, a);
+    return vec ? launch_join_k<0, 8, 32, true, 1>(st, a) : launch_join_k<0, 8, 32, false, 1>(st, a);
 }
 
 template <int METRIC>
@@ -998,14 +1145,21 @@ extern "C" __attribute__((visibility("default"))) uint64_t knng_build_workspace_
         if (e_ != hipSuccess) { rc = set_hip_error(e_, #expr); goto done; } \
     } while (0)
 
-extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const float* points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,
-                                    const knng_params_t* params, int32_t* ids_out_dev, float* dists_out_dev)
+// elem 0: fp32 rows; elem 1: uint8 rows (squared L2, d % 4 == 0, d <= 65536)
+static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, int32_t k, int32_t metric,
+                      const knng_params_t* params, int32_t* ids_out_dev, float* dists_out_dev)
 {
+    const float* points_dev = static_cast<const float*>(points_void);   // kernels cast back for elem 1
     if (!points_dev || !ids_out_dev || !dists_out_dev || !params) return KNNG_EINVAL;
     if (params->struct_size != sizeof(knng_params_t)) return KNNG_EINVAL;
     if (metric != KNNG_METRIC_L2SQ && metric != KNNG_METRIC_IP_UNIT) return KNNG_EINVAL;
     BuildPlan bp;
     if (!make_plan(n, d, k, params, &bp)) return KNNG_EINVAL;
+    if (elem == 1) {
+        if (metric != KNNG_METRIC_L2SQ || (d & 3) || d > 65536 ||
+            (reinterpret_cast<uintptr_t>(points_void) & 3u))
+            return KNNG_EINVAL;
+    }
     if (!params->workspace_dev || params->workspace_bytes < bp.total ||
         (reinterpret_cast<uintptr_t>(params->workspace_dev) & 255u))
         return KNNG_EWORKSPACE;
@@ -1024,7 +1178,7 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
     uint32_t* sig = reinterpret_cast<uint32_t*>(ws + bp.off_sig);
     u64* ctr = reinterpret_cast<u64*>(ws + bp.off_ctr);      // [0] updates [1] rows gathered [2] active [3] pairs [4] offers
     knng_stats_t* stats = params->stats_host;
-    const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(points_dev) & 15u) == 0);
+    const bool vec = (d % (elem == 1 ? 16 : 4) == 0) && ((reinterpret_cast<uintptr_t>(points_dev) & 15u) == 0);
     const unsigned row_blocks = (unsigned)((n + 3) / 4);
     unsigned upd_blocks = 0;                          // persistent k_update grid, set once num_cu is known
     const double stop_below = (double)bp.delta * (double)bp.K * (double)n;
@@ -1054,11 +1208,14 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
         HIPCHK(hipEventRecord(ev[0], st));
     }
     HIPCHK(hipMemsetAsync(ctr, 0, 256, st));
-    if (metric == 0)
-        hipLaunchKernelGGL(k_init<0>, dim3(row_blocks), dim3(256), 0, st, points_dev, n, d, bp.K, bp.C,
+    if (elem == 1)
+        hipLaunchKernelGGL((k_init<0, 1>), dim3(row_blocks), dim3(256), 0, st, points_dev, n, d, bp.K, bp.C,
+                           params->seed, params->init_ids_dev, G, cand, cnt, worst, rev, bp.B);
+    else if (metric == 0)
+        hipLaunchKernelGGL((k_init<0, 0>), dim3(row_blocks), dim3(256), 0, st, points_dev, n, d, bp.K, bp.C,
                            params->seed, params->init_ids_dev, G, cand, cnt, worst, rev, bp.B);
     else
-        hipLaunchKernelGGL(k_init<1>, dim3(row_blocks), dim3(256), 0, st, points_dev, n, d, bp.K, bp.C,
+        hipLaunchKernelGGL((k_init<1, 0>), dim3(row_blocks), dim3(256), 0, st, points_dev, n, d, bp.K, bp.C,
                            params->seed, params->init_ids_dev, G, cand, cnt, worst, rev, bp.B);
     HIPCHK(hipGetLastError());
     if (stats) HIPCHK(hipEventRecord(ev[1], st));
@@ -1093,9 +1250,10 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
         HIPCHK(hipGetLastError());
         if (rec) HIPCHK(hipEventRecord(ev[3 + 4 * it], st));
         {
-            JoinArgs ja{points_dev, d, bp.C, bp.s, (uint32_t)it, newl, oldl, plan, active, ctr + 2,
+            JoinArgs ja{points_dev, elem == 1 ? d / 4 : d, bp.C, bp.s, (uint32_t)it, newl, oldl, plan, active, ctr + 2,
                         worst, sig, cand, ctr + 4, num_cu, n};
-            if (metric == 0) HIPCHK(launch_join<0>(st, vec, bp.S16, ja));
+            if (elem == 1) HIPCHK(launch_join_u8(st, vec, bp.S16, ja));
+            else if (metric == 0) HIPCHK(launch_join<0>(st, vec, bp.S16, ja));
             else HIPCHK(launch_join<1>(st, vec, bp.S16, ja));
         }
         if (rec) HIPCHK(hipEventRecord(ev[4 + 4 * it], st));
@@ -1106,10 +1264,11 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
         while (Kp < bp.K) Kp <<= 1;
         const int64_t per_block = 4 * (WAVE / Kp);
         const dim3 grid((unsigned)((n + per_block - 1) / per_block)), block(256);
-#define KNNG_FIN(M, V) hipLaunchKernelGGL((k_finalize<M, V>), grid, block, 0, st, points_dev, n, d, bp.K, Kp, k, \
-                                          G, ids_out_dev, dists_out_dev)
-        if (metric == 0) { if (vec) KNNG_FIN(0, true); else KNNG_FIN(0, false); }
-        else { if (vec) KNNG_FIN(1, true); else KNNG_FIN(1, false); }
+#define KNNG_FIN(M, V, E) hipLaunchKernelGGL((k_finalize<M, V, E>), grid, block, 0, st, points_dev, n, d, bp.K, Kp, k, \
+                                             G, ids_out_dev, dists_out_dev)
+        if (elem == 1) { if (vec) KNNG_FIN(0, true, 1); else KNNG_FIN(0, false, 1); }
+        else if (metric == 0) { if (vec) KNNG_FIN(0, true, 0); else KNNG_FIN(0, false, 0); }
+        else { if (vec) KNNG_FIN(1, true, 0); else KNNG_FIN(1, false, 0); }
 #undef KNNG_FIN
         HIPCHK(hipGetLastError());
     }
@@ -1147,4 +1306,16 @@ done:
     }
     if (host_ctr) (void)hipHostFree(host_ctr);
     return rc;
+}
+
+extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const float* points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,
+                                    const knng_params_t* params, int32_t* ids_out_dev, float* dists_out_dev)
+{
+    return build_impl(points_dev, 0, n, d, k, metric, params, ids_out_dev, dists_out_dev);
+}
+
+extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph_u8(const uint8_t* points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,
+                                       const knng_params_t* params, int32_t* ids_out_dev, float* dists_out_dev)
+{
+    return build_impl(points_dev, 1, n, d, k, metric, params, ids_out_dev, dists_out_dev);
 }

@@ -1,5 +1,6 @@
 // Device-side helpers shared by the libknng kernels (gfx950, 64-wide wavefronts).
 #pragma once
+#include <type_traits>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -7,6 +8,7 @@ namespace knng {
 
 typedef unsigned long long u64;
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
 
 constexpr int WAVE = 64;
 constexpr u64 EMPTY_KEY = ~0ull;
@@ -83,5 +85,9 @@ template <int METRIC> __device__ __forceinline__ float exact_finish(double acc)
     double r = 1.0 - acc;
     return (float)(r > 0.0 ? r : 0.0);
 }
+
+// an accumulator element as the 32 bits stored in LDS (fp32 Gram tiles / integer Gram tiles)
+__device__ __forceinline__ uint32_t acc_bits(float x) { return __float_as_uint(x); }
+__device__ __forceinline__ uint32_t acc_bits(int x) { return (uint32_t)x; }
 
 }  // namespace knng

@@ -28,11 +28,20 @@
 // operand tile once per k-step, and the partner scan advances one LDS address per partner.
 // (Specialising the Gram pass on the tile counts was tried: the extra code paths cost 40
 // registers, spills, and 25% of the speed.)
+//
+// ELEM = 1: uint8 rows (squared L2 only).  A row is handled as d/4 32-bit words, so a slab of 32
+// words is 128 coordinates and the gather and the LDS slab are the same bytes as for floats.
+// The bytes are stored as signed values x - 128 (one xor) and not centred; the Gram pass is
+// v_mfma_i32_16x16x64_i8, one instruction where the fp32 pass needs sixteen, exact in 32-bit
+// integers, and |a-b|^2 = |a|^2 + |b|^2 - 2<a,b> is evaluated in integers before the one
+// conversion to fp32.  The products with the pivot (for its reverse members) come from one more
+// accumulator tile: column c of that tile takes the pivot as B operand for member tile c and a
+// row of zeros for the others, column 4 the pivot against itself.
 #pragma once
 
 namespace knng {
 
-template <int S16> struct WaveCfg {
+template <int S16, int ELEM = 0> struct WaveCfg {
     static constexpr int NCOLS = 32 * S16;            // max members (<= 64 lanes)
     static constexpr int MROWS = 16 * S16;            // max |NEW|
     static constexpr int CT = 2 * S16;                // 16-member operand tiles
@@ -44,23 +53,34 @@ template <int S16> struct WaveCfg {
     static constexpr int LDD = NCOLS + 1;             // distance-block row stride (last column: +inf cell)
     static constexpr int NL = NCOLS * (DS / 4) / 64;  // 16-byte pieces per lane and slab
     static constexpr int NTILES = (3 * S16 * S16 + 3 * S16) / 2;  // upper triangle rows<S16 + extra diagonals
-    static constexpr int XBYTES = NCOLS * LD * 4 > MROWS * LDD * 4 ? NCOLS * LD * 4 : MROWS * LDD * 4;
-    // X/D | mid[2][NCOLS] | nrm[NCOLS] | sg[8][NCOLS+1]
-    static constexpr int WBYTES = ((XBYTES + NCOLS * (8 + 4) + (NCOLS + 1) * 4 * SIG_WORDS) + 255) & ~255;
+    static_assert(NCOLS * LD >= MROWS * LDD, "the distance block lies over the slab rows");
+    // ELEM 1: two more slab rows (the pivot, zeros) and the pivot distances dpv[NCOLS]
+    static constexpr int XBYTES = (NCOLS + (ELEM ? 2 : 0)) * LD * 4;
+    // X/D | mid[2][NCOLS] | nrm[NCOLS] | sg[8][NCOLS+1] | dpv[NCOLS]
+    static constexpr int WBYTES = ((XBYTES + NCOLS * (8 + 4) + (NCOLS + 1) * 4 * SIG_WORDS +
+                                    (ELEM ? NCOLS * 4 : 0)) + 255) & ~255;
 };
 
 #ifndef KNNG_WAVE_OCC
 #define KNNG_WAVE_OCC 3
 #endif
-template <int METRIC, int S16, bool VEC>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(KNNG_WAVE_OCC, KNNG_WAVE_OCC)))
+// Wavefronts per SIMD the register allocation aims at: three; two for uint8 rows with up to 64
+// members, whose extra accumulator tile does not fit beside the rest in 168 registers.
+template <int S16, int ELEM> struct WaveOcc { static constexpr int V = (ELEM == 1 && S16 == 2) ? 2 : KNNG_WAVE_OCC; };
+
+template <int METRIC, int S16, bool VEC, int ELEM = 0>
+__global__ void __launch_bounds__(256)
+__attribute__((amdgpu_waves_per_eu(WaveOcc<S16, ELEM>::V, WaveOcc<S16, ELEM>::V)))
 k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl, const int4* __restrict__ plan,
             const int32_t* __restrict__ active, const u64* __restrict__ nactive_ptr,
             const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand,
             u64* __restrict__ offers_ctr)
 {
-    using Cfg = WaveCfg<S16>;
+    // ELEM 1: pts points at uint8 rows of 4 d bytes, d counts 32-bit words
+    static_assert(ELEM == 0 || METRIC == 0, "uint8 rows: squared L2 only");
+    using Cfg = WaveCfg<S16, ELEM>;
+    using accv = typename std::conditional<ELEM == 1, intx4, floatx4>::type;
     constexpr int NCOLS = Cfg::NCOLS, CT = Cfg::CT, DS = Cfg::DS, LD = Cfg::LD, LDD = Cfg::LDD,
                   NL = Cfg::NL, NTILES = Cfg::NTILES;
     constexpr int INF_CELL = NCOLS;                             // D[0][NCOLS]: holds +inf
@@ -70,9 +90,13 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
     unsigned char* wbase = smem + wib * Cfg::WBYTES;
     float* X = reinterpret_cast<float*>(wbase);                 // [NCOLS][LD], later D [MROWS][LDD]
     int* midbuf = reinterpret_cast<int*>(wbase + Cfg::XBYTES);  // [2][NCOLS] member ids, double-buffered
-    float* nrm = reinterpret_cast<float*>(midbuf + 2 * NCOLS);  // [NCOLS] |x_m - x_v|^2
-    uint32_t* sg = reinterpret_cast<uint32_t*>(nrm + NCOLS);    // [SIG_WORDS][NCOLS + 1], column nTot = pivot
+    // [NCOLS] bits of |x_m - x_v|^2 (fp32); ELEM 1: of |x_m - 128|^2 (integer)
+    uint32_t* nrm = reinterpret_cast<uint32_t*>(midbuf + 2 * NCOLS);
+    uint32_t* sg = nrm + NCOLS;                                 // [SIG_WORDS][NCOLS + 1], column nTot = pivot
     constexpr int SGLD = NCOLS + 1;
+    float* dpv = reinterpret_cast<float*>(sg + SIG_WORDS * SGLD);   // ELEM 1: [NCOLS] |x_m - x_v|^2
+    constexpr int PIV_ROW = NCOLS * LD, ZERO_ROW = (NCOLS + 1) * LD;   // ELEM 1: two more slab rows
+    if (ELEM == 1 && lane < LD) X[ZERO_ROW + lane] = 0.0f;
 
     const int r16 = lane & 15, kq = lane >> 4;
     const int64_t nact = (int64_t)*nactive_ptr;
@@ -189,10 +213,19 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             sg[6 * SGLD + lane] = sg_r1.z; sg[7 * SGLD + lane] = sg_r1.w;
         }
 
-        floatx4 acc[NTILES];
+        accv acc[NTILES];
 #pragma unroll
-        for (int q = 0; q < NTILES; ++q) acc[q] = floatx4{0, 0, 0, 0};
+        for (int q = 0; q < NTILES; ++q) acc[q] = accv{0, 0, 0, 0};
+        intx4 accp = intx4{0, 0, 0, 0};                         // ELEM 1: <member, pivot>, <pivot, pivot>
 
+        // uint8 -> signed bytes x - 128; words past the end of the row (zero-filled by the
+        // predicated loads of the unaligned path) stay zero
+        auto enc_u8 = [&](float4 f, int k0) -> float4 {
+            uint32_t w[4] = {__float_as_uint(f.x), __float_as_uint(f.y), __float_as_uint(f.z), __float_as_uint(f.w)};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = (VEC || k0 + 4 * c4 + j < d) ? (w[j] ^ 0x80808080u) : 0u;
+            return float4{__uint_as_float(w[0]), __uint_as_float(w[1]), __uint_as_float(w[2]), __uint_as_float(w[3])};
+        };
         // ---- A: registers -> LDS (rows up to the end of the last loaded group of 8)
         auto store_slab = [&](int k0) {
             float* xdst = X + rsub * LD + 4 * c4;
@@ -201,10 +234,16 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             for (int i = 0; i < NL; ++i) {
                 if (RPW * i < nTot) {                           // uniform
                     float4 x = buf[i];
-                    x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w;
+                    if (ELEM == 1) x = enc_u8(x, k0);
+                    else { x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w; }
                     if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
                     *reinterpret_cast<float4*>(xdst + RPW * i * LD) = x;
                 }
+            }
+            if (ELEM == 1 && rsub == 0) {                       // the pivot's own row
+                float4 x = enc_u8(pv, k0);
+                if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
+                *reinterpret_cast<float4*>(X + PIV_ROW + 4 * c4) = x;
             }
         };
         store_slab(0);
@@ -228,7 +267,37 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 issue_slab(nmid, n_tot, n_piv, last ? 0 : k0 + DS);
             }
             // ---- C: all Gram tiles of the point for this slab
-                        for (int kk = 0; kk < len16; kk += 16) {
+            if constexpr (ELEM == 1) {
+                for (int kk = 0; kk < len16; kk += 16) {
+                    intx4 x[CT];
+#pragma unroll
+                    for (int t = 0; t < CT; ++t)
+                        if (t < nct) x[t] = *reinterpret_cast<const intx4*>(X + (t * 16 + r16) * LD + 4 * kq + kk);
+                    const intx4 xp = *reinterpret_cast<const intx4*>(X + PIV_ROW + 4 * kq + kk);
+                    int q = 0;
+#pragma unroll
+                    for (int rt = 0; rt < S16; ++rt) {
+#pragma unroll
+                        for (int ct = rt; ct < CT; ++ct, ++q) {
+                            if (ct < nct && (rt < nrt || rt == ct))
+                                acc[q] = __builtin_amdgcn_mfma_i32_16x16x64_i8(x[rt], x[ct], acc[q], 0, 0, 0);
+                        }
+                    }
+#pragma unroll
+                    for (int ct = S16; ct < CT; ++ct, ++q) {
+                        if (ct < nct) acc[q] = __builtin_amdgcn_mfma_i32_16x16x64_i8(x[ct], x[ct], acc[q], 0, 0, 0);
+                    }
+                    // column c of accp: members of tile c against the pivot; column CT: the pivot's norm
+#pragma unroll
+                    for (int ct = 0; ct <= CT; ++ct) {
+                        if (ct < nct || ct == CT) {
+                            const intx4 b = *reinterpret_cast<const intx4*>(X + (r16 == ct ? PIV_ROW : ZERO_ROW) + 4 * kq + kk);
+                            accp = __builtin_amdgcn_mfma_i32_16x16x64_i8(ct < CT ? x[ct < CT ? ct : 0] : xp, b, accp, 0, 0, 0);
+                        }
+                    }
+                }
+            } else {
+            for (int kk = 0; kk < len16; kk += 16) {
                 float4 x[CT];
 #pragma unroll
                 for (int t = 0; t < CT; ++t)
@@ -256,6 +325,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                     }
                 }
             }
+            }
             wave_lds_sync();
             if (!last) store_slab(k0 + DS);
         }
@@ -279,16 +349,29 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
 #pragma unroll
                 for (int ct = rt; ct < CT; ++ct, ++q) {
                     if (ct == rt && ct < nct && (r16 >> 2) == kq)
-                        nrm[ct * 16 + r16] = e == 0 ? acc[q][0] : e == 1 ? acc[q][1] : e == 2 ? acc[q][2] : acc[q][3];
+                        nrm[ct * 16 + r16] = acc_bits(e == 0 ? acc[q][0] : e == 1 ? acc[q][1] : e == 2 ? acc[q][2] : acc[q][3]);
                 }
             }
 #pragma unroll
             for (int ct = S16; ct < CT; ++ct, ++q) {
                 if (ct < nct && (r16 >> 2) == kq)
-                    nrm[ct * 16 + r16] = e == 0 ? acc[q][0] : e == 1 ? acc[q][1] : e == 2 ? acc[q][2] : acc[q][3];
+                    nrm[ct * 16 + r16] = acc_bits(e == 0 ? acc[q][0] : e == 1 ? acc[q][1] : e == 2 ? acc[q][2] : acc[q][3]);
             }
         }
         wave_lds_sync();
+        if constexpr (ELEM == 1) {
+            // lane (c, kq), c < CT, holds <member 16c + 4kq + r, pivot> in accp[r]; column CT is <pivot, pivot>
+            const uint32_t npiv = (uint32_t)__builtin_amdgcn_readlane(accp[0], CT);
+            if (r16 < CT) {
+                const uint4 nm = *reinterpret_cast<const uint4*>(nrm + r16 * 16 + 4 * kq);
+                float4 o;
+                o.x = (float)(nm.x + npiv - 2u * (uint32_t)accp[0]);
+                o.y = (float)(nm.y + npiv - 2u * (uint32_t)accp[1]);
+                o.z = (float)(nm.z + npiv - 2u * (uint32_t)accp[2]);
+                o.w = (float)(nm.w + npiv - 2u * (uint32_t)accp[3]);
+                *reinterpret_cast<float4*>(dpv + r16 * 16 + 4 * kq) = o;
+            }
+        }
         // ---- distance block D[row][col] over the slab storage; cells outside NEW x members are
         // +inf so the partner scan needs no bounds tests
         float* D = X;
@@ -301,15 +384,20 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 for (int ct = rt; ct < CT; ++ct, ++q) {
                     if (ct < nct && rt < nrt) {
                         const int col = ct * 16 + r16;
-                        const float nc = nrm[col];
-                        const float4 nr = *reinterpret_cast<const float4*>(nrm + rt * 16 + 4 * kq);
-                        const float nra[4] = {nr.x, nr.y, nr.z, nr.w};
+                        const uint32_t nc = nrm[col];
+                        const uint4 nr = *reinterpret_cast<const uint4*>(nrm + rt * 16 + 4 * kq);
+                        const uint32_t nra[4] = {nr.x, nr.y, nr.z, nr.w};
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
                             const int row = rt * 16 + 4 * kq + r;
-                            float l = nra[r] + nc - 2.0f * acc[q][r];
-                            if (METRIC == 1) l *= 0.5f;        // unit rows: 1 - <a,b> = |a-b|^2 / 2
-                            l = nonneg(l);
+                            float l;
+                            if constexpr (ELEM == 1) {
+                                l = (float)(nra[r] + nc - 2u * (uint32_t)acc[q][r]);   // exact, >= 0
+                            } else {
+                                l = __uint_as_float(nra[r]) + __uint_as_float(nc) - 2.0f * acc[q][r];
+                                if (METRIC == 1) l *= 0.5f;    // unit rows: 1 - <a,b> = |a-b|^2 / 2
+                                l = nonneg(l);
+                            }
                             D[row * LDD + col] = (row < nNew && col < nTot) ? l : inf;
                         }
                     }
@@ -326,7 +414,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             float l = 0.0f;
             uint32_t vw = 0xffffffffu;
             if (rev) {
-                l = nrm[m];
+                l = ELEM == 1 ? dpv[m] : __uint_as_float(nrm[m]);
                 if (METRIC == 1) l *= 0.5f;
                 l = nonneg(l);
                 vw = sg[(my_hb >> 5) * SGLD + nTot];

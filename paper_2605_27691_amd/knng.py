@@ -47,7 +47,8 @@ class Params(ctypes.Structure):
                 ("stats_host", ctypes.POINTER(Stats))]
 
 
-EXPORTS = ("knng_build_workspace_bytes", "knng_build_knn_graph", "knng_brute_workspace_bytes",
+EXPORTS = ("knng_build_workspace_bytes", "knng_build_knn_graph", "knng_build_knn_graph_u8",
+           "knng_brute_workspace_bytes",
            "knng_brute_knn", "knng_graph_recall", "knng_merge_graphs", "knng_strerror", "knng_version")
 
 _lib = None
@@ -70,6 +71,8 @@ def load():
     L.knng_build_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(Params)]
     L.knng_build_knn_graph.restype = ctypes.c_int
     L.knng_build_knn_graph.argtypes = [_P, i64, i32, i32, i32, ctypes.POINTER(Params), _P, _P]
+    L.knng_build_knn_graph_u8.restype = ctypes.c_int
+    L.knng_build_knn_graph_u8.argtypes = [_P, i64, i32, i32, i32, ctypes.POINTER(Params), _P, _P]
     L.knng_brute_workspace_bytes.restype = u64
     L.knng_brute_workspace_bytes.argtypes = [i64, i32, i32, i64]
     L.knng_brute_knn.restype = ctypes.c_int
@@ -130,17 +133,10 @@ def knng_build_workspace_bytes(n, d, k, params=None) -> int:
     return int(load().knng_build_workspace_bytes(n, d, k, ctypes.byref(params) if params else None))
 
 
-def knng_build_knn_graph(points, k, metric=L2SQ, *, k_build=0, rho=0.0, delta=0.0, max_iters=0,
-                         cand_cap=0, seed=0, init_ids=None, workspace=None, want_stats=True,
-                         ids_out=None, dists_out=None):
-    """Approximate k-NN graph of `points` ([n][d] fp32, GPU).  -> (ids, dists, stats | None).
-
-    Zero-valued keyword parameters select the library defaults; max_iters=-1 runs
-    no refinement iteration (random graph).  `workspace` (uint8 GPU tensor) is
-    allocated here when not given.
-    """
+def _build_graph(entry, dtype, points, k, metric, k_build, rho, delta, max_iters, cand_cap, seed,
+                 init_ids, workspace, want_stats, ids_out, dists_out):
     L = load()
-    points = _dev(points, torch.float32, "points")
+    points = _dev(points, dtype, "points")
     n, d = points.shape
     p = make_params(k_build, rho, delta, max_iters, cand_cap, seed)
     need = int(L.knng_build_workspace_bytes(n, d, k, ctypes.byref(p)))
@@ -163,8 +159,7 @@ def knng_build_knn_graph(points, k, metric=L2SQ, *, k_build=0, rho=0.0, delta=0.
     p.workspace_bytes = workspace.numel()
     if st is not None:
         p.stats_host = ctypes.pointer(st)
-    _check(L.knng_build_knn_graph(_ptr(points), n, d, k, metric, ctypes.byref(p),
-                                  _ptr(ids_out), _ptr(dists_out)))
+    _check(getattr(L, entry)(_ptr(points), n, d, k, metric, ctypes.byref(p), _ptr(ids_out), _ptr(dists_out)))
     stats = None
     if st is not None:
         it = min(st.iterations, STATS_MAX_ITERS)
@@ -175,6 +170,27 @@ def knng_build_knn_graph(points, k, metric=L2SQ, *, k_build=0, rho=0.0, delta=0.
                  "ms_finalize": st.ms_finalize, "ms_total": st.ms_total,
                  "offers": int(st.offers), "pairs": int(st.pairs)}
     return ids_out, dists_out, stats
+
+
+def knng_build_knn_graph(points, k, metric=L2SQ, *, k_build=0, rho=0.0, delta=0.0, max_iters=0,
+                         cand_cap=0, seed=0, init_ids=None, workspace=None, want_stats=True,
+                         ids_out=None, dists_out=None):
+    """Approximate k-NN graph of `points` ([n][d] fp32, GPU).  -> (ids, dists, stats | None).
+
+    Zero-valued keyword parameters select the library defaults; max_iters=-1 runs
+    no refinement iteration (random graph).  `workspace` (uint8 GPU tensor) is
+    allocated here when not given.
+    """
+    return _build_graph("knng_build_knn_graph", torch.float32, points, k, metric, k_build, rho, delta,
+                        max_iters, cand_cap, seed, init_ids, workspace, want_stats, ids_out, dists_out)
+
+
+def knng_build_knn_graph_u8(points, k, metric=L2SQ, *, k_build=0, rho=0.0, delta=0.0, max_iters=0,
+                            cand_cap=0, seed=0, init_ids=None, workspace=None, want_stats=True,
+                            ids_out=None, dists_out=None):
+    """The same for `points` stored as [n][d] uint8 (GPU): squared L2 only, d % 4 == 0."""
+    return _build_graph("knng_build_knn_graph_u8", torch.uint8, points, k, metric, k_build, rho, delta,
+                        max_iters, cand_cap, seed, init_ids, workspace, want_stats, ids_out, dists_out)
 
 
 def knng_brute_workspace_bytes(n, d, k, nq) -> int:

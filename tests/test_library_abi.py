@@ -14,7 +14,7 @@ def _declared_functions():
     with open(os.path.join(ROOT, "include", "knng.h")) as f:
         text = f.read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(knng_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(knng_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_declares_the_expected_entry_points():
