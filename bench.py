@@ -28,12 +28,15 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
+INT8_MFMA_PEAK_TOPS = 5000.0     # dense int8 MFMA (the uint8 build's Gram tiles)
 SIG_BYTES = 32          # row signature read per gathered member
 # HBM-side bytes per join launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each
 # scaled by what a plain 1 GiB device copy reads: 2.0 and 1.0 KiB per count), averaged over the same
 # launch mix as the timed region.  Only measured for the default workload and parameters
 # (profiles/k_join_config1_1m_d128_hbm_traffic.txt: 17.28 GB fetched + 1.47 GB written).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("u8gmm1024_1m_d128_l2", 32, 0.5): 18.75e9}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("u8gmm1024_1m_d128_l2", "f32", 32, 0.5): 18.75e9,
+                                     # profiles/k_join_wave_u8_config1_1m_d128.txt: 7.92 GB + 1.47 GB
+                                     ("u8gmm1024_1m_d128_l2", "u8", 32, 0.5): 9.39e9}
 
 
 def parse():
@@ -43,6 +46,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=1, help="workload index (0..4)")
     ap.add_argument("--n", type=int, default=0, help="override the number of points")
+    ap.add_argument("--elem", choices=("f32", "u8"), default="f32",
+                    help="point storage; u8 (knng_build_knn_graph_u8) needs a workload with 8-bit values: config 1")
     ap.add_argument("--k-build", type=int, default=0)
     ap.add_argument("--rho", type=float, default=0.0)
     ap.add_argument("--delta", type=float, default=0.0)
@@ -74,9 +79,16 @@ def main():
     ids = torch.empty((n, k), dtype=torch.int32, device=dev)
     dists = torch.empty((n, k), dtype=torch.float32, device=dev)
 
+    build, xb, elem_bytes = knng.knng_build_knn_graph, x, 4
+    if a.elem == "u8":
+        xb = x.to(torch.uint8)
+        if w.metric != 0 or not torch.equal(xb.float(), x):
+            print("bench.py: --elem u8 needs 8-bit point values and squared L2 (config 1)", file=sys.stderr)
+            sys.exit(2)
+        build, elem_bytes = knng.knng_build_knn_graph_u8, 1
+
     def step(seed):
-        return knng.knng_build_knn_graph(x, k, w.metric, seed=seed, workspace=ws, ids_out=ids,
-                                         dists_out=dists, **kw)[2]
+        return build(xb, k, w.metric, seed=seed, workspace=ws, ids_out=ids, dists_out=dists, **kw)[2]
 
     for i in range(a.warmup):
         step(1000 + i)
@@ -110,7 +122,7 @@ def main():
     join_ms = sum(sum(s["join_ms"]) for s in stats)
     launches = sum(len(s["join_ms"]) for s in stats)
     rows = sum(sum(s["join_rows"]) for s in stats)
-    alg_bytes = rows * (4 * d + 4 + 4 + SIG_BYTES) + launches * n * 16
+    alg_bytes = rows * (elem_bytes * d + 4 + 4 + SIG_BYTES) + launches * n * 16
     achieved = alg_bytes / (join_ms * 1e-3) / 1e9 if join_ms > 0 else 0.0
     pairs = sum(s["pairs"] for s in stats)                    # pairs the joins had to evaluate
     offers = sum(s["offers"] for s in stats)                  # atomic mins sent to candidate slots
@@ -118,9 +130,10 @@ def main():
     last = stats[-1]
     # the join is priced against HBM (a gather) unless its Gram blocks are the larger fraction of
     # their own peak (large samples: s = 32 does four times the pair work per gathered byte)
-    if needed_tflops / FP32_MFMA_PEAK_TFLOPS > achieved / HBM_PEAK_GBS:
-        bound = {"bound": "mfma", "achieved": needed_tflops, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                 "frac": needed_tflops / FP32_MFMA_PEAK_TFLOPS, "hbm_gbs": achieved, "frac_of_hbm_peak": achieved / HBM_PEAK_GBS}
+    mfma_peak = INT8_MFMA_PEAK_TOPS if a.elem == "u8" else FP32_MFMA_PEAK_TFLOPS
+    if needed_tflops / mfma_peak > achieved / HBM_PEAK_GBS:
+        bound = {"bound": "mfma", "achieved": needed_tflops, "peak": mfma_peak, "unit": "TFLOP/s",
+                 "frac": needed_tflops / mfma_peak, "hbm_gbs": achieved, "frac_of_hbm_peak": achieved / HBM_PEAK_GBS}
     else:
         bound = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                  "frac": achieved / HBM_PEAK_GBS}
@@ -159,8 +172,8 @@ def main():
         "metric": "kNN-graph build points/sec at recall@k>=0.95 (1 MI355X)",
         "value": n / sec, "unit": "points/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "n": n, "d": d, "k": k, "metric": ["l2sq", "ip_unit"][w.metric],
+        "dtype": "f32" if a.elem == "f32" else "i8 x i8 -> i32", "data": "synthetic",
+        "config": {"workload": w.name + ("" if a.elem == "f32" else "_stored_u8"), "n": n, "d": d, "k": k, "metric": ["l2sq", "ip_unit"][w.metric],
                    "k_build": a.k_build or k, "rho": a.rho or 0.5, "delta": a.delta or 1e-4,
                    "iterations": last["iterations"], "converged": last["converged"]},
         "recall_at_k": recall, "recall_at_k_distance": recall_dist, "recall_rows": int(len(rows_s)),
@@ -169,11 +182,11 @@ def main():
         "kernel_ms": {"init": last["ms_init"], "sample": last["ms_sample"], "join": last["ms_join"],
                       "merge": last["ms_merge"], "finalize": last["ms_finalize"], "total": last["ms_total"]},
         "roofline": {"kernel": "k_join", **bound,
-                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((w.name, a.k_build or k, a.rho or 0.5)),
+                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((w.name, a.elem, a.k_build or k, a.rho or 0.5)),
                      "launches": launches, "avg_launch_ms": join_ms / max(launches, 1),
                      "alg_bytes_per_launch": alg_bytes / max(launches, 1),
                      "device_copy_gbs": copy_gbs, "frac_of_device_copy": achieved / copy_gbs,
-                     "needed_pair_tflops": needed_tflops, "frac_of_fp32_mfma_peak": needed_tflops / FP32_MFMA_PEAK_TFLOPS,
+                     "needed_pair_tflops": needed_tflops, "frac_of_mfma_peak": needed_tflops / mfma_peak,
                      "offers_per_launch": offers / max(launches, 1)},
         "cpu_baseline": cpu,
     }
