@@ -36,6 +36,8 @@ def lib():
                                         c_i32, c_i32, c_u64, P, P, P]
         L.oracle_merge_rows.restype = ctypes.c_int
         L.oracle_merge_rows.argtypes = [P, P, c_i32, P, P, c_i32, c_i64, c_i32, P, P]
+        L.oracle_optimize_graph.restype = ctypes.c_int
+        L.oracle_optimize_graph.argtypes = [P, c_i64, c_i32, c_i32, P]
         _lib = L
     return _lib
 
@@ -110,6 +112,18 @@ def merge_rows(ids_a, dists_a, ids_b, dists_b, k_out):
 
 VIOLATION_NAMES = ("id_range", "self_loop", "duplicate_id", "not_ascending",
                    "distance_mismatch", "bad_distance")
+
+
+def optimize_graph(ids, d_out):
+    """Search graph G^s of a k-NN graph given as ids [n][k], nearest first.  -> ids [n][d_out]."""
+    ids = _i32(ids)
+    assert ids.ndim == 2
+    n, k = ids.shape
+    out = np.empty((n, d_out), dtype=np.int32)
+    rc = lib().oracle_optimize_graph(_p(ids), n, k, d_out, _p(out))
+    if rc != 0:
+        raise ValueError(f"oracle_optimize_graph: bad arguments (rc={rc})")
+    return out
 
 
 def check_graph(points, ids, dists, metric=L2SQ, rel_tol=1e-5, rows=None):

@@ -15,6 +15,7 @@
  *   oracle_nn_descent    NN-Descent with candidate lists and a
  *                        single-owner merge, step by step              (Sec. 3.1, 3.1.1)
  *   oracle_merge_rows    a graph's rows updated with search results R  (Sec. 4.3 step 4, 4.4)
+ *   oracle_optimize_graph  k-NN graph G -> search graph G^s            (Sec. 3.3)
  *
  * Pin status: every function is pinned by tests that do not go through this
  * file (closed forms, exhaustive enumeration in numpy on tiny inputs, integer
@@ -571,5 +572,122 @@ int oracle_merge_rows(const int32_t *ids_a, const float *dists_a, int32_t ka,
         for (; w < k_out; ++w) { ids_out[i * k_out + w] = -1; dists_out[i * k_out + w] = INFINITY; }
     }
     free(id); free(ds); free(used);
+    return 0;
+}
+
+/* ======================================================================== */
+/* Search-graph optimisation G -> G^s (Sec. 3.3): drop edges that a shorter  */
+/* two-hop path bypasses, then add reverse edges; ids only, no distances.    */
+/* The section names the technique and its properties (rank-based, needs no  */
+/* distance data); the steps below are this build's reading of it.           */
+/*                                                                           */
+/* ids [n][k]: row u lists u's neighbours nearest first, so the column is the */
+/* rank.  An entry is *valid* if it lies in [0,n), is not u and does not      */
+/* repeat an earlier entry of the row; other entries are padding.            */
+/* 1. Detours.  The edge u -> v at rank j can be bypassed through a          */
+/*    neighbour w of u if both hops rank before it: w at rank i < j in u's   */
+/*    row and v at some rank r < j in w's row.  c(u,j) = number of such w.   */
+/*    Padding entries get c = k (more than any count).                       */
+/* 2. Prune.  P(u) = the d_out entries of row u with the smallest (c, rank), */
+/*    in that order; padding is written as -1.                               */
+/* 3. Reverse.  Every edge u -> v at position p of P(u) hands (p, u) to v;   */
+/*    R(v) = what v received, ascending by (p, u).                           */
+/* 4. Merge, with h = d_out / 2: the row of v in G^s starts with the first   */
+/*    d_out - h entries of P(v); then R(v) in order, then the rest of P(v)   */
+/*    in order, are appended, skipping -1 and ids the row already holds,     */
+/*    until it has d_out entries (at most h come from R(v) unless P(v) runs  */
+/*    out); if everything runs out the row is padded with -1.                */
+/* Returns 0, or -1 on bad arguments (n < 1, k < 1, d_out < 1, d_out > k).   */
+/* ------------------------------------------------------------------------ */
+typedef struct { int32_t p, u; } rev_t;
+static int rev_cmp(const void *a, const void *b)
+{
+    const rev_t *x = (const rev_t *)a, *y = (const rev_t *)b;
+    if (x->p != y->p) return x->p < y->p ? -1 : 1;
+    return x->u < y->u ? -1 : (x->u > y->u ? 1 : 0);
+}
+
+int oracle_optimize_graph(const int32_t *ids, int64_t n, int32_t k, int32_t d_out, int32_t *out)
+{
+    if (!ids || !out || n < 1 || k < 1 || d_out < 1 || d_out > k) return -1;
+    int32_t *P = (int32_t *)malloc((size_t)n * d_out * sizeof(int32_t));
+    int64_t *start = (int64_t *)calloc((size_t)n + 1, sizeof(int64_t));
+    if (!P || !start) { free(P); free(start); return -1; }
+
+    /* steps 1 and 2 */
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t u = 0; u < n; ++u) {
+        const int32_t *row = ids + u * k;
+        int32_t c[1024], valid[1024], order[1024];
+        int32_t *cc = c, *vv = valid, *oo = order;
+        if (k > 1024) { cc = malloc(3 * (size_t)k * sizeof(int32_t)); vv = cc + k; oo = vv + k; }
+        for (int32_t j = 0; j < k; ++j) {
+            int ok = row[j] >= 0 && (int64_t)row[j] < n && (int64_t)row[j] != u;
+            for (int32_t i = 0; ok && i < j; ++i) if (row[i] == row[j]) ok = 0;
+            vv[j] = ok;
+        }
+        for (int32_t j = 0; j < k; ++j) {
+            if (!vv[j]) { cc[j] = k; continue; }
+            int32_t cnt = 0;
+            for (int32_t i = 0; i < j; ++i) {
+                if (!vv[i]) continue;
+                const int32_t *wrow = ids + (int64_t)row[i] * k;
+                int found = 0;
+                for (int32_t r = 0; r < j && !found; ++r) found = wrow[r] == row[j];
+                cnt += found;
+            }
+            cc[j] = cnt;
+        }
+        /* stable selection by (count, rank) */
+        for (int32_t j = 0; j < k; ++j) oo[j] = j;
+        for (int32_t a = 1; a < k; ++a) {
+            int32_t x = oo[a], b = a;
+            while (b > 0 && cc[oo[b - 1]] > cc[x]) { oo[b] = oo[b - 1]; --b; }
+            oo[b] = x;
+        }
+        for (int32_t p = 0; p < d_out; ++p) P[u * d_out + p] = vv[oo[p]] ? row[oo[p]] : -1;
+        if (cc != c) free(cc);
+    }
+
+    /* step 3: what every point received, ascending by (p, u) */
+    for (int64_t u = 0; u < n; ++u)
+        for (int32_t p = 0; p < d_out; ++p)
+            if (P[u * d_out + p] >= 0) ++start[P[u * d_out + p] + 1];
+    for (int64_t v = 0; v < n; ++v) start[v + 1] += start[v];
+    rev_t *R = (rev_t *)malloc((size_t)(start[n] > 0 ? start[n] : 1) * sizeof(rev_t));
+    int64_t *fill = (int64_t *)malloc((size_t)n * sizeof(int64_t));
+    if (!R || !fill) { free(P); free(start); free(R); free(fill); return -1; }
+    memcpy(fill, start, (size_t)n * sizeof(int64_t));
+    for (int64_t u = 0; u < n; ++u)
+        for (int32_t p = 0; p < d_out; ++p) {
+            const int32_t v = P[u * d_out + p];
+            if (v >= 0) { R[fill[v]].p = p; R[fill[v]].u = (int32_t)u; ++fill[v]; }
+        }
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t v = 0; v < n; ++v)
+        qsort(R + start[v], (size_t)(start[v + 1] - start[v]), sizeof(rev_t), rev_cmp);
+
+    /* step 4 */
+    const int32_t h = d_out / 2;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t v = 0; v < n; ++v) {
+        int32_t *o = out + v * d_out;
+        const int32_t *pv = P + v * d_out;
+        int32_t m = 0;
+        for (int32_t p = 0; p < d_out - h; ++p) if (pv[p] >= 0) o[m++] = pv[p];
+        for (int64_t e = start[v]; e < start[v + 1] && m < d_out; ++e) {
+            int dup = 0;
+            for (int32_t t = 0; t < m; ++t) dup |= o[t] == R[e].u;
+            if (!dup) o[m++] = R[e].u;
+        }
+        for (int32_t p = d_out - h; p < d_out && m < d_out; ++p) {
+            if (pv[p] < 0) continue;
+            int dup = 0;
+            for (int32_t t = 0; t < m; ++t) dup |= o[t] == pv[p];
+            if (!dup) o[m++] = pv[p];
+        }
+        while (m < d_out) o[m++] = -1;
+    }
+    free(P); free(start); free(R); free(fill);
     return 0;
 }

@@ -448,3 +448,112 @@ def test_merge_rows_against_a_python_statement_on_random_lists():
         got = [(float(a), int(b)) for a, b in zip(od[i], oi[i]) if b >= 0]
         assert got == want
         assert all(b == -1 for b in oi[i, len(want):])
+
+
+# ------------------------------------------------------------------ optimize_graph (Sec. 3.3)
+def test_optimize_graph_hand_fixture(golden_dir):
+    rows_in, rows_out = [], []
+    with open(os.path.join(golden_dir, "optimize_graph_hand.txt")) as f:
+        for line in f:
+            t = line.split()
+            if t and t[0] == "in":
+                rows_in.append([int(x) for x in t[1:]])
+            if t and t[0] == "out":
+                rows_out.append([int(x) for x in t[1:]])
+    got = oracle.optimize_graph(np.array(rows_in, np.int32), 2)
+    assert got.tolist() == rows_out
+
+
+def test_optimize_graph_ring_closed_form():
+    # row u = [u+1, ..., u+k] (mod n): the edge at rank t is bypassed through every earlier
+    # entry, so its count is t, pruning keeps the first d_out, v receives (p, v-1-p), and the
+    # search graph is [v+1 .. v+d_out-h, v-1 .. v-h]
+    n, k = 101, 12
+    ids = (np.arange(n)[:, None] + np.arange(1, k + 1)[None, :]) % n
+    for d_out in (12, 8, 5, 2, 1):
+        h = d_out // 2
+        want = np.concatenate([(np.arange(n)[:, None] + np.arange(1, d_out - h + 1)[None, :]) % n,
+                               (np.arange(n)[:, None] - np.arange(1, h + 1)[None, :]) % n], axis=1)
+        assert np.array_equal(oracle.optimize_graph(ids.astype(np.int32), d_out), want)
+
+
+def _optimize_by_path_enumeration(ids, d_out):
+    """The same definition, from the two-hop paths' side: a path u -> w -> v with ranks (a, b)
+    bypasses u's edge to v iff that edge ranks after both hops.  Pure Python, tiny inputs."""
+    n, k = ids.shape
+    def valid_row(u):
+        seen, ok = set(), []
+        for x in ids[u]:
+            good = 0 <= x < n and x != u and x not in seen
+            ok.append(good)
+            if good:
+                seen.add(int(x))
+        return ok
+    P = []
+    for u in range(n):
+        ok = valid_row(u)
+        rank_of = {int(ids[u][j]): j for j in range(k) if ok[j]}
+        cnt = [0 if ok[j] else k for j in range(k)]
+        for a in range(k):
+            if not ok[a]:
+                continue
+            w = int(ids[u][a])
+            first = {}
+            for b in range(k):
+                first.setdefault(int(ids[w][b]), b)         # first position of every value in row w
+            for v, b in first.items():
+                j = rank_of.get(v)
+                if j is not None and j > a and j > b:
+                    cnt[j] += 1
+        order = sorted(range(k), key=lambda j: (cnt[j], j))[:d_out]
+        P.append([int(ids[u][j]) if ok[j] else -1 for j in order])
+    recv = [[] for _ in range(n)]
+    for u in range(n):
+        for p, v in enumerate(P[u]):
+            if v >= 0:
+                recv[v].append((p, u))
+    h = d_out // 2
+    out = []
+    for v in range(n):
+        row = [x for x in P[v][:d_out - h] if x >= 0]
+        for x in [u for _, u in sorted(recv[v])] + [x for x in P[v][d_out - h:] if x >= 0]:
+            if len(row) < d_out and x not in row:
+                row.append(x)
+        out.append(row + [-1] * (d_out - len(row)))
+    return np.array(out, np.int32)
+
+
+def test_optimize_graph_against_path_enumeration_on_small_graphs():
+    rng = np.random.default_rng(21)
+    for n, k, d_out in [(30, 6, 4), (50, 8, 8), (40, 10, 5), (12, 11, 6), (25, 4, 1), (64, 16, 7)]:
+        # exact graphs of points on a line with jitter: heavy neighbour overlap, many bypasses
+        x = np.sort(rng.random(n)) + 0.05 * rng.random(n)
+        dist = np.abs(x[:, None] - x[None, :])
+        np.fill_diagonal(dist, np.inf)
+        ids = np.argsort(dist, axis=1, kind="stable")[:, :k].astype(np.int32)
+        assert np.array_equal(oracle.optimize_graph(ids, d_out), _optimize_by_path_enumeration(ids, d_out))
+        # random graphs with padding, self loops and repeats
+        bad = rng.integers(-2, n + 2, (n, k)).astype(np.int32)
+        assert np.array_equal(oracle.optimize_graph(bad, d_out), _optimize_by_path_enumeration(bad, d_out))
+
+
+def test_optimize_graph_invariants_and_a_hub():
+    rng = np.random.default_rng(22)
+    x = rng.standard_normal((400, 3)).astype(np.float32)
+    ids, _ = oracle.brute_knn(x, 16, oracle.L2SQ)
+    ids[:, 0] = np.where(np.arange(400) == 7, ids[:, 0], 7)     # a hub: everyone's nearest neighbour is 7
+    for d_out in (16, 9, 4):
+        g = oracle.optimize_graph(ids, d_out)
+        h = d_out // 2
+        for v in range(400):
+            row = g[v]
+            assert len(set(row.tolist())) == d_out and v not in row and row.min() >= 0
+            for t, u in enumerate(row):
+                # every edge is a pruned forward edge or the reverse of one
+                assert u in ids[v] or v in ids[u]
+        # the hub received (0, u) from every u: its reverse part is the h smallest ids
+        fwd = g[7][:d_out - h].tolist()
+        want_rev = [u for u in range(400) if u != 7 and u not in fwd][:h]
+        assert g[7][d_out - h:].tolist() == want_rev
+    with pytest.raises(ValueError):
+        oracle.optimize_graph(ids, 17)
