@@ -188,6 +188,37 @@ int knng_merge_graphs(const int32_t *ids_a_dev, const float *dists_a_dev, int32_
                       int64_t n, int32_t k_out, int32_t *ids_out_dev, float *dists_out_dev,
                       void *stream);
 
+/* Device scratch needed by knng_optimize_graph (0 on bad arguments). */
+uint64_t knng_optimize_workspace_bytes(int64_t n, int32_t k, int32_t d_out);
+
+/*
+ * Search graph G^s from a k-NN graph G (Sec. 3.3: edges that can be bypassed via
+ * shorter paths are removed, reverse edges added; ranks only, no distance data).
+ * The section names the technique; the steps are fixed here as follows.
+ *
+ * ids_dev [n][k] int32 (device, read-only): row u lists u's neighbours nearest
+ * first (what knng_build_knn_graph writes), so the column is the rank.  An entry
+ * is valid if it lies in [0,n), is not u and does not repeat an earlier entry of
+ * its row; any other entry is padding.
+ *   1. c(u,j) = number of neighbours w of u at a rank i < j whose own row holds
+ *      u's j-th neighbour at a rank r < j (the edge u -> that neighbour can be
+ *      bypassed through w); padding entries get c = k.
+ *   2. P(u) = the d_out entries of row u with the smallest (c, rank), in that
+ *      order (padding as -1).
+ *   3. Every edge u -> v at position p of P(u) hands (p, u) to v; R(v) = what v
+ *      received, ascending by (p, u).
+ *   4. Row v of the result = the first d_out - d_out/2 entries of P(v); then R(v)
+ *      in order, then the remaining entries of P(v) in order, are appended,
+ *      skipping -1 and ids the row already holds, until it has d_out entries; a
+ *      row that runs out of candidates is padded with -1.
+ * ids_out_dev [n][d_out] int32 (device, written in full on success; must not
+ * overlap ids_dev).  1 <= d_out <= k <= KNNG_MAX_K.  The result is deterministic.
+ * Errors: KNNG_EINVAL (null pointers, sizes out of range), KNNG_EWORKSPACE, KNNG_EHIP.
+ */
+int knng_optimize_graph(const int32_t *ids_dev, int64_t n, int32_t k, int32_t d_out,
+                        int32_t *ids_out_dev, void *workspace_dev, uint64_t workspace_bytes,
+                        void *stream);
+
 /* Text for a return code; for KNNG_EHIP the text of the last HIP failure on this thread. */
 const char *knng_strerror(int code);
 

@@ -49,7 +49,8 @@ class Params(ctypes.Structure):
 
 EXPORTS = ("knng_build_workspace_bytes", "knng_build_knn_graph", "knng_build_knn_graph_u8",
            "knng_brute_workspace_bytes",
-           "knng_brute_knn", "knng_graph_recall", "knng_merge_graphs", "knng_strerror", "knng_version")
+           "knng_brute_knn", "knng_graph_recall", "knng_merge_graphs", "knng_optimize_workspace_bytes",
+           "knng_optimize_graph", "knng_strerror", "knng_version")
 
 _lib = None
 
@@ -82,6 +83,10 @@ def load():
                                     ctypes.POINTER(ctypes.c_double), _P]
     L.knng_merge_graphs.restype = ctypes.c_int
     L.knng_merge_graphs.argtypes = [_P, _P, i32, _P, _P, i32, i64, i32, _P, _P, _P]
+    L.knng_optimize_workspace_bytes.restype = u64
+    L.knng_optimize_workspace_bytes.argtypes = [i64, i32, i32]
+    L.knng_optimize_graph.restype = ctypes.c_int
+    L.knng_optimize_graph.argtypes = [_P, i64, i32, i32, _P, _P, u64, _P]
     L.knng_strerror.restype = ctypes.c_char_p
     L.knng_strerror.argtypes = [ctypes.c_int]
     L.knng_version.restype = ctypes.c_int
@@ -255,3 +260,26 @@ def knng_merge_graphs(ids_a, dists_a, ids_b, dists_b, k_out, ids_out=None, dists
                                ids_b.shape[1], n, k_out, _ptr(_dev(ids_out, torch.int32, "ids_out")),
                                _ptr(_dev(dists_out, torch.float32, "dists_out")), _stream()))
     return ids_out, dists_out
+
+
+def knng_optimize_workspace_bytes(n, k, d_out) -> int:
+    return int(load().knng_optimize_workspace_bytes(n, k, d_out))
+
+
+def knng_optimize_graph(ids, d_out, workspace=None, ids_out=None):
+    """Search graph of the k-NN graph `ids` ([n][k] int32, GPU, nearest first).  -> ids [n][d_out]."""
+    L = load()
+    ids = _dev(ids, torch.int32, "ids")
+    n, k = ids.shape
+    need = int(L.knng_optimize_workspace_bytes(n, k, d_out))
+    if need == 0:
+        raise KnngError(-1)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=ids.device)
+    workspace = _dev(workspace, torch.uint8, "workspace")
+    if ids_out is None:
+        ids_out = torch.empty((n, d_out), dtype=torch.int32, device=ids.device)
+    ids_out = _dev(ids_out, torch.int32, "ids_out")
+    _check(L.knng_optimize_graph(_ptr(ids), n, k, d_out, _ptr(ids_out), _ptr(workspace), workspace.numel(),
+                                 _stream()))
+    return ids_out
