@@ -15,6 +15,11 @@ already resident in HBM.  Prints ONE JSON line:
 Recall@k is measured outside the timed region against the exact rows of a
 seeded sample of points (GPU brute force, itself compared bit-for-bit with the
 CPU oracle on a few rows); the run fails if recall@k < 0.95.
+
+`--op optimize` times the search-graph optimisation (`knng_optimize_graph`) of
+the graph that build produces instead (one step = one call; the graph is built
+once, outside the timed region); the oracle runs on the same graph beside it
+and the run fails unless the two results are identical.
 """
 import argparse
 import json
@@ -48,6 +53,8 @@ def parse():
     ap.add_argument("--n", type=int, default=0, help="override the number of points")
     ap.add_argument("--elem", choices=("f32", "u8"), default="f32",
                     help="point storage; u8 (knng_build_knn_graph_u8) needs a workload with 8-bit values: config 1")
+    ap.add_argument("--op", choices=("build", "optimize"), default="build")
+    ap.add_argument("--d-out", type=int, default=0, help="--op optimize: degree of the search graph (default k)")
     ap.add_argument("--k-build", type=int, default=0)
     ap.add_argument("--rho", type=float, default=0.0)
     ap.add_argument("--delta", type=float, default=0.0)
@@ -59,12 +66,73 @@ def parse():
     return ap.parse_args()
 
 
+def bench_optimize(a):
+    """knng_optimize_graph on the k-NN graph of the workload (built once, untimed)."""
+    import numpy as np
+    import torch
+    from paper_2605_27691_amd import knng, workloads
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    x, w = workloads.make(a.config, n=(a.n or None), device=dev)
+    n, k = w.n, w.k
+    d_out = a.d_out or k
+    g_ids, _, st = knng.knng_build_knn_graph(x, k, w.metric, seed=0, k_build=a.k_build, rho=a.rho, delta=a.delta)
+    del x
+    ws = torch.empty(knng.knng_optimize_workspace_bytes(n, k, d_out), dtype=torch.uint8, device=dev)
+    out = torch.empty((n, d_out), dtype=torch.int32, device=dev)
+    for _ in range(a.warmup):
+        knng.knng_optimize_graph(g_ids, d_out, workspace=ws, ids_out=out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(a.steps):
+        knng.knng_optimize_graph(g_ids, d_out, workspace=ws, ids_out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / max(a.steps, 1)
+    dev_ms = e0.elapsed_time(e1) / max(a.steps, 1)
+    # algorithmic bytes per point: own row + k neighbour rows (4k each); the pruned list with its
+    # places (8 per entry) written once and read twice; the (p, u) words (8) written and read;
+    # the result (4 per entry); in-degree counter, offsets
+    alg_bytes = n * (4 * k * (k + 1) + (24 + 16 + 4) * d_out + 40)
+    import oracle
+    ids_h = g_ids.cpu().numpy()
+    t1 = time.perf_counter()
+    want = oracle.optimize_graph(ids_h, d_out)
+    cpu_sec = time.perf_counter() - t1
+    same = bool(np.array_equal(want, out.cpu().numpy()))
+    achieved = alg_bytes / (dev_ms * 1e-3) / 1e9
+    res = {
+        "metric": "search-graph optimisation points/sec (1 MI355X)",
+        "value": n / sec, "unit": "points/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "i32", "data": "synthetic",
+        "config": {"workload": w.name + "_knn_graph", "n": n, "k": k, "d_out": d_out,
+                   "graph_from": "knng_build_knn_graph, seed 0", "build_iterations": st["iterations"]},
+        "oracle_check": {"identical_to_oracle": same, "rows": n},
+        "roofline": {"kernel": "knng_optimize_graph (k_opt_prune, prefix sum, k_opt_fill, k_opt_merge)",
+                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "device_ms_per_call": dev_ms,
+                     "alg_bytes_per_call": alg_bytes},
+        "cpu_baseline": {"value": n / cpu_sec, "unit": "points/s", "cores": oracle.num_threads(), "kind": "oracle",
+                         "sample": f"oracle_optimize_graph on the same {n} x {k} graph, {cpu_sec:.2f} s"},
+    }
+    print(json.dumps(res))
+    if not same:
+        print("bench.py: the search graph differs from the oracle's", file=sys.stderr)
+        sys.exit(1)
+
+
 def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (nothing here uses a second GPU)",
               file=sys.stderr)
         sys.exit(2)
+    if a.op == "optimize":
+        return bench_optimize(a)
     import numpy as np
     import torch
     from paper_2605_27691_amd import knng, workloads

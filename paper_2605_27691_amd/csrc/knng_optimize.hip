@@ -10,9 +10,11 @@
 //   4. Row v of G^s = the first d_out - d_out/2 entries of P(v), then R(v) in order, then the
 //      rest of P(v), skipping -1 and ids already in the row, until it has d_out entries.
 //
-// k_opt_prune (1, 2; one wavefront per point), a three-kernel prefix sum over the in-degrees,
-// k_opt_fill (3: an edge list per point, in arrival order), k_opt_merge (3, 4; one wavefront per
-// point picks the smallest (p, u) words of its list, so the result does not depend on that order).
+// k_opt_prune (1, 2; one wavefront per point; an edge also takes its place in its target's list
+// here, with the one atomic that counts the in-degree), a three-kernel prefix sum over the
+// in-degrees, k_opt_fill (3: writes every edge's (p, u) word to its place), k_opt_merge (3, 4; one
+// wavefront per point picks the smallest words of its list, so the result does not depend on
+// the order the places were handed out in).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -34,7 +36,7 @@ constexpr int OPT_HT = 128;                       // hash slots per wavefront (>
 // repeated id in w's row sets the same bit again, so "some r < j" is counted once.
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_opt_prune(const int32_t* __restrict__ ids, int64_t n, int k, int d_out, int32_t* __restrict__ P,
+k_opt_prune(const int32_t* __restrict__ ids, int64_t n, int k, int d_out, int2* __restrict__ P,
             uint32_t* __restrict__ deg)
 {
     __shared__ int hkey[4][OPT_HT];
@@ -73,17 +75,25 @@ k_opt_prune(const int32_t* __restrict__ ids, int64_t n, int k, int d_out, int32_
     const bool valid = inr && lookup(my) == lane;
     const u64 vmask = __ballot(valid);
 
+    // four neighbour rows per step, the next step's rows in flight meanwhile
+    int xn[4];
+    auto issue = [&](int i0) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int i = i0 + t;
+            xn[t] = -1;
+            if (i < k && ((vmask >> i) & 1ull)) {              // uniform
+                const int wi = __builtin_amdgcn_readlane(my, i);
+                if (lane < k) xn[t] = ids[(int64_t)wi * k + lane];
+            }
+        }
+    };
+    issue(0);
     for (int i0 = 0; i0 < k; i0 += 4) {
         int x[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {                          // four rows in flight
-            const int i = i0 + t;
-            x[t] = -1;
-            if (i < k && ((vmask >> i) & 1ull)) {              // uniform
-                const int wi = __builtin_amdgcn_readlane(my, i);
-                if (lane < k) x[t] = ids[(int64_t)wi * k + lane];
-            }
-        }
+        for (int t = 0; t < 4; ++t) x[t] = xn[t];
+        if (i0 + 4 < k) issue(i0 + 4);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int i = i0 + t;
@@ -99,8 +109,9 @@ k_opt_prune(const int32_t* __restrict__ ids, int64_t n, int k, int d_out, int32_
     int rank = 0;
     for (int j = 0; j < k; ++j) rank += bcast32(key, j) < key ? 1 : 0;
     if (lane < k && rank < d_out) {
-        P[u * d_out + rank] = valid ? my : -1;
-        if (valid) atomicAdd(&deg[my], 1u);
+        // {neighbour, place of this edge in the neighbour's reverse list}
+        const int place = valid ? (int)atomicAdd(&deg[my], 1u) : 0;
+        P[u * d_out + rank] = int2{valid ? my : -1, place};
     }
 }
 
@@ -181,20 +192,18 @@ k_opt_scan(const uint32_t* __restrict__ deg, int64_t n, const u64* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------
-// k_opt_fill: edge (u, p) -> v appends the word (p << 32 | u) to v's list; the in-degree counter
-// is counted down to hand out the places, so it ends at zero.
+// k_opt_fill: edge (u, p) -> v writes the word (p << 32 | u) to its place in v's list
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_opt_fill(const int32_t* __restrict__ P, int64_t total, int d_out, uint32_t* __restrict__ deg,
-           const u64* __restrict__ start, u64* __restrict__ E)
+k_opt_fill(const int2* __restrict__ P, int64_t total, int d_out, const u64* __restrict__ start,
+           u64* __restrict__ E)
 {
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int v = P[e];
-        if (v < 0) continue;
+        const int2 vp = P[e];
+        if (vp.x < 0) continue;
         const int64_t u = e / d_out;
         const int p = (int)(e - u * d_out);
-        const uint32_t place = atomicSub(&deg[v], 1u) - 1u;
-        E[start[v] + place] = ((u64)(uint32_t)p << 32) | (u64)(uint32_t)u;
+        E[start[vp.x] + (u64)(uint32_t)vp.y] = ((u64)(uint32_t)p << 32) | (u64)(uint32_t)u;
     }
 }
 
@@ -205,7 +214,7 @@ k_opt_fill(const int32_t* __restrict__ P, int64_t total, int d_out, uint32_t* __
 // keeps the 64 smallest words above the last batch's largest; then the rest of P(v).
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_opt_merge(const int32_t* __restrict__ P, const u64* __restrict__ start, const u64* __restrict__ E,
+k_opt_merge(const int2* __restrict__ P, const u64* __restrict__ start, const u64* __restrict__ E,
             int64_t n, int d_out, int32_t* __restrict__ out)
 {
     __shared__ int rowb[4][WAVE];
@@ -215,7 +224,7 @@ k_opt_merge(const int32_t* __restrict__ P, const u64* __restrict__ start, const 
     int* row = rowb[w];
     const u64 lt = lanemask_lt();
     const int h = d_out / 2, nf = d_out - h;
-    const int pv = lane < d_out ? P[v * d_out + lane] : -1;
+    const int pv = lane < d_out ? P[v * d_out + lane].x : -1;
     int m;
     {
         const bool f = lane < nf && pv >= 0;
@@ -278,7 +287,7 @@ bool opt_plan(int64_t n, int32_t k, int32_t d_out, OptPlan* op)
     uint64_t off = 0;
     auto take = [&](uint64_t bytes) { uint64_t o = off; off = (off + bytes + 255) & ~255ull; return o; };
     op->nb = (n + SCAN_PER_BLOCK - 1) / SCAN_PER_BLOCK;
-    op->off_P = take((uint64_t)n * d_out * 4);
+    op->off_P = take((uint64_t)n * d_out * 8);
     op->off_deg = take((uint64_t)n * 4);
     op->off_start = take(((uint64_t)n + 1) * 8);
     op->off_E = take((uint64_t)n * d_out * 8);
@@ -303,7 +312,7 @@ extern "C" __attribute__((visibility("default"))) int knng_optimize_graph(const 
         return KNNG_EWORKSPACE;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     unsigned char* ws = static_cast<unsigned char*>(workspace_dev);
-    int32_t* P = reinterpret_cast<int32_t*>(ws + op.off_P);
+    int2* P = reinterpret_cast<int2*>(ws + op.off_P);
     uint32_t* deg = reinterpret_cast<uint32_t*>(ws + op.off_deg);
     u64* start = reinterpret_cast<u64*>(ws + op.off_start);
     u64* E = reinterpret_cast<u64*>(ws + op.off_E);
@@ -320,7 +329,7 @@ extern "C" __attribute__((visibility("default"))) int knng_optimize_graph(const 
     const int64_t total = n * d_out;
     int64_t fill_blocks = (total + 255) / 256;
     if (fill_blocks > 1048576) fill_blocks = 1048576;
-    hipLaunchKernelGGL(k_opt_fill, dim3((unsigned)fill_blocks), dim3(256), 0, st, P, total, d_out, deg, start, E);
+    hipLaunchKernelGGL(k_opt_fill, dim3((unsigned)fill_blocks), dim3(256), 0, st, P, total, d_out, start, E);
     if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e, "k_opt_fill launch");
     hipLaunchKernelGGL(k_opt_merge, dim3(row_blocks), dim3(256), 0, st, P, start, E, n, d_out, ids_out_dev);
     if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e, "k_opt_merge launch");
