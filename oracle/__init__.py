@@ -38,6 +38,9 @@ def lib():
         L.oracle_merge_rows.argtypes = [P, P, c_i32, P, P, c_i32, c_i64, c_i32, P, P]
         L.oracle_optimize_graph.restype = ctypes.c_int
         L.oracle_optimize_graph.argtypes = [P, c_i64, c_i32, c_i32, P]
+        L.oracle_graph_search.restype = ctypes.c_int
+        L.oracle_graph_search.argtypes = [P, c_i64, c_i32, c_i32, P, c_i32, P, c_i64, P, c_i32,
+                                          c_i32, c_i32, c_i32, c_i32, P, P, P]
         _lib = L
     return _lib
 
@@ -124,6 +127,23 @@ def optimize_graph(ids, d_out):
     if rc != 0:
         raise ValueError(f"oracle_optimize_graph: bad arguments (rc={rc})")
     return out
+
+
+def graph_search(points, graph, queries, starts, k_s, itopk, width=1, max_iters=64, metric=L2SQ):
+    """Greedy search of `queries` over `graph` ([n][deg] ids).  -> (ids, dists, iterations per query)."""
+    x, qv = _f32(points), _f32(queries)
+    g, st = _i32(graph), _i32(starts)
+    n, d = x.shape
+    nq = qv.shape[0]
+    assert qv.shape[1] == d and g.shape[0] == n and st.shape[0] == nq
+    ids = np.empty((nq, k_s), dtype=np.int32)
+    dists = np.empty((nq, k_s), dtype=np.float32)
+    iters = np.empty(nq, dtype=np.int32)
+    rc = lib().oracle_graph_search(_p(x), n, d, metric, _p(g), g.shape[1], _p(qv), nq, _p(st), st.shape[1],
+                                   k_s, itopk, width, max_iters, _p(ids), _p(dists), _p(iters))
+    if rc != 0:
+        raise ValueError(f"oracle_graph_search: bad arguments (rc={rc})")
+    return ids, dists, iters
 
 
 def check_graph(points, ids, dists, metric=L2SQ, rel_tol=1e-5, rows=None):

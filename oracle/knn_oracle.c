@@ -16,6 +16,7 @@
  *                        single-owner merge, step by step              (Sec. 3.1, 3.1.1)
  *   oracle_merge_rows    a graph's rows updated with search results R  (Sec. 4.3 step 4, 4.4)
  *   oracle_optimize_graph  k-NN graph G -> search graph G^s            (Sec. 3.3)
+ *   oracle_graph_search  greedy graph search for query points           (Sec. 3.2)
  *
  * Pin status: every function is pinned by tests that do not go through this
  * file (closed forms, exhaustive enumeration in numpy on tiny inputs, integer
@@ -689,5 +690,80 @@ int oracle_optimize_graph(const int32_t *ids, int64_t n, int32_t k, int32_t d_ou
         while (m < d_out) o[m++] = -1;
     }
     free(P); free(start); free(R); free(fill);
+    return 0;
+}
+
+/* ======================================================================== */
+/* Graph-based ANN search (Sec. 3.2): start from given points of the graph,  */
+/* greedily explore by visiting neighbours of points already visited, until  */
+/* no closer neighbours turn up or the iteration cap is reached; k_s results */
+/* per query.  The section describes the search in these words and leaves    */
+/* the bookkeeping open; this is the build's reading of it:                  */
+/*                                                                           */
+/* Per query a list of at most L entries (distance, id, expanded?) is kept   */
+/* ascending by (fp32 distance, id), ids distinct.  "Offer x" means: if x is */
+/* a valid id (in [0,n)) not in the list, evaluate sigma(query, x) and keep  */
+/* the L smallest of the list and x.                                         */
+/*   start: offer starts[q][0 .. n_starts) in order.                         */
+/*   iteration (at most max_iters): take the first `width` entries of the    */
+/*   list that are not yet expanded (stop if there is none), mark them       */
+/*   expanded, then for each of them in list order offer its graph row in    */
+/*   row order.                                                              */
+/* Result: the first k_s entries (padded with id -1 and distance +inf).      */
+/* iters_out (optional): iterations performed per query.                     */
+/* Returns 0, or -1 on bad arguments.                                        */
+/* ------------------------------------------------------------------------ */
+int oracle_graph_search(const float *points, int64_t n, int32_t d, int32_t metric,
+                        const int32_t *graph, int32_t deg,
+                        const float *queries, int64_t nq,
+                        const int32_t *starts, int32_t n_starts,
+                        int32_t k_s, int32_t L, int32_t width, int32_t max_iters,
+                        int32_t *ids_out, float *dists_out, int32_t *iters_out)
+{
+    if (!points || !graph || (!queries && nq > 0) || !starts || !ids_out || !dists_out) return -1;
+    if (n < 1 || d < 1 || deg < 1 || nq < 0 || n_starts < 1 || k_s < 1 || L < k_s || width < 1 || max_iters < 0)
+        return -1;
+    if (metric != ORACLE_L2SQ && metric != ORACLE_IP_UNIT && metric != ORACLE_COSINE) return -1;
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t q = 0; q < nq; ++q) {
+        const float *qv = queries + q * d;
+        int32_t *lid = (int32_t *)malloc((size_t)L * sizeof(int32_t));
+        float *ld = (float *)malloc((size_t)L * sizeof(float));
+        char *lex = (char *)malloc((size_t)L);
+        int32_t *par = (int32_t *)malloc((size_t)width * sizeof(int32_t));
+        int32_t len = 0, iters = 0;
+#define ORACLE_OFFER(x)                                                                     \
+        do {                                                                                    \
+            const int32_t x_ = (x);                                                             \
+            if (x_ < 0 || (int64_t)x_ >= n) break;                                              \
+            int in_ = 0;                                                                        \
+            for (int32_t t_ = 0; t_ < len; ++t_) in_ |= lid[t_] == x_;                          \
+            if (in_) break;                                                                     \
+            const float dx_ = oracle_distance(qv, points + (int64_t)x_ * d, d, metric);         \
+            int32_t pos_ = len;                                                                 \
+            while (pos_ > 0 && key_less(dx_, x_, ld[pos_ - 1], lid[pos_ - 1])) --pos_;          \
+            if (pos_ >= L) break;                                                               \
+            const int32_t last_ = len < L ? len : L - 1;                                        \
+            for (int32_t t_ = last_; t_ > pos_; --t_) { lid[t_] = lid[t_ - 1]; ld[t_] = ld[t_ - 1]; lex[t_] = lex[t_ - 1]; } \
+            lid[pos_] = x_; ld[pos_] = dx_; lex[pos_] = 0;                                      \
+            if (len < L) ++len;                                                                 \
+        } while (0)
+        for (int32_t t = 0; t < n_starts; ++t) ORACLE_OFFER(starts[q * n_starts + t]);
+        for (; iters < max_iters; ++iters) {
+            int32_t np = 0;
+            for (int32_t t = 0; t < len && np < width; ++t)
+                if (!lex[t]) { lex[t] = 1; par[np++] = lid[t]; }
+            if (np == 0) break;
+            for (int32_t a = 0; a < np; ++a)
+                for (int32_t j = 0; j < deg; ++j) ORACLE_OFFER(graph[(int64_t)par[a] * deg + j]);
+        }
+#undef ORACLE_OFFER
+        for (int32_t t = 0; t < k_s; ++t) {
+            ids_out[q * k_s + t] = t < len ? lid[t] : -1;
+            dists_out[q * k_s + t] = t < len ? ld[t] : INFINITY;
+        }
+        if (iters_out) iters_out[q] = iters;
+        free(lid); free(ld); free(lex); free(par);
+    }
     return 0;
 }

@@ -557,3 +557,110 @@ def test_optimize_graph_invariants_and_a_hub():
         assert g[7][d_out - h:].tolist() == want_rev
     with pytest.raises(ValueError):
         oracle.optimize_graph(ids, 17)
+
+
+# ------------------------------------------------------------------ graph_search (Sec. 3.2)
+def _line_graph():
+    x = np.arange(10, dtype=np.float32)[:, None]
+    g = np.array([[i - 1, i + 1, i - 2, i + 2] for i in range(10)], np.int32)
+    g[(g < 0) | (g > 9)] = -1
+    return x, g
+
+
+def test_graph_search_hand_fixture_on_a_line(golden_dir):
+    x, g = _line_graph()
+    q = np.array([[6.4]], np.float32)
+    st = np.array([[0]], np.int32)
+    with open(os.path.join(golden_dir, "graph_search_line.txt")) as f:
+        lines = [l.split() for l in f if l.strip() and not l.startswith("#")]
+    for t in lines:
+        width = int(t[1])
+        cap = int(t[t.index("cap") + 1]) if "cap" in t else 100
+        want_ids = [int(v) for v in t[t.index("ids") + 1:]]
+        ids, dists, iters = oracle.graph_search(x, g, q, st, 3, 3, width, cap)
+        assert ids[0].tolist() == want_ids
+        if "iterations" in t:
+            assert iters[0] == int(t[t.index("iterations") + 1])
+        # one term each: (p - q)^2 in double from the fp32 inputs, rounded once
+        assert dists[0].tolist() == [np.float32((np.float64(np.float32(6.4)) - v) ** 2) for v in want_ids]
+
+
+def test_graph_search_complete_graph_is_brute_force():
+    # every point adjacent to every other and a list that holds them all: the result is the
+    # exact k_s nearest under (distance, id), whatever the start; integer data, exact in int64
+    rng = np.random.default_rng(31)
+    n, d, nq, k_s = 40, 6, 25, 7
+    x = rng.integers(-9, 10, (n, d)).astype(np.float32)
+    x[11] = x[3]                                              # a tie on the distance: lower id first
+    q = rng.integers(-9, 10, (nq, d)).astype(np.float32)
+    g = np.array([[j for j in range(n) if j != i] for i in range(n)], np.int32)
+    st = rng.integers(0, n, (nq, 1)).astype(np.int32)
+    ids, dists, iters = oracle.graph_search(x, g, q, st, k_s, n, 1, 1000)
+    dd = ((q[:, None, :].astype(np.int64) - x[None, :, :].astype(np.int64)) ** 2).sum(-1)
+    for r in range(nq):
+        order = sorted((int(dd[r, j]), j) for j in range(n))[:k_s]
+        assert ids[r].tolist() == [j for _, j in order]
+        assert dists[r].tolist() == [float(l) for l, _ in order]
+    assert np.all(iters == n)                                 # every entry of the list gets expanded once
+
+
+def _search_by_pool(x, g, q, starts, k_s, L, width, max_iters, metric):
+    """The same definition from the other side: remember everything ever evaluated; the list
+    is the L best of that pool.  Pure Python with a visited set, tiny inputs."""
+    n = x.shape[0]
+    pool, expanded = {}, set()
+    def offer(v):
+        if 0 <= v < n and v not in pool:
+            pool[int(v)] = float(oracle.distance(q, x[v], metric))
+    def current():
+        return sorted((l, v) for v, l in pool.items())[:L]
+    for v in starts:
+        offer(v)
+    iters = 0
+    while iters < max_iters:
+        parents = [v for _, v in current() if v not in expanded][:width]
+        if not parents:
+            break
+        expanded.update(parents)
+        for p in parents:
+            for v in g[p]:
+                offer(v)
+        iters += 1
+    best = current()[:k_s]
+    ids = [v for _, v in best] + [-1] * (k_s - len(best))
+    dists = [np.float32(l) for l, _ in best] + [np.float32(np.inf)] * (k_s - len(best))
+    return ids, dists, iters
+
+
+@pytest.mark.parametrize("metric", (oracle.L2SQ, oracle.IP_UNIT))
+def test_graph_search_against_the_pool_formulation(metric):
+    rng = np.random.default_rng(32 + metric)
+    for n, d, deg, nq, k_s, L, width, cap, ns in [(60, 4, 6, 12, 5, 8, 1, 100, 3), (80, 3, 8, 10, 8, 8, 2, 100, 1),
+                                                  (50, 5, 5, 10, 3, 16, 3, 4, 6), (30, 2, 4, 8, 4, 6, 1, 0, 5),
+                                                  (40, 6, 10, 8, 10, 64, 4, 100, 2)]:
+        x = rng.standard_normal((n, d)).astype(np.float32)
+        q = rng.standard_normal((nq, d)).astype(np.float32)
+        if metric == oracle.IP_UNIT:
+            x /= np.linalg.norm(x, axis=1, keepdims=True)
+            q /= np.linalg.norm(q, axis=1, keepdims=True)
+        g = oracle.brute_knn(x, deg, metric)[0]
+        g[rng.random(g.shape) < 0.1] = -1                     # padding
+        g[rng.random(g.shape) < 0.05] = n + 3                 # out of range
+        g[:, 1] = np.where(rng.random(n) < 0.2, g[:, 0], g[:, 1])   # repeats
+        st = rng.integers(-1, n, (nq, ns)).astype(np.int32)
+        ids, dists, iters = oracle.graph_search(x, g, q, st, k_s, L, width, cap, metric)
+        for r in range(nq):
+            wi, wd, wit = _search_by_pool(x, g, q[r], st[r], k_s, L, width, cap, metric)
+            assert ids[r].tolist() == wi and dists[r].tolist() == wd and iters[r] == wit
+
+
+def test_graph_search_argument_checks():
+    x, g = _line_graph()
+    q = np.array([[1.0]], np.float32)
+    st = np.array([[0]], np.int32)
+    with pytest.raises(ValueError):
+        oracle.graph_search(x, g, q, st, 4, 3)                # k_s > L
+    with pytest.raises(ValueError):
+        oracle.graph_search(x, g, q, st, 1, 3, width=0)
+    ids, dists, _ = oracle.graph_search(x, g, q, np.array([[-1]], np.int32), 2, 3)
+    assert ids.tolist() == [[-1, -1]] and np.all(np.isinf(dists))   # nothing to start from
