@@ -219,6 +219,42 @@ int knng_optimize_graph(const int32_t *ids_dev, int64_t n, int32_t k, int32_t d_
                         int32_t *ids_out_dev, void *workspace_dev, uint64_t workspace_bytes,
                         void *stream);
 
+/*
+ * Graph-based approximate nearest-neighbour search for query points (Sec. 3.2: the
+ * search starts from selected points of the graph and greedily explores it by
+ * visiting neighbours of previously visited points, until no closer neighbours are
+ * found or a stopping criterion is met; k_s neighbours per query).  The bookkeeping,
+ * which the section leaves open, is fixed as follows.
+ *
+ * Per query a list of at most itopk entries (distance, id, expanded or not) is kept
+ * ascending by (fp32 distance, id), ids distinct.  "Offer x": if x is a valid id (in
+ * [0,n)) that is not in the list, sigma(query, x) is evaluated (the fp64 recipe
+ * above) and the itopk smallest of the list and x are kept.
+ *   start:     starts_dev[q][0 .. n_starts) are offered in order;
+ *   iteration: the first `width` entries of the list that are not yet expanded are
+ *              marked expanded (none: the search ends), then the graph row of each
+ *              is offered, in list order and row order; at most max_iters iterations.
+ * Result: the first k_s entries of the list, padded with id -1 / distance +inf.
+ * The start points are an input: the caller draws them (the paper picks them at
+ * random), so the result is a function of the arguments alone.
+ *
+ * points_dev [n][d] fp32, graph_dev [n][deg] int32 (a k-NN graph or a search graph;
+ * entries outside [0,n) are ignored), queries_dev [nq][d] fp32, starts_dev
+ * [nq][n_starts] int32: device, read-only.  ids_out_dev [nq][k_s] int32,
+ * dists_out_dev [nq][k_s] fp32: device, written in full.  iters_out_dev [nq] int32
+ * (optional, NULL to skip): iterations performed per query.
+ * 1 <= k_s <= itopk <= KNNG_MAX_K; deg, n_starts, width in [1, KNNG_MAX_K];
+ * max_iters >= 0; d <= 8192; nq = 0 is a no-op.  Needs no workspace.
+ * Errors: KNNG_EINVAL, KNNG_EHIP.
+ */
+int knng_graph_search(const float *points_dev, int64_t n, int32_t d, int32_t metric,
+                      const int32_t *graph_dev, int32_t deg,
+                      const float *queries_dev, int64_t nq,
+                      const int32_t *starts_dev, int32_t n_starts,
+                      int32_t k_s, int32_t itopk, int32_t width, int32_t max_iters,
+                      int32_t *ids_out_dev, float *dists_out_dev, int32_t *iters_out_dev,
+                      void *stream);
+
 /* Text for a return code; for KNNG_EHIP the text of the last HIP failure on this thread. */
 const char *knng_strerror(int code);
 

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libknng.so")
-SOURCES = ("knng_build.hip", "knng_brute.hip", "knng_recall.hip", "knng_merge.hip", "knng_optimize.hip")
+SOURCES = ("knng_build.hip", "knng_brute.hip", "knng_recall.hip", "knng_merge.hip", "knng_optimize.hip", "knng_search.hip")
 HEADERS = ("knng_device.h", "knng_host.h", "knng_join_wave.h", os.path.join("..", "..", "include", "knng.h"))
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

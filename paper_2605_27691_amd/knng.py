@@ -50,7 +50,7 @@ class Params(ctypes.Structure):
 EXPORTS = ("knng_build_workspace_bytes", "knng_build_knn_graph", "knng_build_knn_graph_u8",
            "knng_brute_workspace_bytes",
            "knng_brute_knn", "knng_graph_recall", "knng_merge_graphs", "knng_optimize_workspace_bytes",
-           "knng_optimize_graph", "knng_strerror", "knng_version")
+           "knng_optimize_graph", "knng_graph_search", "knng_strerror", "knng_version")
 
 _lib = None
 
@@ -87,6 +87,8 @@ def load():
     L.knng_optimize_workspace_bytes.argtypes = [i64, i32, i32]
     L.knng_optimize_graph.restype = ctypes.c_int
     L.knng_optimize_graph.argtypes = [_P, i64, i32, i32, _P, _P, u64, _P]
+    L.knng_graph_search.restype = ctypes.c_int
+    L.knng_graph_search.argtypes = [_P, i64, i32, i32, _P, i32, _P, i64, _P, i32, i32, i32, i32, i32, _P, _P, _P, _P]
     L.knng_strerror.restype = ctypes.c_char_p
     L.knng_strerror.argtypes = [ctypes.c_int]
     L.knng_version.restype = ctypes.c_int
@@ -283,3 +285,25 @@ def knng_optimize_graph(ids, d_out, workspace=None, ids_out=None):
     _check(L.knng_optimize_graph(_ptr(ids), n, k, d_out, _ptr(ids_out), _ptr(workspace), workspace.numel(),
                                  _stream()))
     return ids_out
+
+
+def knng_graph_search(points, graph, queries, starts, k_s, itopk, width=1, max_iters=64, metric=L2SQ,
+                      want_iters=False):
+    """Greedy search of `queries` ([nq][d] fp32) over `graph` ([n][deg] int32) from `starts`
+    ([nq][n_starts] int32); all GPU tensors.  -> (ids [nq][k_s], dists [nq][k_s][, iterations])."""
+    L = load()
+    points = _dev(points, torch.float32, "points")
+    queries = _dev(queries, torch.float32, "queries")
+    graph = _dev(graph, torch.int32, "graph")
+    starts = _dev(starts, torch.int32, "starts")
+    n, d = points.shape
+    nq = queries.shape[0]
+    if queries.shape[1] != d or graph.shape[0] != n or starts.shape[0] != nq:
+        raise KnngError(-1)
+    ids = torch.empty((nq, k_s), dtype=torch.int32, device=points.device)
+    dists = torch.empty((nq, k_s), dtype=torch.float32, device=points.device)
+    iters = torch.empty(nq, dtype=torch.int32, device=points.device) if want_iters else None
+    _check(L.knng_graph_search(_ptr(points), n, d, metric, _ptr(graph), graph.shape[1], _ptr(queries), nq,
+                               _ptr(starts), starts.shape[1], k_s, itopk, width, max_iters, _ptr(ids),
+                               _ptr(dists), _ptr(iters), _stream()))
+    return (ids, dists, iters) if want_iters else (ids, dists)

@@ -1,0 +1,106 @@
+"""GPU parity of knng_graph_search against the CPU oracle.
+
+Both sides evaluate distances with the fp64 recipe and order by (fp32 distance, id), so every
+decision is the same: ids, distances and iteration counts are compared bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_27691_amd import knng, workloads
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _gpu(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+
+
+def _both(x, g, q, st, k_s, L, width, cap, metric=0):
+    gi, gd, git = knng.knng_graph_search(_gpu(x), _gpu(g), _gpu(q), _gpu(st), k_s, L, width, cap, metric,
+                                         want_iters=True)
+    oi, od, oit = oracle.graph_search(x, g, q, st, k_s, L, width, cap, metric)
+    return (gi.cpu().numpy(), gd.cpu().numpy(), git.cpu().numpy()), (oi, od, oit)
+
+
+def _assert_same(a, b):
+    assert np.array_equal(a[0], b[0])
+    assert np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
+    assert np.array_equal(a[2], b[2])
+
+
+def _data(n, d, nq, metric, seed):
+    rng = np.random.default_rng(seed)
+    c = rng.standard_normal((10, d)) * 3.0
+    x = (c[rng.integers(0, 10, n)] + rng.standard_normal((n, d))).astype(np.float32)
+    q = (c[rng.integers(0, 10, nq)] + rng.standard_normal((nq, d))).astype(np.float32)
+    if metric == 1:
+        x = (x / np.linalg.norm(x, axis=1, keepdims=True)).astype(np.float32)
+        q = (q / np.linalg.norm(q, axis=1, keepdims=True)).astype(np.float32)
+    return x, q, rng
+
+
+@pytest.mark.parametrize("n,d,deg,nq,k_s,L,width,cap,ns,metric", [
+    (4000, 32, 16, 300, 10, 32, 1, 100, 8, 0),
+    (4000, 32, 16, 300, 16, 64, 2, 100, 16, 0),
+    (3000, 96, 32, 200, 32, 64, 1, 100, 32, 1),
+    (2000, 13, 8, 150, 5, 8, 3, 100, 1, 0),          # odd d: scalar loads
+    (2500, 128, 64, 101, 1, 1, 1, 100, 64, 0),       # a list of one entry, the widest rows and starts
+    (2000, 20, 12, 100, 12, 12, 64, 3, 5, 0),        # capped at three iterations, every entry a parent
+    (1500, 960, 24, 40, 8, 24, 1, 100, 4, 0),        # long vectors
+    (3000, 8, 10, 130, 4, 16, 1, 0, 6, 1),           # no iteration: the best of the start points
+])
+def test_search_bit_exact_against_the_oracle(n, d, deg, nq, k_s, L, width, cap, ns, metric):
+    x, q, rng = _data(n, d, nq, metric, seed=n + d + deg)
+    g = oracle.brute_knn(x, deg, metric)[0]
+    st = rng.integers(0, n, (nq, ns)).astype(np.int32)
+    got, want = _both(x, g, q, st, k_s, L, width, cap, metric)
+    _assert_same(got, want)
+
+
+def test_search_graph_with_padding_repeats_and_bad_starts():
+    x, q, rng = _data(1200, 16, 120, 0, seed=9)
+    g = oracle.brute_knn(x, 12, 0)[0]
+    g[rng.random(g.shape) < 0.15] = -1
+    g[rng.random(g.shape) < 0.05] = 1200 + 7
+    g[:, 3] = np.where(rng.random(1200) < 0.3, g[:, 2], g[:, 3])
+    st = rng.integers(-2, 1202, (120, 7)).astype(np.int32)
+    st[5] = -1                                                   # nothing to start from
+    st[6] = st[6, 0]                                             # the same start seven times
+    got, want = _both(x, g, q, st, 9, 20, 2, 100)
+    _assert_same(got, want)
+    assert got[0][5].tolist() == [-1] * 9 and np.all(np.isinf(got[1][5]))
+
+
+def test_search_on_the_search_graph_of_a_built_graph_two_partitions():
+    # one level of the paper's scheme without the network: the points of partition B search
+    # the optimised graph of partition A
+    x, w = workloads.make(0)
+    a, b = x[:12_000], x[12_000:]
+    ids, _, _ = knng.knng_build_knn_graph(_gpu(a), 16, w.metric, k_build=32, seed=3)
+    gs = knng.knng_optimize_graph(ids, 16).cpu().numpy()
+    rng = np.random.default_rng(4)
+    # the workload's 16 clusters are islands of the graph: enough starts to land in the right one
+    st = rng.integers(0, len(a), (len(b), 64)).astype(np.int32)
+    got, want = _both(a, gs, b, st, 16, 64, 1, 100, w.metric)
+    _assert_same(got, want)
+    ex = np.argsort(((b[:2000, None, :].astype(np.float64) - a[None, :, :]) ** 2).sum(-1), axis=1)[:, :16]
+    rec = np.mean([len(set(p.tolist()) & set(e.tolist())) / 16 for p, e in zip(got[0][:2000], ex)])
+    assert rec >= 0.95, rec
+
+
+def test_search_argument_errors():
+    x, q, rng = _data(500, 8, 10, 0, seed=1)
+    g = oracle.brute_knn(x, 8, 0)[0]
+    st = rng.integers(0, 500, (10, 4)).astype(np.int32)
+    for kw in (dict(k_s=9, itopk=8), dict(k_s=4, itopk=65), dict(k_s=4, itopk=8, width=0),
+               dict(k_s=4, itopk=8, max_iters=-1), dict(k_s=4, itopk=8, metric=2)):
+        with pytest.raises(knng.KnngError):
+            knng.knng_graph_search(_gpu(x), _gpu(g), _gpu(q), _gpu(st), **kw)
+    with pytest.raises(knng.KnngError):
+        knng.knng_graph_search(_gpu(x), _gpu(g), _gpu(q[:, :7].copy()), _gpu(st), 4, 8)
+    ids, dists = knng.knng_graph_search(_gpu(x), _gpu(g), _gpu(q[:0]), _gpu(st[:0]), 4, 8)
+    assert ids.shape == (0, 4)
