@@ -242,7 +242,8 @@ int knng_optimize_graph(const int32_t *ids_dev, int64_t n, int32_t k, int32_t d_
  * entries outside [0,n) are ignored), queries_dev [nq][d] fp32, starts_dev
  * [nq][n_starts] int32: device, read-only.  ids_out_dev [nq][k_s] int32,
  * dists_out_dev [nq][k_s] fp32: device, written in full.  iters_out_dev [nq] int32
- * (optional, NULL to skip): iterations performed per query.
+ * and evals_out_dev [nq] int32 (optional, NULL to skip): iterations performed and
+ * distances evaluated per query.
  * 1 <= k_s <= itopk <= KNNG_MAX_K; deg, n_starts, width in [1, KNNG_MAX_K];
  * max_iters >= 0; d <= 8192; nq = 0 is a no-op.  Needs no workspace.
  * Errors: KNNG_EINVAL, KNNG_EHIP.
@@ -253,7 +254,7 @@ int knng_graph_search(const float *points_dev, int64_t n, int32_t d, int32_t met
                       const int32_t *starts_dev, int32_t n_starts,
                       int32_t k_s, int32_t itopk, int32_t width, int32_t max_iters,
                       int32_t *ids_out_dev, float *dists_out_dev, int32_t *iters_out_dev,
-                      void *stream);
+                      int32_t *evals_out_dev, void *stream);
 
 /* Text for a return code; for KNNG_EHIP the text of the last HIP failure on this thread. */
 const char *knng_strerror(int code);

@@ -40,7 +40,7 @@ def lib():
         L.oracle_optimize_graph.argtypes = [P, c_i64, c_i32, c_i32, P]
         L.oracle_graph_search.restype = ctypes.c_int
         L.oracle_graph_search.argtypes = [P, c_i64, c_i32, c_i32, P, c_i32, P, c_i64, P, c_i32,
-                                          c_i32, c_i32, c_i32, c_i32, P, P, P]
+                                          c_i32, c_i32, c_i32, c_i32, P, P, P, P]
         _lib = L
     return _lib
 
@@ -129,8 +129,9 @@ def optimize_graph(ids, d_out):
     return out
 
 
-def graph_search(points, graph, queries, starts, k_s, itopk, width=1, max_iters=64, metric=L2SQ):
-    """Greedy search of `queries` over `graph` ([n][deg] ids).  -> (ids, dists, iterations per query)."""
+def graph_search(points, graph, queries, starts, k_s, itopk, width=1, max_iters=64, metric=L2SQ, want_evals=False):
+    """Greedy search of `queries` over `graph` ([n][deg] ids).
+    -> (ids, dists, iterations per query[, distance evaluations per query])."""
     x, qv = _f32(points), _f32(queries)
     g, st = _i32(graph), _i32(starts)
     n, d = x.shape
@@ -139,11 +140,12 @@ def graph_search(points, graph, queries, starts, k_s, itopk, width=1, max_iters=
     ids = np.empty((nq, k_s), dtype=np.int32)
     dists = np.empty((nq, k_s), dtype=np.float32)
     iters = np.empty(nq, dtype=np.int32)
+    evals = np.empty(nq, dtype=np.int32)
     rc = lib().oracle_graph_search(_p(x), n, d, metric, _p(g), g.shape[1], _p(qv), nq, _p(st), st.shape[1],
-                                   k_s, itopk, width, max_iters, _p(ids), _p(dists), _p(iters))
+                                   k_s, itopk, width, max_iters, _p(ids), _p(dists), _p(iters), _p(evals))
     if rc != 0:
         raise ValueError(f"oracle_graph_search: bad arguments (rc={rc})")
-    return ids, dists, iters
+    return (ids, dists, iters, evals) if want_evals else (ids, dists, iters)
 
 
 def check_graph(points, ids, dists, metric=L2SQ, rel_tol=1e-5, rows=None):

@@ -710,7 +710,9 @@ int oracle_optimize_graph(const int32_t *ids, int64_t n, int32_t k, int32_t d_ou
 /*   expanded, then for each of them in list order offer its graph row in    */
 /*   row order.                                                              */
 /* Result: the first k_s entries (padded with id -1 and distance +inf).      */
-/* iters_out (optional): iterations performed per query.                     */
+/* iters_out, evals_out (optional): iterations performed per query, and the   */
+/* distances a batch-wise evaluation needs: per batch (the start ids; one     */
+/* graph row) the valid, distinct ids that are not in the list before it.     */
 /* Returns 0, or -1 on bad arguments.                                        */
 /* ------------------------------------------------------------------------ */
 int oracle_graph_search(const float *points, int64_t n, int32_t d, int32_t metric,
@@ -718,7 +720,7 @@ int oracle_graph_search(const float *points, int64_t n, int32_t d, int32_t metri
                         const float *queries, int64_t nq,
                         const int32_t *starts, int32_t n_starts,
                         int32_t k_s, int32_t L, int32_t width, int32_t max_iters,
-                        int32_t *ids_out, float *dists_out, int32_t *iters_out)
+                        int32_t *ids_out, float *dists_out, int32_t *iters_out, int32_t *evals_out)
 {
     if (!points || !graph || (!queries && nq > 0) || !starts || !ids_out || !dists_out) return -1;
     if (n < 1 || d < 1 || deg < 1 || nq < 0 || n_starts < 1 || k_s < 1 || L < k_s || width < 1 || max_iters < 0)
@@ -731,7 +733,7 @@ int oracle_graph_search(const float *points, int64_t n, int32_t d, int32_t metri
         float *ld = (float *)malloc((size_t)L * sizeof(float));
         char *lex = (char *)malloc((size_t)L);
         int32_t *par = (int32_t *)malloc((size_t)width * sizeof(int32_t));
-        int32_t len = 0, iters = 0;
+        int32_t len = 0, iters = 0, evals = 0;
 #define ORACLE_OFFER(x)                                                                     \
         do {                                                                                    \
             const int32_t x_ = (x);                                                             \
@@ -748,21 +750,34 @@ int oracle_graph_search(const float *points, int64_t n, int32_t d, int32_t metri
             lid[pos_] = x_; ld[pos_] = dx_; lex[pos_] = 0;                                      \
             if (len < L) ++len;                                                                 \
         } while (0)
+#define ORACLE_COUNT(row, cnt)                                                              \
+        for (int32_t a_ = 0; a_ < (cnt); ++a_) {                                                \
+            const int32_t x_ = (row)[a_];                                                       \
+            int skip_ = x_ < 0 || (int64_t)x_ >= n;                                             \
+            for (int32_t b_ = 0; b_ < a_ && !skip_; ++b_) skip_ = (row)[b_] == x_;              \
+            for (int32_t t_ = 0; t_ < len && !skip_; ++t_) skip_ = lid[t_] == x_;               \
+            evals += !skip_;                                                                    \
+        }
+        ORACLE_COUNT(starts + q * n_starts, n_starts)
         for (int32_t t = 0; t < n_starts; ++t) ORACLE_OFFER(starts[q * n_starts + t]);
         for (; iters < max_iters; ++iters) {
             int32_t np = 0;
             for (int32_t t = 0; t < len && np < width; ++t)
                 if (!lex[t]) { lex[t] = 1; par[np++] = lid[t]; }
             if (np == 0) break;
-            for (int32_t a = 0; a < np; ++a)
+            for (int32_t a = 0; a < np; ++a) {
+                ORACLE_COUNT(graph + (int64_t)par[a] * deg, deg)
                 for (int32_t j = 0; j < deg; ++j) ORACLE_OFFER(graph[(int64_t)par[a] * deg + j]);
+            }
         }
 #undef ORACLE_OFFER
+#undef ORACLE_COUNT
         for (int32_t t = 0; t < k_s; ++t) {
             ids_out[q * k_s + t] = t < len ? lid[t] : -1;
             dists_out[q * k_s + t] = t < len ? ld[t] : INFINITY;
         }
         if (iters_out) iters_out[q] = iters;
+        if (evals_out) evals_out[q] = evals;
         free(lid); free(ld); free(lex); free(par);
     }
     return 0;

@@ -32,7 +32,7 @@ __global__ void __launch_bounds__(256)
 k_graph_search(const float* __restrict__ pts, int64_t n, int d, const int32_t* __restrict__ graph, int deg,
                const float* __restrict__ queries, int64_t nq, const int32_t* __restrict__ starts, int n_starts,
                int k_s, int L, int width, int max_iters, int32_t* __restrict__ ids_out,
-               float* __restrict__ dists_out, int32_t* __restrict__ iters_out)
+               float* __restrict__ dists_out, int32_t* __restrict__ iters_out, int32_t* __restrict__ evals_out)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ u64 lbuf[4][WAVE];
@@ -47,6 +47,7 @@ k_graph_search(const float* __restrict__ pts, int64_t n, int d, const int32_t* _
 
     u64 lk = EMPTY_KEY;                                         // list entry `lane`
     int len = 0;
+    int evals = 0;                                              // distances evaluated
 
     // offer the ids held by lanes < cnt
     auto offer_batch = [&](int id, int cnt) {
@@ -59,7 +60,9 @@ k_graph_search(const float* __restrict__ pts, int64_t n, int d, const int32_t* _
             const int lj = key_id(bcast64(lk, j));
             ok = ok && lj != id;
         }
-        if (__ballot(ok) == 0ull) return;
+        const u64 okm = __ballot(ok);
+        if (okm == 0ull) return;
+        evals += __popcll(okm);
         float dist = 0.0f;
         if (ok) {
             const float* __restrict__ b = pts + (int64_t)id * d;
@@ -154,6 +157,7 @@ k_graph_search(const float* __restrict__ pts, int64_t n, int d, const int32_t* _
         dists_out[q * k_s + lane] = lane < len ? key_dist(lk) : __uint_as_float(0x7f800000u);
     }
     if (iters_out && lane == 0) iters_out[q] = iters;
+    if (evals_out && lane == 0) evals_out[q] = evals;
 }
 
 }  // namespace knng
@@ -164,7 +168,7 @@ extern "C" __attribute__((visibility("default"))) int knng_graph_search(const fl
                                  const int32_t* graph_dev, int32_t deg, const float* queries_dev, int64_t nq,
                                  const int32_t* starts_dev, int32_t n_starts, int32_t k_s, int32_t itopk,
                                  int32_t width, int32_t max_iters, int32_t* ids_out_dev, float* dists_out_dev,
-                                 int32_t* iters_out_dev, void* stream)
+                                 int32_t* iters_out_dev, int32_t* evals_out_dev, void* stream)
 {
     if (!points_dev || !graph_dev || nq < 0) return KNNG_EINVAL;
     if (nq > 0 && (!queries_dev || !starts_dev || !ids_out_dev || !dists_out_dev)) return KNNG_EINVAL;
@@ -187,7 +191,7 @@ extern "C" __attribute__((visibility("default"))) int knng_graph_search(const fl
     }
     const unsigned blocks = (unsigned)((nq + 3) / 4);
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, points_dev, n, d, graph_dev, deg, queries_dev, nq,
-                       starts_dev, n_starts, k_s, itopk, width, max_iters, ids_out_dev, dists_out_dev, iters_out_dev);
+                       starts_dev, n_starts, k_s, itopk, width, max_iters, ids_out_dev, dists_out_dev, iters_out_dev, evals_out_dev);
     if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e, "k_graph_search launch");
     if ((e = hipStreamSynchronize(st)) != hipSuccess) return set_hip_error(e, "hipStreamSynchronize");
     return KNNG_OK;

@@ -88,7 +88,7 @@ def load():
     L.knng_optimize_graph.restype = ctypes.c_int
     L.knng_optimize_graph.argtypes = [_P, i64, i32, i32, _P, _P, u64, _P]
     L.knng_graph_search.restype = ctypes.c_int
-    L.knng_graph_search.argtypes = [_P, i64, i32, i32, _P, i32, _P, i64, _P, i32, i32, i32, i32, i32, _P, _P, _P, _P]
+    L.knng_graph_search.argtypes = [_P, i64, i32, i32, _P, i32, _P, i64, _P, i32, i32, i32, i32, i32, _P, _P, _P, _P, _P]
     L.knng_strerror.restype = ctypes.c_char_p
     L.knng_strerror.argtypes = [ctypes.c_int]
     L.knng_version.restype = ctypes.c_int
@@ -290,7 +290,8 @@ def knng_optimize_graph(ids, d_out, workspace=None, ids_out=None):
 def knng_graph_search(points, graph, queries, starts, k_s, itopk, width=1, max_iters=64, metric=L2SQ,
                       want_iters=False):
     """Greedy search of `queries` ([nq][d] fp32) over `graph` ([n][deg] int32) from `starts`
-    ([nq][n_starts] int32); all GPU tensors.  -> (ids [nq][k_s], dists [nq][k_s][, iterations])."""
+    ([nq][n_starts] int32); all GPU tensors.
+    -> (ids [nq][k_s], dists [nq][k_s][, iterations per query, distance evaluations per query])."""
     L = load()
     points = _dev(points, torch.float32, "points")
     queries = _dev(queries, torch.float32, "queries")
@@ -303,7 +304,8 @@ def knng_graph_search(points, graph, queries, starts, k_s, itopk, width=1, max_i
     ids = torch.empty((nq, k_s), dtype=torch.int32, device=points.device)
     dists = torch.empty((nq, k_s), dtype=torch.float32, device=points.device)
     iters = torch.empty(nq, dtype=torch.int32, device=points.device) if want_iters else None
+    evals = torch.empty(nq, dtype=torch.int32, device=points.device) if want_iters else None
     _check(L.knng_graph_search(_ptr(points), n, d, metric, _ptr(graph), graph.shape[1], _ptr(queries), nq,
                                _ptr(starts), starts.shape[1], k_s, itopk, width, max_iters, _ptr(ids),
-                               _ptr(dists), _ptr(iters), _stream()))
-    return (ids, dists, iters) if want_iters else (ids, dists)
+                               _ptr(dists), _ptr(iters), _ptr(evals), _stream()))
+    return (ids, dists, iters, evals) if want_iters else (ids, dists)

@@ -20,16 +20,17 @@ def _gpu(x):
 
 
 def _both(x, g, q, st, k_s, L, width, cap, metric=0):
-    gi, gd, git = knng.knng_graph_search(_gpu(x), _gpu(g), _gpu(q), _gpu(st), k_s, L, width, cap, metric,
-                                         want_iters=True)
-    oi, od, oit = oracle.graph_search(x, g, q, st, k_s, L, width, cap, metric)
-    return (gi.cpu().numpy(), gd.cpu().numpy(), git.cpu().numpy()), (oi, od, oit)
+    gi, gd, git, gev = knng.knng_graph_search(_gpu(x), _gpu(g), _gpu(q), _gpu(st), k_s, L, width, cap, metric,
+                                              want_iters=True)
+    oi, od, oit, oev = oracle.graph_search(x, g, q, st, k_s, L, width, cap, metric, want_evals=True)
+    return (gi.cpu().numpy(), gd.cpu().numpy(), git.cpu().numpy(), gev.cpu().numpy()), (oi, od, oit, oev)
 
 
 def _assert_same(a, b):
     assert np.array_equal(a[0], b[0])
     assert np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
     assert np.array_equal(a[2], b[2])
+    assert np.array_equal(a[3], b[3])                          # the same distances were evaluated
 
 
 def _data(n, d, nq, metric, seed):

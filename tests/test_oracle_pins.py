@@ -577,8 +577,10 @@ def test_graph_search_hand_fixture_on_a_line(golden_dir):
         width = int(t[1])
         cap = int(t[t.index("cap") + 1]) if "cap" in t else 100
         want_ids = [int(v) for v in t[t.index("ids") + 1:]]
-        ids, dists, iters = oracle.graph_search(x, g, q, st, 3, 3, width, cap)
+        ids, dists, iters, evals = oracle.graph_search(x, g, q, st, 3, 3, width, cap, want_evals=True)
         assert ids[0].tolist() == want_ids
+        if "evaluations" in t:
+            assert evals[0] == int(t[t.index("evaluations") + 1])
         if "iterations" in t:
             assert iters[0] == int(t[t.index("iterations") + 1])
         # one term each: (p - q)^2 in double from the fp32 inputs, rounded once
