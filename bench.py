@@ -20,6 +20,13 @@ CPU oracle on a few rows); the run fails if recall@k < 0.95.
 the graph that build produces instead (one step = one call; the graph is built
 once, outside the timed region); the oracle runs on the same graph beside it
 and the run fails unless the two results are identical.
+
+`--op search` times the graph search (`knng_graph_search`): the workload's second
+half searches the search graph of its first half (one level of the paper's
+cross-partition refinement on one GPU; graph built and optimised once, outside
+the timed region; one step = all queries); the oracle runs on a sample of the
+queries beside it (identical results required), recall against exact neighbours
+is measured on a sample outside the timed region.
 """
 import argparse
 import json
@@ -49,11 +56,17 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=1, help="workload index (0..4)")
+    ap.add_argument("--config", type=int, default=-1,
+                    help="workload index (0..5); default 1, for --op search 5 (a set whose graph a walk can cross)")
     ap.add_argument("--n", type=int, default=0, help="override the number of points")
     ap.add_argument("--elem", choices=("f32", "u8"), default="f32",
                     help="point storage; u8 (knng_build_knn_graph_u8) needs a workload with 8-bit values: config 1")
-    ap.add_argument("--op", choices=("build", "optimize"), default="build")
+    ap.add_argument("--op", choices=("build", "optimize", "search"), default="build")
+    ap.add_argument("--itopk", type=int, default=64, help="--op search: list length")
+    ap.add_argument("--width", type=int, default=1, help="--op search: entries expanded per iteration")
+    ap.add_argument("--n-starts", type=int, default=32, help="--op search: start points per query")
+    ap.add_argument("--max-search-iters", type=int, default=100)
+    ap.add_argument("--oracle-queries", type=int, default=20000, help="--op search: queries the oracle repeats")
     ap.add_argument("--d-out", type=int, default=0, help="--op optimize: degree of the search graph (default k)")
     ap.add_argument("--k-build", type=int, default=0)
     ap.add_argument("--rho", type=float, default=0.0)
@@ -125,14 +138,105 @@ def bench_optimize(a):
         sys.exit(1)
 
 
+def bench_search(a):
+    """knng_graph_search: the second half of the workload searches the first half's search graph."""
+    import numpy as np
+    import torch
+    from paper_2605_27691_amd import knng, workloads
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    x, w = workloads.make(a.config, n=(a.n or None), device=dev)
+    n, d, k = w.n // 2, w.d, w.k
+    pa, qb = x[:n].contiguous(), x[n:2 * n].contiguous()
+    del x
+    nq = qb.shape[0]
+    d_out = a.d_out or k
+    g_ids, _, st = knng.knng_build_knn_graph(pa, k, w.metric, seed=0, k_build=a.k_build, rho=a.rho, delta=a.delta)
+    gs = knng.knng_optimize_graph(g_ids, d_out)
+    del g_ids
+    gen = torch.Generator(device="cpu").manual_seed(12345)
+    starts = torch.randint(0, n, (nq, a.n_starts), generator=gen, dtype=torch.int32).to(dev)
+    args = (pa, gs, qb, starts, k, a.itopk, a.width, a.max_search_iters, w.metric)
+    for _ in range(a.warmup):
+        knng.knng_graph_search(*args)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(a.steps):
+        ids, dists = knng.knng_graph_search(*args)
+    e1.record()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / max(a.steps, 1)
+    dev_ms = e0.elapsed_time(e1) / max(a.steps, 1)
+    ids, dists, iters, evals = knng.knng_graph_search(*args, want_iters=True)
+    tot_iters, tot_evals = int(iters.sum()), int(evals.sum())
+    # algorithmic bytes: every evaluated candidate's vector, every expanded row, per query its
+    # vector, start ids and result
+    alg_bytes = tot_evals * 4 * d + tot_iters * a.width * 4 * d_out + nq * (4 * d + 4 * a.n_starts + 8 * k)
+    achieved = alg_bytes / (dev_ms * 1e-3) / 1e9
+    # recall on a sample: exact neighbours among the first half by fp32 products in chunks (outside
+    # the timed region; quality only, nothing is compared bit for bit with it)
+    ns = min(2000, nq)
+    sel = torch.from_numpy(workloads.sample_rows(nq, ns)).to(dev).long()
+    qn = qb[sel]
+    if w.metric == 0:
+        sc = (pa * pa).sum(1)[None, :] - 2.0 * (qn @ pa.T)
+    else:
+        sc = -(qn @ pa.T)
+    ex = sc.topk(k, dim=1, largest=False).indices
+    got = ids[sel].long()
+    recall = float((got[:, :, None] == ex[:, None, :]).any(2).float().mean())
+    del sc
+    import oracle
+    no = min(a.oracle_queries, nq)
+    pa_h, gs_h = pa.cpu().numpy(), gs.cpu().numpy()
+    t1 = time.perf_counter()
+    o_i, o_d, o_it, o_ev = oracle.graph_search(pa_h, gs_h, qb[:no].cpu().numpy(), starts[:no].cpu().numpy(), k, a.itopk,
+                                                a.width, a.max_search_iters, w.metric, want_evals=True)
+    cpu_sec = time.perf_counter() - t1
+    same = bool(np.array_equal(o_i, ids[:no].cpu().numpy()) and
+                np.array_equal(o_d.view(np.uint32), dists[:no].cpu().numpy().view(np.uint32)) and
+                np.array_equal(o_it, iters[:no].cpu().numpy()) and np.array_equal(o_ev, evals[:no].cpu().numpy()))
+    res = {
+        "metric": "graph search queries/sec (1 MI355X)",
+        "value": nq / sec, "unit": "queries/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": w.name + "_second_half_searches_first_half", "n": n, "nq": nq, "d": d, "k_s": k,
+                   "graph_degree": d_out, "itopk": a.itopk, "width": a.width, "n_starts": a.n_starts,
+                   "max_iters": a.max_search_iters, "metric": ["l2sq", "ip_unit"][w.metric]},
+        "recall_at_k": recall, "recall_rows": ns,
+        "mean_iterations": tot_iters / nq, "mean_distance_evaluations": tot_evals / nq,
+        "oracle_check": {"identical_to_oracle": same, "queries": no},
+        "roofline": {"kernel": "k_graph_search", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     # profiles/k_graph_search_manifold16_500k_d128.txt (FETCH_SIZE + WRITE_SIZE), default arguments
+                     "traffic": 417.3e9 if (w.name, a.itopk, a.width, a.n_starts, d_out) ==
+                                ("manifold16_1m_d128_l2", 64, 1, 32, 32) and not a.n else None,
+                     "device_ms_per_call": dev_ms, "alg_bytes_per_call": alg_bytes},
+        "cpu_baseline": {"value": no / cpu_sec, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
+                         "sample": f"oracle_graph_search on the first {no} queries, {cpu_sec:.1f} s"},
+    }
+    print(json.dumps(res))
+    if not same:
+        print("bench.py: the search results differ from the oracle's", file=sys.stderr)
+        sys.exit(1)
+
+
 def main():
     a = parse()
+    if a.config < 0:
+        a.config = 5 if a.op == "search" else 1
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (nothing here uses a second GPU)",
               file=sys.stderr)
         sys.exit(2)
     if a.op == "optimize":
         return bench_optimize(a)
+    if a.op == "search":
+        return bench_search(a)
     import numpy as np
     import torch
     from paper_2605_27691_amd import knng, workloads

@@ -13,8 +13,8 @@
 // expanded flag in bit 0).  A batch (the start ids, or one graph row: at most 64 ids) has a lane
 // per id: the lane drops ids that are invalid, repeat an earlier lane's or are in the list,
 // evaluates the distance with the fp64 recipe (the query sits in LDS, the candidate's vector
-// streams through the lane), drops what cannot enter a full list, and the survivors are merged
-// by counting ranks.  Offering a batch at once gives the same list as offering its ids one by
+// streams through the lane, and stops early where a partial sum already rules the candidate
+// out), drops what cannot enter a full list, and the survivors are merged by counting ranks.  Offering a batch at once gives the same list as offering its ids one by
 // one: the L smallest of a union do not depend on the order of insertion.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -64,12 +64,17 @@ k_graph_search(const float* __restrict__ pts, int64_t n, int d, const int32_t* _
         if (okm == 0ull) return;
         evals += __popcll(okm);
         float dist = 0.0f;
+        // Squared L2 with a full list: the partial sums only grow, in fp64 and after rounding to
+        // fp32 alike, so a lane whose partial sum already rounds above the list's last distance
+        // stops reading its vector -- the candidate would be left out with the full sum too.
+        const float worst_d = len == L ? key_dist(bcast64(lk, L - 1)) : __uint_as_float(0x7f800000u);
         if (ok) {
             const float* __restrict__ b = pts + (int64_t)id * d;
             double acc = 0.0;
             if (VEC) {
                 int t = 0;
                 for (; t + 16 <= d; t += 16) {
+                    if (METRIC == 0 && (float)acc > worst_d) { ok = false; break; }
                     float4 bv[4], av[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u) bv[u] = *reinterpret_cast<const float4*>(b + t + 4 * u);
@@ -83,7 +88,7 @@ k_graph_search(const float* __restrict__ pts, int64_t n, int d, const int32_t* _
                         acc = exact_step<METRIC>(acc, av[u].w, bv[u].w);
                     }
                 }
-                for (; t < d; t += 4) {
+                for (; ok && t < d; t += 4) {
                     const float4 bv = *reinterpret_cast<const float4*>(b + t);
                     const float4 av = *reinterpret_cast<const float4*>(qs + t);
                     acc = exact_step<METRIC>(acc, av.x, bv.x);

@@ -20,6 +20,11 @@ Recipes (index = position in the benchmark's config list):
    s_j = (j+1)^-1.5; c = s * U[-10,10], x = c + s * N(0,1).  k=32, squared L2.
 4  20,000,000 x 128 (one GPU's share of a ~1B-point set): 4,096 centres
    ~ U[-10,10]^128, x = c + N(0,1).  k=32, squared L2.
+5  1,000,000 x 128, one connected cloud of low intrinsic dimension (what real
+   descriptor sets look like to a graph search; the isolated clusters of the
+   recipes above are islands of their k-NN graphs, which no walk can leave):
+   z ~ N(0, I_16), x = z A + 0.05 N(0,1) with A (16 x 128) ~ N(0, 1/16).
+   k=32, squared L2.  Used by the graph-search benchmark and tests.
 
 `n` may be overridden to get a smaller set with the same per-cluster
 population (the number of centres is scaled with n, at least 1).
@@ -53,7 +58,9 @@ CONFIGS = (
     Workload("unitgmm4096_1m_d96_ip", 1_000_000, 96, 32, IP_UNIT, 4096, 2),
     Workload("powergmm256_1m_d960_l2", 1_000_000, 960, 32, L2SQ, 256, 3),
     Workload("gmm4096_20m_d128_l2", 20_000_000, 128, 32, L2SQ, 4096, 4),
+    Workload("manifold16_1m_d128_l2", 1_000_000, 128, 32, L2SQ, 1, 5),
 )
+LATENT_DIM = 16
 
 
 def scaled(cfg: Workload, n: int) -> Workload:
@@ -82,6 +89,10 @@ def _numpy_points(idx: int, w: Workload) -> np.ndarray:
         s = ((np.arange(d, dtype=np.float64) + 1.0) ** -1.5).astype(np.float32)
         c = s * rng.uniform(-10.0, 10.0, size=(nc, d)).astype(np.float32)
         x = c[assign] + s * rng.standard_normal((n, d), dtype=np.float32)
+    elif idx == 5:
+        a = (rng.standard_normal((LATENT_DIM, d), dtype=np.float32) * np.float32(0.25))
+        x = rng.standard_normal((n, LATENT_DIM), dtype=np.float32) @ a
+        x += np.float32(0.05) * rng.standard_normal((n, d), dtype=np.float32)
     else:
         raise ValueError(idx)
     return np.ascontiguousarray(x, dtype=np.float32)
@@ -113,6 +124,10 @@ def _torch_points(idx: int, w: Workload, device):
         c = s * (torch.rand(nc, d, generator=g, **f32) * 20.0 - 10.0)
         x = c[assign]
         x += s * torch.randn(n, d, generator=g, **f32)
+    elif idx == 5:
+        a = torch.randn(LATENT_DIM, d, generator=g, **f32) * 0.25
+        x = torch.randn(n, LATENT_DIM, generator=g, **f32) @ a
+        x += 0.05 * torch.randn(n, d, generator=g, **f32)
     else:
         raise ValueError(idx)
     return x.contiguous()
