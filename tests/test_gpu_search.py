@@ -105,3 +105,38 @@ def test_search_argument_errors():
         knng.knng_graph_search(_gpu(x), _gpu(g), _gpu(q[:, :7].copy()), _gpu(st), 4, 8)
     ids, dists = knng.knng_graph_search(_gpu(x), _gpu(g), _gpu(q[:0]), _gpu(st[:0]), 4, 8)
     assert ids.shape == (0, 4)
+
+
+def test_one_refinement_level_on_one_gpu_build_optimise_search_merge():
+    # Two partitions A and B of one point set, the way the paper's scheme treats two ranks
+    # (Sec. 4.3, 4.4), with the exchange left out: each builds its own graph, B's points search
+    # A's search graph and A's search B's, each updates its rows with what it found.  The
+    # result is compared with the exact graph of the whole set.
+    x, w = workloads.make(5, n=24_000)
+    k = 16
+    half = len(x) // 2
+    parts = [x[:half], x[half:]]
+    dev = [_gpu(p) for p in parts]
+    local, search_graph = [], []
+    for p in dev:
+        ids, dists, _ = knng.knng_build_knn_graph(p, k, w.metric, k_build=32, seed=6)
+        local.append((ids, dists))
+        search_graph.append(knng.knng_optimize_graph(ids, k))
+    rng = np.random.default_rng(8)
+    merged = []
+    for me, other in ((0, 1), (1, 0)):
+        st = _gpu(rng.integers(0, half, (half, 16)).astype(np.int32))
+        r_ids, r_dists = knng.knng_graph_search(dev[other], search_graph[other], dev[me], st, k, 48, 1, 100, w.metric)
+        # global ids: partition 0 keeps its ids, partition 1 is shifted by `half`
+        own = local[me][0] + me * half
+        found = torch.where(r_ids >= 0, r_ids + other * half, r_ids)
+        merged.append(knng.knng_merge_graphs(own, local[me][1], found, r_dists, k))
+    g_ids = torch.cat([m[0] for m in merged]).cpu().numpy()
+    g_dists = torch.cat([m[1] for m in merged]).cpu().numpy()
+    viol = oracle.check_graph(x, g_ids, g_dists, w.metric, rel_tol=0.0)
+    assert sum(viol.values()) == 0, viol
+    ex = knng.knng_brute_knn(_gpu(x), k, w.metric)
+    rec = knng.knng_graph_recall(_gpu(g_ids), _gpu(g_dists), ex[0], ex[1], k, 0)
+    before = knng.knng_graph_recall(torch.cat([local[0][0], local[1][0] + half]), torch.cat([local[0][1], local[1][1]]),
+                                    ex[0], ex[1], k, 0)
+    assert before < 0.7 and rec >= 0.95, (before, rec)
