@@ -709,7 +709,9 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             const SlabMap sm = slab_map(d, k0, DS, tid);
             // ---- A: registers -> LDS
             if (first) {
-                if (tid == NCOLS - 1 && nTot == NCOLS) thr_v[0] = 0.0f;     // no thread holds the pivot
+                // all 256 threads hold members: no thread is left for the pivot (with 128 member
+                // slots thread 128 holds it, and must be the only writer of its threshold)
+                if (NCOLS == 256 && tid == NCOLS - 1 && nTot == NCOLS) thr_v[0] = 0.0f;
                 if (tid == nTot) {
                     thr_v[0] = thr_r;
                     reinterpret_cast<uint4*>(sg)[2 * NCOLS] = sg_r0;

@@ -253,7 +253,8 @@ def test_build_candidate_capacity_and_heavy_contention():
 def test_build_is_reproducible_run_to_run():
     # every cross-point write of the build is an atomic min (candidate slots, reverse buckets):
     # the result does not depend on the order the wavefronts ran in
-    for idx, n, kb, rho in ((0, 20_000, 32, 0.5), (2, 9_000, 24, 1.0)):
+    # (the larger sets reach every member count of the 128- and 256-member kernels, their maxima included)
+    for idx, n, kb, rho in ((0, 20_000, 32, 0.5), (2, 9_000, 24, 1.0), (4, 200_000, 64, 0.5), (4, 100_000, 64, 1.0)):
         x, w = workloads.make(idx, n=n)
         xg = _gpu(x)
         k = min(w.k, kb)
