@@ -120,6 +120,25 @@ def test_distance_against_exact_rational_arithmetic(metric):
     assert same >= 0.9 * trials
 
 
+def test_float16_points_are_taken_at_their_values():
+    # half-precision inputs: short mantissas, so a sum of a few squared differences is exact in
+    # double and the result is the correctly rounded exact value -- compared with rational
+    # arithmetic on the half values themselves; and a graph of such points is the graph of the
+    # same values stored as fp32
+    rng = np.random.default_rng(14)
+    for _ in range(100):
+        d = int(rng.integers(1, 40))
+        a = rng.standard_normal(d).astype(np.float16)
+        b = (a + rng.standard_normal(d).astype(np.float16)).astype(np.float16)
+        exact = sum((Fraction(float(x)) - Fraction(float(y))) ** 2 for x, y in zip(a, b))
+        assert oracle.distance(a, b, oracle.L2SQ) == np.float32(float(exact)) or \
+            abs(float(oracle.distance(a, b, oracle.L2SQ)) - float(exact)) <= np.spacing(np.float32(float(exact))) / 2
+    x16 = rng.standard_normal((200, 12)).astype(np.float16)
+    i16, d16 = oracle.brute_knn(x16, 6, oracle.L2SQ)
+    i32, d32 = oracle.brute_knn(x16.astype(np.float32), 6, oracle.L2SQ)
+    assert np.array_equal(i16, i32) and np.array_equal(d16, d32)
+
+
 # --------------------------------------------------------------------------- exact kNN
 def _enumerate_knn(x, k, metric):
     """Exhaustive enumeration + full sort, float64 numpy formulas written independently."""
