@@ -130,6 +130,22 @@ int knng_build_knn_graph(const float *points_dev, int64_t n, int32_t d, int32_t 
 int knng_build_knn_graph_u8(const uint8_t *points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,
                             const knng_params_t *params, int32_t *ids_out_dev, float *dists_out_dev);
 
+/*
+ * The same build for points stored as IEEE half precision (compact element types
+ * halve the bytes the joins gather; Sec. 5.2 lists the element types of the paper's
+ * sets).  points_dev [n][d] fp16 (device, read-only, 4-byte aligned; 16-byte pieces
+ * when d % 8 == 0 and the pointer is 16-byte aligned, else 4-byte words).  The values
+ * are taken as they are: the result obeys the definition of knng_build_knn_graph on
+ * the same values converted to fp32 (every written distance is the fp64 recipe on
+ * them).  During the search the joins centre rows in fp16, so candidates are compared
+ * at a relative precision of about 1e-3; this affects which neighbours are found, not
+ * what is written about them.  Workspace: knng_build_workspace_bytes (the same).
+ * Additional KNNG_EINVAL cases: metric other than KNNG_METRIC_L2SQ, d % 2 != 0,
+ * pointer not 4-byte aligned.
+ */
+int knng_build_knn_graph_f16(const uint16_t *points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,
+                             const knng_params_t *params, int32_t *ids_out_dev, float *dists_out_dev);
+
 /* Device scratch needed by knng_brute_knn (0 on bad arguments). */
 uint64_t knng_brute_workspace_bytes(int64_t n, int32_t d, int32_t k, int64_t nq);
 

@@ -94,6 +94,32 @@ __device__ __forceinline__ float dist_group8_u8(const unsigned char* __restrict_
     return (float)acc;
 }
 
+// fp16 rows (squared L2), search-time precision: fp32 accumulation of the squared differences
+// of the converted halves; d % 2 == 0, rows 4-byte aligned
+__device__ __forceinline__ float dist_group8_f16(const uint32_t* __restrict__ a, const uint32_t* __restrict__ b,
+                                                 int d, int sub)
+{
+    float acc = 0.0f;
+    auto word = [&](uint32_t x, uint32_t y) {
+        const float e0 = h_lo(x) - h_lo(y), e1 = h_hi(x) - h_hi(y);
+        acc = fmaf(e0, e0, acc); acc = fmaf(e1, e1, acc);
+    };
+    if ((d & 7) == 0) {
+        const uint4* a4 = reinterpret_cast<const uint4*>(a);
+        const uint4* b4 = reinterpret_cast<const uint4*>(b);
+        for (int t = sub; t < (d >> 3); t += 8) {
+            const uint4 x = a4[t], y = b4[t];
+            word(x.x, y.x); word(x.y, y.y); word(x.z, y.z); word(x.w, y.w);
+        }
+    } else {
+        for (int t = sub; t < (d >> 1); t += 8) word(a[t], b[t]);
+    }
+    acc += __shfl_xor(acc, 1);
+    acc += __shfl_xor(acc, 2);
+    acc += __shfl_xor(acc, 4);
+    return nonneg(acc);
+}
+
 // ------------------------------------------------------------------------------------------
 // Row signature: a 256-bit Bloom-style set of the ids in a point's row (bit hash(id) & 255).
 // The join uses it to skip partners a member most likely already holds: such offers would be
@@ -123,7 +149,7 @@ constexpr uint32_t EMPTY_REV = 0xffffffffu;            // an empty reverse bucke
 // with bad entries redrawn), their distances, row sorted by (distance, id), all flagged new.
 // Also puts the point's candidate slots, counters and threshold into their start state.
 // ------------------------------------------------------------------------------------------
-// ELEM 1: pts points at uint8 rows of d bytes.
+// ELEM 1: pts points at uint8 rows of d bytes; ELEM 2: at fp16 rows of d halves.
 template <int METRIC, int ELEM>
 __global__ void __launch_bounds__(256)
 k_init(const float* __restrict__ pts, int64_t n, int d, int K, int C, u64 seed,
@@ -177,6 +203,9 @@ k_init(const float* __restrict__ pts, int64_t n, int d, int K, int C, u64 seed,
         if constexpr (ELEM == 1) {
             const unsigned char* p8 = reinterpret_cast<const unsigned char*>(pts);
             val = dist_group8_u8(p8 + v * (int64_t)d, p8 + (int64_t)uid * d, d, sub);
+        } else if constexpr (ELEM == 2) {
+            const uint32_t* p16 = reinterpret_cast<const uint32_t*>(pts);       // d / 2 words per row
+            val = dist_group8_f16(p16 + v * (int64_t)(d >> 1), p16 + (int64_t)uid * (d >> 1), d, sub);
         } else {
             val = dist_group8<METRIC>(xv, pts + (int64_t)uid * d, d, sub);
         }
@@ -491,7 +520,7 @@ template <int S16, int DS_, int ELEM = 0> struct JoinCfg {
     static constexpr int XBYTES = NCOLS * LD * 4 > MROWS * LDD * 4 ? NCOLS * LD * 4 : MROWS * LDD * 4;
     // ELEM 1 (uint8 rows): + the pivot's row and a row of zeros [2][LD], pivot distances [NCOLS]
     static constexpr int LDS_BYTES = XBYTES + NCOLS * (8 + 8 + 8 + 4 * SIG_WORDS) + 16 + 4 * SIG_WORDS +
-                                     (ELEM ? 2 * LD * 4 + NCOLS * 4 : 0);
+                                     (ELEM == 1 ? 2 * LD * 4 + NCOLS * 4 : 0);
 };
 
 // 16-byte piece [t, t+4) of a row, zero beyond d.  VEC: d % 4 == 0 and rows 16-byte aligned, so
@@ -579,7 +608,7 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
        const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand,
        u64* __restrict__ offers_ctr)
 {
-    static_assert(ELEM == 0 || METRIC == 0, "uint8 rows: squared L2 only");
+    static_assert(ELEM == 0 || METRIC == 0, "uint8 and fp16 rows: squared L2 only");
     using Cfg = JoinCfg<S16, DS_, ELEM>;
     using accv = typename std::conditional<ELEM == 1, intx4, floatx4>::type;
     uint32_t n_offers = 0;                                     // this thread's, summed per wavefront at exit
@@ -732,6 +761,7 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                     if (i * sm.RP < nTot) {                     // uniform: the group was loaded
                         float4 x = buf[i];
                         if (ELEM == 1) x = enc_u8(x, k0 + 4 * sm.c4);
+                        else if (ELEM == 2) x = sub_h2x4(x, pv);
                         else { x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w; }
                         if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
                         if (sm.rsub + i * sm.RP < nTot) *reinterpret_cast<float4*>(xdst + i * sm.RP * LD) = x;
@@ -770,6 +800,10 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                             const intx4 a = *reinterpret_cast<const intx4*>(xa + kk);
                             const intx4 b = *reinterpret_cast<const intx4*>(xb + kk);
                             acc[q] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[q], 0, 0, 0);
+                        } else if constexpr (ELEM == 2) {
+                            const half8v a = *reinterpret_cast<const half8v*>(xa + kk);
+                            const half8v b = *reinterpret_cast<const half8v*>(xb + kk);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[q], 0, 0, 0);
                         } else {
                             const float4 a = *reinterpret_cast<const float4*>(xa + kk);
                             const float4 b = *reinterpret_cast<const float4*>(xb + kk);
@@ -963,6 +997,37 @@ k_finalize(const float* __restrict__ pts, int64_t n, int d, int K, int Kp, int k
                 acc += sqdiff4_u8(*reinterpret_cast<const uint32_t*>(a + t), *reinterpret_cast<const uint32_t*>(b + t));
         }
         dist = (float)acc;
+    } else if constexpr (ELEM == 2) {
+        // fp16 rows of d halves: the fp64 recipe on the converted values, in index order
+        const uint32_t* __restrict__ a = reinterpret_cast<const uint32_t*>(pts) + vv * (int64_t)(d >> 1);
+        const uint32_t* __restrict__ b = reinterpret_cast<const uint32_t*>(pts) + (int64_t)id * (d >> 1);
+        double acc = 0.0;
+        auto word = [&](uint32_t x, uint32_t y) {
+            acc = exact_step<0>(acc, h_lo(x), h_lo(y));
+            acc = exact_step<0>(acc, h_hi(x), h_hi(y));
+        };
+        if (VEC) {                                   // d % 8 == 0
+            int t = 0;
+            for (; t + 16 <= (d >> 1); t += 16) {
+                uint4 av[4], bv[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    av[q] = *reinterpret_cast<const uint4*>(a + t + 4 * q);
+                    bv[q] = *reinterpret_cast<const uint4*>(b + t + 4 * q);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    word(av[q].x, bv[q].x); word(av[q].y, bv[q].y); word(av[q].z, bv[q].z); word(av[q].w, bv[q].w);
+                }
+            }
+            for (; t < (d >> 1); t += 4) {
+                const uint4 av = *reinterpret_cast<const uint4*>(a + t), bv = *reinterpret_cast<const uint4*>(b + t);
+                word(av.x, bv.x); word(av.y, bv.y); word(av.z, bv.z); word(av.w, bv.w);
+            }
+        } else {                                     // d % 2 == 0
+            for (int t = 0; t < (d >> 1); ++t) word(a[t], b[t]);
+        }
+        dist = exact_finish<0>(acc);
     } else {
     const float* __restrict__ a = pts + vv * d;
     const float* __restrict__ b = pts + (int64_t)id * d;
@@ -1105,13 +1170,14 @@ static hipError_t launch_join_w(hipStream_t st, const JoinArgs& a)
     return hipGetLastError();
 }
 
-// uint8 rows, squared L2; a.d counts 32-bit words
-static hipError_t launch_join_u8(hipStream_t st, bool vec, int S16, const JoinArgs& a)
+// uint8 (ELEM 1) or fp16 (ELEM 2) rows, squared L2; a.d counts 32-bit words
+template <int ELEM>
+static hipError_t launch_join_compact(hipStream_t st, bool vec, int S16, const JoinArgs& a)
 {
-    if (S16 == 1) return vec ? launch_join_w<0, 1, true, 1>(st, a) : launch_join_w<0, 1, false, 1>(st, a);
-    if (S16 == 2) return vec ? launch_join_w<0, 2, true, 1>(st, a) : launch_join_w<0, 2, false, 1>(st, a);
-    if (S16 == 4) return vec ? launch_join_k<0, 4, 64, true, 1>(st, a) : launch_join_k<0, 4, 64, false, 1>(st, a);
-    return vec ? launch_join_k<0, 8, 32, true, 1>(st, a) : launch_join_k<0, 8, 32, false, 1>(st, a);
+    if (S16 == 1) return vec ? launch_join_w<0, 1, true, ELEM>(st, a) : launch_join_w<0, 1, false, ELEM>(st, a);
+    if (S16 == 2) return vec ? launch_join_w<0, 2, true, ELEM>(st, a) : launch_join_w<0, 2, false, ELEM>(st, a);
+    if (S16 == 4) return vec ? launch_join_k<0, 4, 64, true, ELEM>(st, a) : launch_join_k<0, 4, 64, false, ELEM>(st, a);
+    return vec ? launch_join_k<0, 8, 32, true, ELEM>(st, a) : launch_join_k<0, 8, 32, false, ELEM>(st, a);
 }
 
 template <int METRIC>
@@ -1147,7 +1213,8 @@ extern "C" __attribute__((visibility("default"))) uint64_t knng_build_workspace_
         if (e_ != hipSuccess) { rc = set_hip_error(e_, #expr); goto done; } \
     } while (0)
 
-// elem 0: fp32 rows; elem 1: uint8 rows (squared L2, d % 4 == 0, d <= 65536)
+// elem 0: fp32 rows; elem 1: uint8 rows (squared L2, d % 4 == 0, d <= 65536); elem 2: fp16 rows
+// (squared L2, d % 2 == 0)
 static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, int32_t k, int32_t metric,
                       const knng_params_t* params, int32_t* ids_out_dev, float* dists_out_dev)
 {
@@ -1160,6 +1227,10 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
     if (elem == 1) {
         if (metric != KNNG_METRIC_L2SQ || (d & 3) || d > 65536 ||
             (reinterpret_cast<uintptr_t>(points_void) & 3u))
+            return KNNG_EINVAL;
+    }
+    if (elem == 2) {
+        if (metric != KNNG_METRIC_L2SQ || (d & 1) || (reinterpret_cast<uintptr_t>(points_void) & 3u))
             return KNNG_EINVAL;
     }
     if (!params->workspace_dev || params->workspace_bytes < bp.total ||
@@ -1180,7 +1251,7 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
     uint32_t* sig = reinterpret_cast<uint32_t*>(ws + bp.off_sig);
     u64* ctr = reinterpret_cast<u64*>(ws + bp.off_ctr);      // [0] updates [1] rows gathered [2] active [3] pairs [4] offers
     knng_stats_t* stats = params->stats_host;
-    const bool vec = (d % (elem == 1 ? 16 : 4) == 0) && ((reinterpret_cast<uintptr_t>(points_dev) & 15u) == 0);
+    const bool vec = (d % (elem == 1 ? 16 : elem == 2 ? 8 : 4) == 0) && ((reinterpret_cast<uintptr_t>(points_dev) & 15u) == 0);
     const unsigned row_blocks = (unsigned)((n + 3) / 4);
     unsigned upd_blocks = 0;                          // persistent k_update grid, set once num_cu is known
     const double stop_below = (double)bp.delta * (double)bp.K * (double)n;
@@ -1210,7 +1281,10 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
         HIPCHK(hipEventRecord(ev[0], st));
     }
     HIPCHK(hipMemsetAsync(ctr, 0, 256, st));
-    if (elem == 1)
+    if (elem == 2)
+        hipLaunchKernelGGL((k_init<0, 2>), dim3(row_blocks), dim3(256), 0, st, points_dev, n, d, bp.K, bp.C,
+                           params->seed, params->init_ids_dev, G, cand, cnt, worst, rev, bp.B);
+    else if (elem == 1)
         hipLaunchKernelGGL((k_init<0, 1>), dim3(row_blocks), dim3(256), 0, st, points_dev, n, d, bp.K, bp.C,
                            params->seed, params->init_ids_dev, G, cand, cnt, worst, rev, bp.B);
     else if (metric == 0)
@@ -1252,9 +1326,10 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
         HIPCHK(hipGetLastError());
         if (rec) HIPCHK(hipEventRecord(ev[3 + 4 * it], st));
         {
-            JoinArgs ja{points_dev, elem == 1 ? d / 4 : d, bp.C, bp.s, (uint32_t)it, newl, oldl, plan, active, ctr + 2,
+            JoinArgs ja{points_dev, elem == 1 ? d / 4 : elem == 2 ? d / 2 : d, bp.C, bp.s, (uint32_t)it, newl, oldl, plan, active, ctr + 2,
                         worst, sig, cand, ctr + 4, num_cu, n};
-            if (elem == 1) HIPCHK(launch_join_u8(st, vec, bp.S16, ja));
+            if (elem == 1) HIPCHK(launch_join_compact<1>(st, vec, bp.S16, ja));
+            else if (elem == 2) HIPCHK(launch_join_compact<2>(st, vec, bp.S16, ja));
             else if (metric == 0) HIPCHK(launch_join<0>(st, vec, bp.S16, ja));
             else HIPCHK(launch_join<1>(st, vec, bp.S16, ja));
         }
@@ -1269,6 +1344,7 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
 #define KNNG_FIN(M, V, E) hipLaunchKernelGGL((k_finalize<M, V, E>), grid, block, 0, st, points_dev, n, d, bp.K, Kp, k, \
                                              G, ids_out_dev, dists_out_dev)
         if (elem == 1) { if (vec) KNNG_FIN(0, true, 1); else KNNG_FIN(0, false, 1); }
+        else if (elem == 2) { if (vec) KNNG_FIN(0, true, 2); else KNNG_FIN(0, false, 2); }
         else if (metric == 0) { if (vec) KNNG_FIN(0, true, 0); else KNNG_FIN(0, false, 0); }
         else { if (vec) KNNG_FIN(1, true, 0); else KNNG_FIN(1, false, 0); }
 #undef KNNG_FIN
@@ -1314,6 +1390,12 @@ extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph(const
                                     const knng_params_t* params, int32_t* ids_out_dev, float* dists_out_dev)
 {
     return build_impl(points_dev, 0, n, d, k, metric, params, ids_out_dev, dists_out_dev);
+}
+
+extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph_f16(const uint16_t* points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,
+                                        const knng_params_t* params, int32_t* ids_out_dev, float* dists_out_dev)
+{
+    return build_impl(points_dev, 2, n, d, k, metric, params, ids_out_dev, dists_out_dev);
 }
 
 extern "C" __attribute__((visibility("default"))) int knng_build_knn_graph_u8(const uint8_t* points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,

@@ -86,6 +86,24 @@ template <int METRIC> __device__ __forceinline__ float exact_finish(double acc)
     return (float)(r > 0.0 ? r : 0.0);
 }
 
+// fp16 rows: two halves per 32-bit word
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+// a - b on the two halves of each word (v_pk_add_f16)
+__device__ __forceinline__ uint32_t sub_h2(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, (half2v)(__builtin_bit_cast(half2v, a) - __builtin_bit_cast(half2v, b)));
+}
+__device__ __forceinline__ float4 sub_h2x4(float4 a, float4 b)
+{
+    return float4{__uint_as_float(sub_h2(__float_as_uint(a.x), __float_as_uint(b.x))),
+                  __uint_as_float(sub_h2(__float_as_uint(a.y), __float_as_uint(b.y))),
+                  __uint_as_float(sub_h2(__float_as_uint(a.z), __float_as_uint(b.z))),
+                  __uint_as_float(sub_h2(__float_as_uint(a.w), __float_as_uint(b.w)))};
+}
+__device__ __forceinline__ float h_lo(uint32_t w) { return (float)__builtin_bit_cast(half2v, w)[0]; }
+__device__ __forceinline__ float h_hi(uint32_t w) { return (float)__builtin_bit_cast(half2v, w)[1]; }
+
 // an accumulator element as the 32 bits stored in LDS (fp32 Gram tiles / integer Gram tiles)
 __device__ __forceinline__ uint32_t acc_bits(float x) { return __float_as_uint(x); }
 __device__ __forceinline__ uint32_t acc_bits(int x) { return (uint32_t)x; }

@@ -37,6 +37,13 @@
 // conversion to fp32.  The products with the pivot (for its reverse members) come from one more
 // accumulator tile: column c of that tile takes the pivot as B operand for member tile c and a
 // row of zeros for the others, column 4 the pivot against itself.
+//
+// ELEM = 2: fp16 rows (squared L2 only), d/2 words per row: a slab is 64 coordinates in the same
+// bytes.  The rows are centred on the pivot in fp16 (one v_pk_add_f16 per word) and stay fp16 in
+// LDS; the Gram pass is v_mfma_f32_16x16x32_f16 with fp32 accumulators, one instruction per
+// operand read, and everything after it is the fp32 kernel's.  The centring rounds to fp16, so
+// the distances the join compares carry a relative error of about 1e-3: search-time precision
+// only, what is written to the caller is recomputed exactly from the fp16 values.
 #pragma once
 
 namespace knng {
@@ -55,18 +62,19 @@ template <int S16, int ELEM = 0> struct WaveCfg {
     static constexpr int NTILES = (3 * S16 * S16 + 3 * S16) / 2;  // upper triangle rows<S16 + extra diagonals
     static_assert(NCOLS * LD >= MROWS * LDD, "the distance block lies over the slab rows");
     // ELEM 1: two more slab rows (the pivot, zeros) and the pivot distances dpv[NCOLS]
-    static constexpr int XBYTES = (NCOLS + (ELEM ? 2 : 0)) * LD * 4;
+    static constexpr int XBYTES = (NCOLS + (ELEM == 1 ? 2 : 0)) * LD * 4;
     // X/D | mid[2][NCOLS] | nrm[NCOLS] | sg[8][NCOLS+1] | dpv[NCOLS]
     static constexpr int WBYTES = ((XBYTES + NCOLS * (8 + 4) + (NCOLS + 1) * 4 * SIG_WORDS +
-                                    (ELEM ? NCOLS * 4 : 0)) + 255) & ~255;
+                                    (ELEM == 1 ? NCOLS * 4 : 0)) + 255) & ~255;
 };
 
 #ifndef KNNG_WAVE_OCC
 #define KNNG_WAVE_OCC 3
 #endif
-// Wavefronts per SIMD the register allocation aims at: three; two for uint8 rows with up to 64
-// members, whose extra accumulator tile does not fit beside the rest in 168 registers.
-template <int S16, int ELEM> struct WaveOcc { static constexpr int V = (ELEM == 1 && S16 == 2) ? 2 : KNNG_WAVE_OCC; };
+// Wavefronts per SIMD the register allocation aims at: three; two for uint8 and fp16 rows with
+// up to 64 members (the extra accumulator tile of the uint8 kernel does not fit beside the rest
+// in 168 registers, and the fp16 kernel spills 39 there).
+template <int S16, int ELEM> struct WaveOcc { static constexpr int V = (ELEM != 0 && S16 == 2) ? 2 : KNNG_WAVE_OCC; };
 
 template <int METRIC, int S16, bool VEC, int ELEM = 0>
 __global__ void __launch_bounds__(256)
@@ -77,8 +85,8 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand,
             u64* __restrict__ offers_ctr)
 {
-    // ELEM 1: pts points at uint8 rows of 4 d bytes, d counts 32-bit words
-    static_assert(ELEM == 0 || METRIC == 0, "uint8 rows: squared L2 only");
+    // ELEM 1 / 2: pts points at uint8 / fp16 rows of 4 d bytes, d counts 32-bit words
+    static_assert(ELEM == 0 || METRIC == 0, "uint8 and fp16 rows: squared L2 only");
     using Cfg = WaveCfg<S16, ELEM>;
     using accv = typename std::conditional<ELEM == 1, intx4, floatx4>::type;
     constexpr int NCOLS = Cfg::NCOLS, CT = Cfg::CT, DS = Cfg::DS, LD = Cfg::LD, LDD = Cfg::LDD,
@@ -235,6 +243,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 if (RPW * i < nTot) {                           // uniform
                     float4 x = buf[i];
                     if (ELEM == 1) x = enc_u8(x, k0);
+                    else if (ELEM == 2) x = sub_h2x4(x, pv);
                     else { x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w; }
                     if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
                     *reinterpret_cast<float4*>(xdst + RPW * i * LD) = x;
@@ -294,6 +303,26 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                             const intx4 b = *reinterpret_cast<const intx4*>(X + (r16 == ct ? PIV_ROW : ZERO_ROW) + 4 * kq + kk);
                             accp = __builtin_amdgcn_mfma_i32_16x16x64_i8(ct < CT ? x[ct < CT ? ct : 0] : xp, b, accp, 0, 0, 0);
                         }
+                    }
+                }
+            } else if constexpr (ELEM == 2) {
+                for (int kk = 0; kk < len16; kk += 16) {
+                    half8v x[CT];
+#pragma unroll
+                    for (int t = 0; t < CT; ++t)
+                        if (t < nct) x[t] = *reinterpret_cast<const half8v*>(X + (t * 16 + r16) * LD + 4 * kq + kk);
+                    int q = 0;
+#pragma unroll
+                    for (int rt = 0; rt < S16; ++rt) {
+#pragma unroll
+                        for (int ct = rt; ct < CT; ++ct, ++q) {
+                            if (ct < nct && (rt < nrt || rt == ct))
+                                acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x[rt], x[ct], acc[q], 0, 0, 0);
+                        }
+                    }
+#pragma unroll
+                    for (int ct = S16; ct < CT; ++ct, ++q) {
+                        if (ct < nct) acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x[ct], x[ct], acc[q], 0, 0, 0);
                     }
                 }
             } else {

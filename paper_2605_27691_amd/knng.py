@@ -47,7 +47,7 @@ class Params(ctypes.Structure):
                 ("stats_host", ctypes.POINTER(Stats))]
 
 
-EXPORTS = ("knng_build_workspace_bytes", "knng_build_knn_graph", "knng_build_knn_graph_u8",
+EXPORTS = ("knng_build_workspace_bytes", "knng_build_knn_graph", "knng_build_knn_graph_u8", "knng_build_knn_graph_f16",
            "knng_brute_workspace_bytes",
            "knng_brute_knn", "knng_graph_recall", "knng_merge_graphs", "knng_optimize_workspace_bytes",
            "knng_optimize_graph", "knng_graph_search", "knng_strerror", "knng_version")
@@ -72,6 +72,8 @@ def load():
     L.knng_build_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(Params)]
     L.knng_build_knn_graph.restype = ctypes.c_int
     L.knng_build_knn_graph.argtypes = [_P, i64, i32, i32, i32, ctypes.POINTER(Params), _P, _P]
+    L.knng_build_knn_graph_f16.restype = ctypes.c_int
+    L.knng_build_knn_graph_f16.argtypes = [_P, i64, i32, i32, i32, ctypes.POINTER(Params), _P, _P]
     L.knng_build_knn_graph_u8.restype = ctypes.c_int
     L.knng_build_knn_graph_u8.argtypes = [_P, i64, i32, i32, i32, ctypes.POINTER(Params), _P, _P]
     L.knng_brute_workspace_bytes.restype = u64
@@ -197,6 +199,14 @@ def knng_build_knn_graph_u8(points, k, metric=L2SQ, *, k_build=0, rho=0.0, delta
                             ids_out=None, dists_out=None):
     """The same for `points` stored as [n][d] uint8 (GPU): squared L2 only, d % 4 == 0."""
     return _build_graph("knng_build_knn_graph_u8", torch.uint8, points, k, metric, k_build, rho, delta,
+                        max_iters, cand_cap, seed, init_ids, workspace, want_stats, ids_out, dists_out)
+
+
+def knng_build_knn_graph_f16(points, k, metric=L2SQ, *, k_build=0, rho=0.0, delta=0.0, max_iters=0,
+                             cand_cap=0, seed=0, init_ids=None, workspace=None, want_stats=True,
+                             ids_out=None, dists_out=None):
+    """The same for `points` stored as [n][d] float16 (GPU): squared L2 only, d % 2 == 0."""
+    return _build_graph("knng_build_knn_graph_f16", torch.float16, points, k, metric, k_build, rho, delta,
                         max_iters, cand_cap, seed, init_ids, workspace, want_stats, ids_out, dists_out)
 
 

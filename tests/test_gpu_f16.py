@@ -1,0 +1,118 @@
+"""GPU parity of the fp16 build (knng_build_knn_graph_f16) against the CPU oracle.
+
+The oracle takes fp16 points at their values (they convert to fp32 without rounding), so the
+bars are those of the fp32 build: every written distance equal to the oracle's recomputation,
+row invariants, recall@k >= 0.95 against the exact graph of those values.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_27691_amd import knng, workloads
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _gpu(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+
+
+def _clustered_f16(n, d, seed, centres=16, scale=1.0):
+    rng = np.random.default_rng(seed)
+    c = rng.uniform(-10.0, 10.0, (centres, d))
+    x = (c[rng.integers(0, centres, n)] + rng.standard_normal((n, d))) * scale
+    return x.astype(np.float16)
+
+
+def _check(x16, k, ids, dists, min_recall=0.95):
+    xf = x16.astype(np.float32)
+    ids, dists = ids.cpu().numpy(), dists.cpu().numpy()
+    viol = oracle.check_graph(xf, ids, dists, 0, rel_tol=0.0)          # the fp64 recipe on the values
+    assert sum(viol.values()) == 0, viol
+    ex = oracle.brute_knn(xf, k, 0)
+    rec = oracle.graph_recall(ids, dists, ex[0], ex[1], k, 0)
+    rec1 = oracle.graph_recall(ids, dists, ex[0], ex[1], k, 1)
+    assert rec >= min_recall and rec1 >= rec, (rec, rec1)
+    return rec
+
+
+@pytest.mark.parametrize("n,d,k,kb,rho", [
+    (4000, 64, 16, 32, 0.5),       # one 128-byte slab per row, 16-byte pieces
+    (4000, 128, 32, 32, 0.5),      # two slabs
+    (2500, 960, 16, 32, 0.5),      # 15 slabs
+    (2000, 20, 10, 16, 1.0),       # d % 8 != 0: 4-byte words, predicated loads
+    (600, 2, 5, 8, 0.5),           # one word per row
+    (100, 16, 32, 32, 0.5),        # K close to n
+    (2, 2, 1, 1, 1.0),             # smallest
+    (3001, 128, 32, 64, 0.5),      # the workgroup kernel with 128 member slots
+    (2000, 64, 16, 64, 1.0),       # 256 member slots
+    (1500, 22, 10, 48, 0.8),       # the same kernel on 4-byte words
+])
+def test_f16_build_against_the_oracle(n, d, k, kb, rho):
+    x16 = _clustered_f16(n, d, seed=n + d)
+    ids, dists, st = knng.knng_build_knn_graph_f16(_gpu(x16), k, 0, k_build=kb, rho=rho, seed=5)
+    _check(x16, k, ids, dists)
+
+
+def test_f16_small_and_large_magnitudes():
+    # values near the bottom and the top of the fp16 range: subnormals convert exactly, squared
+    # differences of large values stay finite in the fp32 accumulators
+    for scale in (1e-4, 100.0):
+        x16 = _clustered_f16(3000, 32, seed=3, scale=scale)
+        ids, dists, _ = knng.knng_build_knn_graph_f16(_gpu(x16), 10, 0, k_build=20, seed=2)
+        _check(x16, 10, ids, dists)
+
+
+def test_f16_pointer_alignment_paths_and_errors():
+    x16 = _clustered_f16(3000, 32, seed=2)
+    flat = torch.zeros(3000 * 32 + 32, dtype=torch.float16, device=DEV)
+    ref = knng.knng_build_knn_graph_f16(_gpu(x16), 10, 0, k_build=16, seed=4)
+    for off in (2, 8):                      # halves: 4-byte aligned (words) and 16-byte aligned (pieces)
+        view = flat[off:off + 3000 * 32].view(3000, 32)
+        view.copy_(_gpu(x16))
+        got = knng.knng_build_knn_graph_f16(view, 10, 0, k_build=16, seed=4)
+        _check(x16, 10, got[0], got[1])
+        if off == 8:
+            assert torch.equal(got[0], ref[0]) and torch.equal(got[1], ref[1])
+    ids = torch.full((3000, 8), -7, dtype=torch.int32, device=DEV)
+    dists = torch.full((3000, 8), -7.0, dtype=torch.float32, device=DEV)
+    xg = _gpu(x16)
+    for pts, metric in ((flat[1:1 + 3000 * 32].view(3000, 32), 0),      # 2-byte aligned only
+                        (xg, 1),                                        # inner product: fp32 build only
+                        (xg[:, :31].contiguous(), 0)):                  # odd d
+        with pytest.raises(knng.KnngError):
+            knng.knng_build_knn_graph_f16(pts, 8, metric, ids_out=ids, dists_out=dists)
+    assert bool((ids == -7).all()) and bool((dists == -7.0).all())
+
+
+def test_f16_full_size_config3_gist_shape():
+    # config 3 (1,000,000 x 960) stored as fp16: the launch configuration of the benchmark's
+    # --elem f16 run; sampled rows against the oracle on the fp16 values
+    x, w = workloads.make(3, device=DEV)
+    x16 = x.to(torch.float16)
+    del x
+    xf = x16.float()
+    n, k = w.n, w.k
+    rows = workloads.sample_rows(n, 4000)
+    rows_d = torch.from_numpy(rows).to(DEV)
+    ex_i, ex_d = knng.knng_brute_knn(xf, k, 0, rows_d)
+    ids, dists, st = knng.knng_build_knn_graph_f16(x16, k, 0, seed=0)
+    sel = rows_d.long()
+    t_i, t_d = ids[sel].contiguous(), dists[sel].contiguous()
+    rec = knng.knng_graph_recall(t_i, t_d, ex_i, ex_d, k, 0)
+    assert rec >= 0.95, rec
+    assert st["converged"] and st["iterations"] < 100
+    sub = np.linspace(0, len(rows) - 1, 16).astype(np.int64)
+    xh = xf.cpu().numpy()
+    o_i, o_d = oracle.brute_knn(xh, k, 0, query_rows=rows[sub])
+    assert np.array_equal(o_i, ex_i[sub].cpu().numpy()) and np.array_equal(o_d, ex_d[sub].cpu().numpy())
+    viol = oracle.check_graph(xh, t_i[sub].cpu().numpy(), t_d[sub].cpu().numpy(), 0, rel_tol=0.0, rows=rows[sub])
+    assert sum(viol.values()) == 0, viol
+    assert int(ids.min()) >= 0 and int(ids.max()) < n
+    assert not bool((ids == torch.arange(n, device=DEV, dtype=torch.int32)[:, None]).any())
+    assert bool((dists[:, 1:] >= dists[:, :-1]).all()) and bool((dists >= 0).all())
+    srt = ids.sort(dim=1).values
+    assert not bool((srt[:, 1:] == srt[:, :-1]).any())
