@@ -41,6 +41,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 INT8_MFMA_PEAK_TOPS = 5000.0     # dense int8 MFMA (the uint8 build's Gram tiles)
+FP16_MFMA_PEAK_TFLOPS = 2500.0   # dense fp16 MFMA (the fp16 build's Gram tiles)
 SIG_BYTES = 32          # row signature read per gathered member
 # HBM-side bytes per join launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each
 # scaled by what a plain 1 GiB device copy reads: 2.0 and 1.0 KiB per count), averaged over the same
@@ -59,8 +60,9 @@ def parse():
     ap.add_argument("--config", type=int, default=-1,
                     help="workload index (0..5); default 1, for --op search 5 (a set whose graph a walk can cross)")
     ap.add_argument("--n", type=int, default=0, help="override the number of points")
-    ap.add_argument("--elem", choices=("f32", "u8"), default="f32",
-                    help="point storage; u8 (knng_build_knn_graph_u8) needs a workload with 8-bit values: config 1")
+    ap.add_argument("--elem", choices=("f32", "u8", "f16"), default="f32",
+                    help="point storage; u8 (knng_build_knn_graph_u8) needs a workload with 8-bit values: config 1; "
+                         "f16 (knng_build_knn_graph_f16) rounds the workload's values to fp16 first (squared L2 only)")
     ap.add_argument("--op", choices=("build", "optimize", "search"), default="build")
     ap.add_argument("--itopk", type=int, default=64, help="--op search: list length")
     ap.add_argument("--width", type=int, default=1, help="--op search: entries expanded per iteration")
@@ -258,6 +260,13 @@ def main():
             print("bench.py: --elem u8 needs 8-bit point values and squared L2 (config 1)", file=sys.stderr)
             sys.exit(2)
         build, elem_bytes = knng.knng_build_knn_graph_u8, 1
+    if a.elem == "f16":
+        if w.metric != 0:
+            print("bench.py: --elem f16 needs squared L2", file=sys.stderr)
+            sys.exit(2)
+        xb = x.to(torch.float16)
+        x = xb.float()                      # the values the build sees: ground truth and oracle use them
+        build, elem_bytes = knng.knng_build_knn_graph_f16, 2
 
     def step(seed):
         return build(xb, k, w.metric, seed=seed, workspace=ws, ids_out=ids, dists_out=dists, **kw)[2]
@@ -302,7 +311,7 @@ def main():
     last = stats[-1]
     # the join is priced against HBM (a gather) unless its Gram blocks are the larger fraction of
     # their own peak (large samples: s = 32 does four times the pair work per gathered byte)
-    mfma_peak = INT8_MFMA_PEAK_TOPS if a.elem == "u8" else FP32_MFMA_PEAK_TFLOPS
+    mfma_peak = {"u8": INT8_MFMA_PEAK_TOPS, "f16": FP16_MFMA_PEAK_TFLOPS, "f32": FP32_MFMA_PEAK_TFLOPS}[a.elem]
     if needed_tflops / mfma_peak > achieved / HBM_PEAK_GBS:
         bound = {"bound": "mfma", "achieved": needed_tflops, "peak": mfma_peak, "unit": "TFLOP/s",
                  "frac": needed_tflops / mfma_peak, "hbm_gbs": achieved, "frac_of_hbm_peak": achieved / HBM_PEAK_GBS}
@@ -344,8 +353,8 @@ def main():
         "metric": "kNN-graph build points/sec at recall@k>=0.95 (1 MI355X)",
         "value": n / sec, "unit": "points/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if a.elem == "f32" else "i8 x i8 -> i32", "data": "synthetic",
-        "config": {"workload": w.name + ("" if a.elem == "f32" else "_stored_u8"), "n": n, "d": d, "k": k, "metric": ["l2sq", "ip_unit"][w.metric],
+        "dtype": {"f32": "f32", "u8": "i8 x i8 -> i32", "f16": "f16 x f16 -> f32"}[a.elem], "data": "synthetic",
+        "config": {"workload": w.name + ("" if a.elem == "f32" else "_stored_" + a.elem), "n": n, "d": d, "k": k, "metric": ["l2sq", "ip_unit"][w.metric],
                    "k_build": a.k_build or k, "rho": a.rho or 0.5, "delta": a.delta or 1e-4,
                    "iterations": last["iterations"], "converged": last["converged"]},
         "recall_at_k": recall, "recall_at_k_distance": recall_dist, "recall_rows": int(len(rows_s)),
