@@ -272,6 +272,21 @@ int knng_graph_search(const float *points_dev, int64_t n, int32_t d, int32_t met
                       int32_t *ids_out_dev, float *dists_out_dev, int32_t *iters_out_dev,
                       int32_t *evals_out_dev, void *stream);
 
+/*
+ * The same search for points and queries stored as uint8 (squared L2 only; the 8-bit
+ * sets of Sec. 5.2): every distance is the exact integer sum of squared differences
+ * rounded once to fp32, i.e. the result is that of knng_graph_search on the same
+ * values stored as fp32.  points_dev [n][d] and queries_dev [nq][d] uint8, 4-byte
+ * aligned, d % 4 == 0, d <= 65536; everything else as above.
+ */
+int knng_graph_search_u8(const uint8_t *points_dev, int64_t n, int32_t d, int32_t metric,
+                         const int32_t *graph_dev, int32_t deg,
+                         const uint8_t *queries_dev, int64_t nq,
+                         const int32_t *starts_dev, int32_t n_starts,
+                         int32_t k_s, int32_t itopk, int32_t width, int32_t max_iters,
+                         int32_t *ids_out_dev, float *dists_out_dev, int32_t *iters_out_dev,
+                         int32_t *evals_out_dev, void *stream);
+
 /* Text for a return code; for KNNG_EHIP the text of the last HIP failure on this thread. */
 const char *knng_strerror(int code);
 

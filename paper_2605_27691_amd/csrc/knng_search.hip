@@ -14,8 +14,13 @@
 // per id: the lane drops ids that are invalid, repeat an earlier lane's or are in the list,
 // evaluates the distance with the fp64 recipe (the query sits in LDS, the candidate's vector
 // streams through the lane, and stops early where a partial sum already rules the candidate
-// out), drops what cannot enter a full list, and the survivors are merged by counting ranks.  Offering a batch at once gives the same list as offering its ids one by
-// one: the L smallest of a union do not depend on the order of insertion.
+// out), drops what cannot enter a full list, and the survivors are merged by counting ranks.
+// Offering a batch at once gives the same list as offering its ids one by one: the L smallest
+// of a union do not depend on the order of insertion.
+//
+// ELEM = 1: points and queries stored as uint8 (squared L2): the distance is the exact integer
+// sum of squared differences (unsigned 8-bit dot products on packed words), rounded once to fp32
+// -- what the fp64 recipe gives on the same values.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -27,7 +32,15 @@ namespace knng {
 
 __device__ __forceinline__ void wave_lds_sync_search() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-template <int METRIC, bool VEC>
+// four packed uint8 pairs: sum of squared differences = a.a + b.b - 2 a.b
+__device__ __forceinline__ uint32_t search_sqdiff4_u8(uint32_t a, uint32_t b)
+{
+    const uint32_t nn = __builtin_amdgcn_udot4(a, a, __builtin_amdgcn_udot4(b, b, 0u, false), false);
+    return nn - 2u * __builtin_amdgcn_udot4(a, b, 0u, false);
+}
+
+// ELEM 1: pts / queries point at uint8 rows and d counts 32-bit words (4 coordinates)
+template <int METRIC, bool VEC, int ELEM = 0>
 __global__ void __launch_bounds__(256)
 k_graph_search(const float* __restrict__ pts, int64_t n, int d, const int32_t* __restrict__ graph, int deg,
                const float* __restrict__ queries, int64_t nq, const int32_t* __restrict__ starts, int n_starts,
@@ -68,7 +81,25 @@ k_graph_search(const float* __restrict__ pts, int64_t n, int d, const int32_t* _
         // fp32 alike, so a lane whose partial sum already rounds above the list's last distance
         // stops reading its vector -- the candidate would be left out with the full sum too.
         const float worst_d = len == L ? key_dist(bcast64(lk, L - 1)) : __uint_as_float(0x7f800000u);
-        if (ok) {
+        if (ELEM == 1) {
+            if (ok) {
+                const uint32_t* __restrict__ b = reinterpret_cast<const uint32_t*>(pts) + (int64_t)id * d;
+                const uint32_t* qw = reinterpret_cast<const uint32_t*>(qs);
+                uint32_t acc = 0u;
+                if (VEC) {
+                    for (int t = 0; t < d; t += 4) {
+                        if ((float)acc > worst_d) { ok = false; break; }
+                        const uint4 bv = *reinterpret_cast<const uint4*>(b + t);
+                        const uint4 av = *reinterpret_cast<const uint4*>(qw + t);
+                        acc += search_sqdiff4_u8(av.x, bv.x) + search_sqdiff4_u8(av.y, bv.y) +
+                               search_sqdiff4_u8(av.z, bv.z) + search_sqdiff4_u8(av.w, bv.w);
+                    }
+                } else {
+                    for (int t = 0; t < d; ++t) acc += search_sqdiff4_u8(qw[t], b[t]);
+                }
+                dist = (float)acc;
+            }
+        } else if (ok) {
             const float* __restrict__ b = pts + (int64_t)id * d;
             double acc = 0.0;
             if (VEC) {
@@ -169,14 +200,23 @@ k_graph_search(const float* __restrict__ pts, int64_t n, int d, const int32_t* _
 
 using namespace knng;
 
-extern "C" __attribute__((visibility("default"))) int knng_graph_search(const float* points_dev, int64_t n, int32_t d, int32_t metric,
-                                 const int32_t* graph_dev, int32_t deg, const float* queries_dev, int64_t nq,
+// elem 0: fp32 points and queries; elem 1: uint8 (squared L2, d % 4 == 0, d <= 65536)
+static int search_impl(const void* points_void, const void* queries_void, int elem, int64_t n, int32_t d, int32_t metric,
+                                 const int32_t* graph_dev, int32_t deg, int64_t nq,
                                  const int32_t* starts_dev, int32_t n_starts, int32_t k_s, int32_t itopk,
                                  int32_t width, int32_t max_iters, int32_t* ids_out_dev, float* dists_out_dev,
                                  int32_t* iters_out_dev, int32_t* evals_out_dev, void* stream)
 {
+    const float* points_dev = static_cast<const float*>(points_void);   // the kernel casts back for elem 1
+    const float* queries_dev = static_cast<const float*>(queries_void);
     if (!points_dev || !graph_dev || nq < 0) return KNNG_EINVAL;
     if (nq > 0 && (!queries_dev || !starts_dev || !ids_out_dev || !dists_out_dev)) return KNNG_EINVAL;
+    if (elem == 1) {
+        if (metric != KNNG_METRIC_L2SQ || (d & 3) || d > 65536 || (reinterpret_cast<uintptr_t>(points_void) & 3u) ||
+            (reinterpret_cast<uintptr_t>(queries_void) & 3u))
+            return KNNG_EINVAL;
+        d /= 4;                                                 // words from here on
+    }
     if (n < 1 || n > 2147483647LL || d < 1 || deg < 1 || deg > KNNG_MAX_K || n_starts < 1 || n_starts > KNNG_MAX_K)
         return KNNG_EINVAL;
     if (k_s < 1 || itopk < k_s || itopk > KNNG_MAX_K || width < 1 || width > KNNG_MAX_K || max_iters < 0)
@@ -187,8 +227,9 @@ extern "C" __attribute__((visibility("default"))) int knng_graph_search(const fl
     if (nq == 0) return KNNG_OK;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(points_dev) & 15u) == 0);
-    auto kern = metric == 0 ? (vec ? k_graph_search<0, true> : k_graph_search<0, false>)
-                            : (vec ? k_graph_search<1, true> : k_graph_search<1, false>);
+    auto kern = elem == 1 ? (vec ? k_graph_search<0, true, 1> : k_graph_search<0, false, 1>)
+              : metric == 0 ? (vec ? k_graph_search<0, true, 0> : k_graph_search<0, false, 0>)
+                            : (vec ? k_graph_search<1, true, 0> : k_graph_search<1, false, 0>);
     hipError_t e;
     if (lds > 48 * 1024) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -200,4 +241,24 @@ extern "C" __attribute__((visibility("default"))) int knng_graph_search(const fl
     if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e, "k_graph_search launch");
     if ((e = hipStreamSynchronize(st)) != hipSuccess) return set_hip_error(e, "hipStreamSynchronize");
     return KNNG_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int knng_graph_search(const float* points_dev, int64_t n, int32_t d, int32_t metric,
+                                 const int32_t* graph_dev, int32_t deg, const float* queries_dev, int64_t nq,
+                                 const int32_t* starts_dev, int32_t n_starts, int32_t k_s, int32_t itopk,
+                                 int32_t width, int32_t max_iters, int32_t* ids_out_dev, float* dists_out_dev,
+                                 int32_t* iters_out_dev, int32_t* evals_out_dev, void* stream)
+{
+    return search_impl(points_dev, queries_dev, 0, n, d, metric, graph_dev, deg, nq, starts_dev, n_starts, k_s, itopk,
+                       width, max_iters, ids_out_dev, dists_out_dev, iters_out_dev, evals_out_dev, stream);
+}
+
+extern "C" __attribute__((visibility("default"))) int knng_graph_search_u8(const uint8_t* points_dev, int64_t n, int32_t d, int32_t metric,
+                                    const int32_t* graph_dev, int32_t deg, const uint8_t* queries_dev, int64_t nq,
+                                    const int32_t* starts_dev, int32_t n_starts, int32_t k_s, int32_t itopk,
+                                    int32_t width, int32_t max_iters, int32_t* ids_out_dev, float* dists_out_dev,
+                                    int32_t* iters_out_dev, int32_t* evals_out_dev, void* stream)
+{
+    return search_impl(points_dev, queries_dev, 1, n, d, metric, graph_dev, deg, nq, starts_dev, n_starts, k_s, itopk,
+                       width, max_iters, ids_out_dev, dists_out_dev, iters_out_dev, evals_out_dev, stream);
 }

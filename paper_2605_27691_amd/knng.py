@@ -50,7 +50,7 @@ class Params(ctypes.Structure):
 EXPORTS = ("knng_build_workspace_bytes", "knng_build_knn_graph", "knng_build_knn_graph_u8", "knng_build_knn_graph_f16",
            "knng_brute_workspace_bytes",
            "knng_brute_knn", "knng_graph_recall", "knng_merge_graphs", "knng_optimize_workspace_bytes",
-           "knng_optimize_graph", "knng_graph_search", "knng_strerror", "knng_version")
+           "knng_optimize_graph", "knng_graph_search", "knng_graph_search_u8", "knng_strerror", "knng_version")
 
 _lib = None
 
@@ -91,6 +91,8 @@ def load():
     L.knng_optimize_graph.argtypes = [_P, i64, i32, i32, _P, _P, u64, _P]
     L.knng_graph_search.restype = ctypes.c_int
     L.knng_graph_search.argtypes = [_P, i64, i32, i32, _P, i32, _P, i64, _P, i32, i32, i32, i32, i32, _P, _P, _P, _P, _P]
+    L.knng_graph_search_u8.restype = ctypes.c_int
+    L.knng_graph_search_u8.argtypes = L.knng_graph_search.argtypes
     L.knng_strerror.restype = ctypes.c_char_p
     L.knng_strerror.argtypes = [ctypes.c_int]
     L.knng_version.restype = ctypes.c_int
@@ -297,14 +299,13 @@ def knng_optimize_graph(ids, d_out, workspace=None, ids_out=None):
     return ids_out
 
 
-def knng_graph_search(points, graph, queries, starts, k_s, itopk, width=1, max_iters=64, metric=L2SQ,
-                      want_iters=False):
+def _graph_search(entry, dtype, points, graph, queries, starts, k_s, itopk, width, max_iters, metric, want_iters):
     """Greedy search of `queries` ([nq][d] fp32) over `graph` ([n][deg] int32) from `starts`
     ([nq][n_starts] int32); all GPU tensors.
     -> (ids [nq][k_s], dists [nq][k_s][, iterations per query, distance evaluations per query])."""
     L = load()
-    points = _dev(points, torch.float32, "points")
-    queries = _dev(queries, torch.float32, "queries")
+    points = _dev(points, dtype, "points")
+    queries = _dev(queries, dtype, "queries")
     graph = _dev(graph, torch.int32, "graph")
     starts = _dev(starts, torch.int32, "starts")
     n, d = points.shape
@@ -315,7 +316,21 @@ def knng_graph_search(points, graph, queries, starts, k_s, itopk, width=1, max_i
     dists = torch.empty((nq, k_s), dtype=torch.float32, device=points.device)
     iters = torch.empty(nq, dtype=torch.int32, device=points.device) if want_iters else None
     evals = torch.empty(nq, dtype=torch.int32, device=points.device) if want_iters else None
-    _check(L.knng_graph_search(_ptr(points), n, d, metric, _ptr(graph), graph.shape[1], _ptr(queries), nq,
+    _check(getattr(L, entry)(_ptr(points), n, d, metric, _ptr(graph), graph.shape[1], _ptr(queries), nq,
                                _ptr(starts), starts.shape[1], k_s, itopk, width, max_iters, _ptr(ids),
                                _ptr(dists), _ptr(iters), _ptr(evals), _stream()))
     return (ids, dists, iters, evals) if want_iters else (ids, dists)
+
+
+def knng_graph_search(points, graph, queries, starts, k_s, itopk, width=1, max_iters=64, metric=L2SQ,
+                      want_iters=False):
+    """Greedy search of `queries` ([nq][d] fp32) over `graph` ([n][deg] int32) from `starts`."""
+    return _graph_search("knng_graph_search", torch.float32, points, graph, queries, starts, k_s, itopk, width,
+                         max_iters, metric, want_iters)
+
+
+def knng_graph_search_u8(points, graph, queries, starts, k_s, itopk, width=1, max_iters=64, metric=L2SQ,
+                         want_iters=False):
+    """The same for uint8 `points` and `queries` (squared L2, d % 4 == 0)."""
+    return _graph_search("knng_graph_search_u8", torch.uint8, points, graph, queries, starts, k_s, itopk, width,
+                         max_iters, metric, want_iters)

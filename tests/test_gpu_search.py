@@ -140,3 +140,45 @@ def test_one_refinement_level_on_one_gpu_build_optimise_search_merge():
     before = knng.knng_graph_recall(torch.cat([local[0][0], local[1][0] + half]), torch.cat([local[0][1], local[1][1]]),
                                     ex[0], ex[1], k, 0)
     assert before < 0.7 and rec >= 0.95, (before, rec)
+
+
+# ------------------------------------------------------------------ uint8 points and queries
+def _both_u8(x8, g, q8, st, k_s, L, width, cap):
+    gi, gd, git, gev = knng.knng_graph_search_u8(_gpu(x8), _gpu(g), _gpu(q8), _gpu(st), k_s, L, width, cap, 0,
+                                                 want_iters=True)
+    oi, od, oit, oev = oracle.graph_search(x8, g, q8, st, k_s, L, width, cap, 0, want_evals=True)
+    return (gi.cpu().numpy(), gd.cpu().numpy(), git.cpu().numpy(), gev.cpu().numpy()), (oi, od, oit, oev)
+
+
+@pytest.mark.parametrize("n,d,deg,nq,k_s,L,width,cap,ns", [
+    (4000, 128, 16, 300, 10, 32, 1, 100, 8),         # 16-byte pieces
+    (3000, 64, 32, 200, 32, 64, 2, 100, 32),
+    (2000, 20, 8, 150, 5, 8, 3, 100, 1),             # d % 16 != 0: 4-byte words
+    (1500, 960, 24, 40, 8, 24, 1, 100, 4),           # distances above 2^24
+    (2000, 4, 12, 100, 12, 12, 64, 3, 5),            # one word per row, capped iterations
+])
+def test_search_u8_bit_exact_against_the_oracle(n, d, deg, nq, k_s, L, width, cap, ns):
+    rng = np.random.default_rng(n + d)
+    c = rng.integers(0, 256, (10, d)).astype(np.float64)
+    x8 = np.clip(np.rint(c[rng.integers(0, 10, n)] + 25.0 * rng.standard_normal((n, d))), 0, 255).astype(np.uint8)
+    q8 = np.clip(np.rint(c[rng.integers(0, 10, nq)] + 25.0 * rng.standard_normal((nq, d))), 0, 255).astype(np.uint8)
+    g = oracle.brute_knn(x8, deg, 0)[0]
+    st = rng.integers(0, n, (nq, ns)).astype(np.int32)
+    got, want = _both_u8(x8, g, q8, st, k_s, L, width, cap)
+    _assert_same(got, want)
+    # and the same answer as the fp32 search of the same values
+    f = knng.knng_graph_search(_gpu(x8.astype(np.float32)), _gpu(g), _gpu(q8.astype(np.float32)), _gpu(st), k_s, L,
+                               width, cap, 0)
+    assert np.array_equal(f[0].cpu().numpy(), got[0]) and np.array_equal(f[1].cpu().numpy(), got[1])
+
+
+def test_search_u8_argument_errors():
+    rng = np.random.default_rng(2)
+    x8 = rng.integers(0, 256, (400, 32), dtype=np.uint8)
+    g = oracle.brute_knn(x8, 8, 0)[0]
+    st = rng.integers(0, 400, (10, 4)).astype(np.int32)
+    xg, qg, gg, sg = _gpu(x8), _gpu(x8[:10]), _gpu(g), _gpu(st)
+    with pytest.raises(knng.KnngError):
+        knng.knng_graph_search_u8(xg, gg, qg, sg, 4, 8, metric=1)
+    with pytest.raises(knng.KnngError):
+        knng.knng_graph_search_u8(xg[:, :30].contiguous(), gg, qg[:, :30].contiguous(), sg, 4, 8)
