@@ -150,33 +150,44 @@ def bench_search(a):
     torch.cuda.set_device(dev)
     x, w = workloads.make(a.config, n=(a.n or None), device=dev)
     n, d, k = w.n // 2, w.d, w.k
-    pa, qb = x[:n].contiguous(), x[n:2 * n].contiguous()
+    build, search, elem_bytes = knng.knng_build_knn_graph, knng.knng_graph_search, 4
+    if a.elem == "u8":                      # the workload quantised to 8 bits: x -> round(24 x + 128), clipped
+        if w.metric != 0:
+            print("bench.py: --elem u8 needs squared L2", file=sys.stderr)
+            sys.exit(2)
+        x = (x * 24.0 + 128.0).round_().clamp_(0.0, 255.0)
+        build, search, elem_bytes = knng.knng_build_knn_graph_u8, knng.knng_graph_search_u8, 1
+    elif a.elem != "f32":
+        print("bench.py: --op search takes --elem f32 or u8", file=sys.stderr)
+        sys.exit(2)
+    pa, qb = x[:n].contiguous(), x[n:2 * n].contiguous()      # fp32 values: ground truth and the oracle use them
     del x
+    sa, sq = (pa.to(torch.uint8), qb.to(torch.uint8)) if a.elem == "u8" else (pa, qb)
     nq = qb.shape[0]
     d_out = a.d_out or k
-    g_ids, _, st = knng.knng_build_knn_graph(pa, k, w.metric, seed=0, k_build=a.k_build, rho=a.rho, delta=a.delta)
+    g_ids, _, st = build(sa, k, w.metric, seed=0, k_build=a.k_build, rho=a.rho, delta=a.delta)
     gs = knng.knng_optimize_graph(g_ids, d_out)
     del g_ids
     gen = torch.Generator(device="cpu").manual_seed(12345)
     starts = torch.randint(0, n, (nq, a.n_starts), generator=gen, dtype=torch.int32).to(dev)
-    args = (pa, gs, qb, starts, k, a.itopk, a.width, a.max_search_iters, w.metric)
+    args = (sa, gs, sq, starts, k, a.itopk, a.width, a.max_search_iters, w.metric)
     for _ in range(a.warmup):
-        knng.knng_graph_search(*args)
+        search(*args)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
     for _ in range(a.steps):
-        ids, dists = knng.knng_graph_search(*args)
+        ids, dists = search(*args)
     e1.record()
     torch.cuda.synchronize()
     sec = (time.perf_counter() - t0) / max(a.steps, 1)
     dev_ms = e0.elapsed_time(e1) / max(a.steps, 1)
-    ids, dists, iters, evals = knng.knng_graph_search(*args, want_iters=True)
+    ids, dists, iters, evals = search(*args, want_iters=True)
     tot_iters, tot_evals = int(iters.sum()), int(evals.sum())
     # algorithmic bytes: every evaluated candidate's vector, every expanded row, per query its
     # vector, start ids and result
-    alg_bytes = tot_evals * 4 * d + tot_iters * a.width * 4 * d_out + nq * (4 * d + 4 * a.n_starts + 8 * k)
+    alg_bytes = tot_evals * elem_bytes * d + tot_iters * a.width * 4 * d_out + nq * (elem_bytes * d + 4 * a.n_starts + 8 * k)
     achieved = alg_bytes / (dev_ms * 1e-3) / 1e9
     # recall on a sample: exact neighbours among the first half by fp32 products in chunks (outside
     # the timed region; quality only, nothing is compared bit for bit with it)
@@ -205,8 +216,8 @@ def bench_search(a):
         "metric": "graph search queries/sec (1 MI355X)",
         "value": nq / sec, "unit": "queries/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f64", "data": "synthetic",
-        "config": {"workload": w.name + "_second_half_searches_first_half", "n": n, "nq": nq, "d": d, "k_s": k,
+        "dtype": "f64" if a.elem == "f32" else "u8 x u8 -> u32", "data": "synthetic",
+        "config": {"workload": w.name + ("" if a.elem == "f32" else "_quantised_u8") + "_second_half_searches_first_half", "n": n, "nq": nq, "d": d, "k_s": k,
                    "graph_degree": d_out, "itopk": a.itopk, "width": a.width, "n_starts": a.n_starts,
                    "max_iters": a.max_search_iters, "metric": ["l2sq", "ip_unit"][w.metric]},
         "recall_at_k": recall, "recall_rows": ns,
@@ -216,7 +227,7 @@ def bench_search(a):
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      # profiles/k_graph_search_manifold16_500k_d128.txt (FETCH_SIZE + WRITE_SIZE), default arguments
                      "traffic": 417.3e9 if (w.name, a.itopk, a.width, a.n_starts, d_out) ==
-                                ("manifold16_1m_d128_l2", 64, 1, 32, 32) and not a.n else None,
+                                ("manifold16_1m_d128_l2", 64, 1, 32, 32) and not a.n and a.elem == "f32" else None,
                      "device_ms_per_call": dev_ms, "alg_bytes_per_call": alg_bytes},
         "cpu_baseline": {"value": no / cpu_sec, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
                          "sample": f"oracle_graph_search on the first {no} queries, {cpu_sec:.1f} s"},
