@@ -64,16 +64,17 @@ k_graph_search(const float* __restrict__ pts, int64_t n, int d, const int32_t* _
 
     // offer the ids held by lanes < cnt
     auto offer_batch = [&](int id, int cnt) {
-        bool ok = lane < cnt && id >= 0 && (int64_t)id < n;
-        for (int j = 0; j < cnt; ++j) {                         // an earlier lane holds the same id
-            const int oj = (int)bcast32((uint32_t)id, j);
-            ok = ok && !(j < lane && oj == id);
+        // one sweep over the batch: lane j's id is dropped if the list holds it, and later lanes
+        // that repeat it are dropped (lanes >= cnt hold -1 and match nothing)
+        const int lid = lane < len ? key_id(lk) : -1;
+        u64 okm = __ballot(lane < cnt && id >= 0 && (int64_t)id < n);
+        for (int j = 0; j < cnt; ++j) {
+            if (!((okm >> j) & 1ull)) continue;                 // uniform
+            const int idj = (int)bcast32((uint32_t)id, j);
+            if (__ballot(lid == idj) != 0ull) { okm &= ~(1ull << j); continue; }
+            okm &= ~__ballot(lane > j && id == idj);
         }
-        for (int j = 0; j < len; ++j) {                         // already in the list
-            const int lj = key_id(bcast64(lk, j));
-            ok = ok && lj != id;
-        }
-        const u64 okm = __ballot(ok);
+        bool ok = (okm >> lane) & 1ull;
         if (okm == 0ull) return;
         evals += __popcll(okm);
         float dist = 0.0f;
