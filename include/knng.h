@@ -1,7 +1,15 @@
 /*
  * knng.h -- C ABI of libknng: single-GPU k-nearest-neighbour-graph construction
  * for AMD MI355X (gfx950), after the local kNNG construction of SOLANET
- * (paper Sec. 3.1 "NN-Descent" and Sec. 3.1.1 "Lock-Free GPU-based NN-Descent").
+ * (paper Sec. 3.1 "NN-Descent" and Sec. 3.1.1 "Lock-Free GPU-based NN-Descent"),
+ * and the local building blocks of its refinement across partitions.
+ *
+ *   knng_build_knn_graph[_u8|_f16]  approximate k-NN graph            (Sec. 3.1, 3.1.1)
+ *   knng_brute_knn                  exact k-NN rows                    (Sec. 2.1, 5.3.1)
+ *   knng_graph_recall               recall of one graph against another (Sec. 2.1, 5.4.3)
+ *   knng_merge_graphs               rows updated with search results   (Sec. 4.3, 4.4)
+ *   knng_optimize_graph             k-NN graph -> search graph          (Sec. 3.3)
+ *   knng_graph_search[_u8]          graph search for query points      (Sec. 3.2)
  *
  * Conventions for every entry point
  *   - Pointers named *_dev are DEVICE pointers (hipMalloc-class memory, as the
