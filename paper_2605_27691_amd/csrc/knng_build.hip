@@ -600,8 +600,13 @@ __device__ __forceinline__ int member_of_slot(int t, int s, int4 c)
 // ELEM 1: uint8 rows handled as d 32-bit words, signed bytes x - 128 in LDS, integer Gram tiles
 // (v_mfma_i32_16x16x64_i8) -- see knng_join_wave.h; here wavefront w also owns the products of
 // the pivot with the member tiles w, w + 4, ... (one accumulator, a column per tile).
+// Wavefronts per SIMD the register allocation aims at.  128 member slots: three (left to itself
+// the compiler parks the accumulators in 32 AGPRs on top of 152 VGPRs, which allows two; told to
+// fit three it needs 149 registers and no spill, and the join runs 28 % faster).  256 member
+// slots: one workgroup per CU by LDS (the distance block alone is 132 KB).
+template <int S16> struct JoinOcc { static constexpr int V = S16 == 4 ? 3 : 1; };
 template <int METRIC, int S16, int DS_, bool VEC, int ELEM = 0>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(JoinOcc<S16>::V, JoinOcc<S16>::V)))
 k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
        const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl, const int4* __restrict__ plan,
        const int32_t* __restrict__ active, const u64* __restrict__ nactive_ptr,
