@@ -31,9 +31,10 @@ constexpr int OPT_HT = 128;                       // hash slots per wavefront (>
 // ------------------------------------------------------------------------------------------
 // k_opt_prune: lane j holds entry j of row u.  The row's ids go into a hash table id -> first
 // rank (LDS, open addressing).  For every valid neighbour w (rank i) the wavefront reads w's row
-// (lane r holds its entry r), looks each entry up in the table and, where it is u's neighbour of
-// a rank j > max(i, r), sets bit i of that neighbour's word: c(u,j) is the number of bits.  A
-// repeated id in w's row sets the same bit again, so "some r < j" is counted once.
+// (a lane per entry r; two rows per load at k <= 32), looks each entry up in the table and, where
+// it is u's neighbour of a rank j > max(i, r), sets bit i of that neighbour's word: c(u,j) is the
+// number of bits.  A repeated id in w's row sets the same bit again, so "some r < j" is counted
+// once.
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 k_opt_prune(const int32_t* __restrict__ ids, int64_t n, int k, int d_out, int2* __restrict__ P,
@@ -75,32 +76,34 @@ k_opt_prune(const int32_t* __restrict__ ids, int64_t n, int k, int d_out, int2* 
     const bool valid = inr && lookup(my) == lane;
     const u64 vmask = __ballot(valid);
 
-    // four neighbour rows per step, the next step's rows in flight meanwhile
+    // A wavefront reads 64 / kp neighbour rows per load (kp = the power of two >= k: lane ->
+    // row `lane / kp` of the group, entry `lane % kp`), four loads per step, the next step's in
+    // flight meanwhile.
+    int kp = 1;
+    while (kp < k) kp <<= 1;
+    const int rpl = WAVE / kp;                                 // rows per load
+    const int sub = lane / kp, r = lane & (kp - 1);
     int xn[4];
     auto issue = [&](int i0) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int i = i0 + t;
+            const int i = i0 + t * rpl + sub;
+            const int wi = __shfl(my, i < k ? i : 0);          // all lanes take part
             xn[t] = -1;
-            if (i < k && ((vmask >> i) & 1ull)) {              // uniform
-                const int wi = __builtin_amdgcn_readlane(my, i);
-                if (lane < k) xn[t] = ids[(int64_t)wi * k + lane];
-            }
+            if (i < k && r < k && ((vmask >> i) & 1ull)) xn[t] = ids[(int64_t)wi * k + r];
         }
     };
     issue(0);
-    for (int i0 = 0; i0 < k; i0 += 4) {
+    for (int i0 = 0; i0 < k; i0 += 4 * rpl) {
         int x[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) x[t] = xn[t];
-        if (i0 + 4 < k) issue(i0 + 4);
+        if (i0 + 4 * rpl < k) issue(i0 + 4 * rpl);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int i = i0 + t;
-            if (i < k && ((vmask >> i) & 1ull)) {              // uniform
-                const int j = (lane < k && x[t] >= 0) ? lookup(x[t]) : k;
-                if (j < k && j > i && j > lane) atomicOr(&bits[w][i >> 5][j], 1u << (i & 31));
-            }
+            const int i = i0 + t * rpl + sub;
+            const int j = x[t] >= 0 ? lookup(x[t]) : k;        // x = -1: row absent, padding or past k
+            if (j < k && j > i && j > r) atomicOr(&bits[w][i >> 5][j], 1u << (i & 31));
         }
     }
     wave_lds_sync_opt();
@@ -218,6 +221,7 @@ k_opt_merge(const int2* __restrict__ P, const u64* __restrict__ start, const u64
             int64_t n, int d_out, int32_t* __restrict__ out)
 {
     __shared__ int rowb[4][WAVE];
+    __shared__ u64 sortb[4][WAVE];
     const int lane = lane_id(), w = threadIdx.x >> 6;
     const int64_t v = (int64_t)blockIdx.x * 4 + w;
     if (v >= n) return;
@@ -250,6 +254,17 @@ k_opt_merge(const int2* __restrict__ P, const u64* __restrict__ start, const u64
     u64 bound = 0;
     bool have_bound = false;
     int64_t taken = 0;
+    if (L <= WAVE && m < d_out && L > 0) {
+        // the usual case, a list that fits the lanes: sort it by counting ranks (the words are distinct)
+        const u64 key = lane < L ? E[base + lane] : INF;
+        int rank = 0;
+        for (int j = 0; j < (int)L; ++j) rank += bcast64(key, j) < key ? 1 : 0;
+        if (lane < L) sortb[w][rank] = key;
+        wave_lds_sync_opt();
+        const u64 sorted = lane < L ? sortb[w][lane] : INF;
+        append(lane < L, (int)(uint32_t)sorted);
+        taken = L;
+    }
     while (m < d_out && taken < L) {
         u64 best = INF;                                         // ascending over the lanes
         for (int64_t off = 0; off < L; off += WAVE) {
