@@ -256,6 +256,8 @@ k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
          u64* __restrict__ updates, uint32_t* __restrict__ rev, int B)
 {
     __shared__ u64 rowbuf[4][WAVE];
+    __shared__ u64 candbuf[4][WAVE];                 // the accepted candidates' order words, compacted
+    __shared__ u64 lobuf[4][WAVE];                   // the row's order words
     __shared__ uint32_t sigbuf[4][SIG_WORDS];
     __shared__ u64 part[4];
     const int lane = lane_id();
@@ -302,22 +304,32 @@ k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
             {
                 const u64 vm = __ballot(valid);
                 if (vm != 0ull) {
-                    // ranks in the union of the row and the accepted candidates: one pass over
-                    // the candidates; candidate j learns how many row entries precede it from
-                    // the vote of the row's lanes
-                    const u64 rowmask = K >= 64 ? ~0ull : ((1ull << K) - 1ull);
+                    // ranks in the union of the row and the accepted candidates.  The candidates'
+                    // order words are compacted into LDS and every lane walks them (one broadcast
+                    // read each): a row entry moves up by the candidates before it, a candidate
+                    // lands after the candidates before it and the row entries before it (a
+                    // binary search in the row, which is ascending).
+                    const int nv = __popcll(vm);
+                    if (valid) candbuf[w][__popcll(vm & lt)] = co;
+                    if (lane < K) lobuf[w][lane] = lo;
+                    wave_lds_sync();
                     int rl = lane;                   // the row is ascending already
-                    int rc = 0, rrow = 0;
-                    for (u64 m = vm; m; m &= m - 1) {
-                        const int j = __ffsll((long long)m) - 1;
-                        const u64 cj = bcast64(co, j);
-                        const bool before = cj < lo;
-                        rl += before ? 1 : 0;
-                        rc += (cj < co) ? 1 : 0;
-                        const int nrow = K - __popcll(__ballot(before) & rowmask);
-                        rrow = lane == j ? nrow : rrow;
+                    int rc = 0;
+#pragma unroll 4
+                    for (int j = 0; j < nv; ++j) {
+                        const u64 cj = candbuf[w][j];
+                        rl += cj < lo ? 1 : 0;
+                        rc += cj < co ? 1 : 0;
                     }
-                    rc += rrow;
+                    {
+                        int a = 0, b = K;
+                        while (__ballot(a < b) != 0ull) {
+                            const int mid = (a + b) >> 1;
+                            const u64 lm = lobuf[w][mid < WAVE ? mid : WAVE - 1];
+                            if (a < b) { if (lm < co) a = mid + 1; else b = mid; }
+                        }
+                        rc += a;
+                    }
                     const bool in = valid && rc < K;
                     if (lane < K && rl < K) rowbuf[w][rl] = row;
                     if (in) rowbuf[w][rc] = ck | 1ull;
