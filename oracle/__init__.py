@@ -27,6 +27,8 @@ def lib():
         L.oracle_num_threads.restype = ctypes.c_int
         L.oracle_brute_knn.restype = ctypes.c_int
         L.oracle_brute_knn.argtypes = [P, c_i64, c_i32, c_i32, c_i32, P, c_i64, P, P]
+        L.oracle_brute_knn_base.restype = ctypes.c_int
+        L.oracle_brute_knn_base.argtypes = [P, c_i64, c_i64, c_i32, c_i32, c_i32, P, c_i64, P, P]
         L.oracle_graph_recall.restype = c_f64
         L.oracle_graph_recall.argtypes = [P, P, c_i32, P, P, c_i32, c_i64, c_i32, c_i32]
         L.oracle_check_graph.restype = c_i64
@@ -70,15 +72,17 @@ def distance(a, b, metric=L2SQ) -> np.float32:
     return np.float32(lib().oracle_distance(_p(a), _p(b), a.shape[0], metric))
 
 
-def brute_knn(points, k, metric=L2SQ, query_rows=None):
-    """Exact k-NN rows for all points (or for query_rows).  -> (ids i32, dists f32)."""
+def brute_knn(points, k, metric=L2SQ, query_rows=None, n_base=None):
+    """Exact k-NN rows for all points (or for query_rows), among all points or the first n_base.
+    -> (ids i32, dists f32)."""
     x = _f32(points)
     n, d = x.shape
     q = None if query_rows is None else _i32(query_rows)
     nq = n if q is None else q.shape[0]
     ids = np.empty((nq, k), dtype=np.int32)
     dists = np.empty((nq, k), dtype=np.float32)
-    rc = lib().oracle_brute_knn(_p(x), n, d, k, metric, _p(q), nq, _p(ids), _p(dists))
+    rc = lib().oracle_brute_knn_base(_p(x), n, n if n_base is None else n_base, d, k, metric, _p(q), nq,
+                                     _p(ids), _p(dists))
     if rc != 0:
         raise ValueError(f"oracle_brute_knn: bad arguments (rc={rc})")
     return ids, dists

@@ -96,12 +96,24 @@ static int key_less(float da, int32_t ia, float db, int32_t ib)
 /* The only parallelism is one query row per OpenMP iteration.               */
 /* Returns 0, or -1 on bad arguments.                                        */
 /* ------------------------------------------------------------------------ */
+/* oracle_brute_knn_base: the same with the candidates restricted to the first */
+/* n_base points (the exact neighbours of one partition's points in another     */
+/* partition: Sec. 4.3); query rows may be any of the n points.                 */
+int oracle_brute_knn_base(const float *points, int64_t n, int64_t n_base, int32_t d, int32_t k, int32_t metric,
+                          const int32_t *query_rows, int64_t nq, int32_t *ids_out, float *dists_out);
+
 int oracle_brute_knn(const float *points, int64_t n, int32_t d, int32_t k, int32_t metric,
                      const int32_t *query_rows, int64_t nq,
                      int32_t *ids_out, float *dists_out)
 {
-    if (!points || !ids_out || !dists_out || n < 2 || d < 1 || k < 1 || k > n - 1 ||
-        metric < 0 || metric > 2 || nq < 0)
+    return oracle_brute_knn_base(points, n, n, d, k, metric, query_rows, nq, ids_out, dists_out);
+}
+
+int oracle_brute_knn_base(const float *points, int64_t n, int64_t n_base, int32_t d, int32_t k, int32_t metric,
+                          const int32_t *query_rows, int64_t nq, int32_t *ids_out, float *dists_out)
+{
+    if (!points || !ids_out || !dists_out || n < 2 || n_base < 2 || n_base > n || d < 1 || k < 1 ||
+        k > n_base - 1 || metric < 0 || metric > 2 || nq < 0)
         return -1;
 #pragma omp parallel for schedule(dynamic, 4)
     for (int64_t q = 0; q < nq; ++q) {
@@ -110,7 +122,7 @@ int oracle_brute_knn(const float *points, int64_t n, int32_t d, int32_t k, int32
         int32_t *oi = ids_out + q * (int64_t)k;
         float *od = dists_out + q * (int64_t)k;
         int32_t cnt = 0;
-        for (int64_t j = 0; j < n; ++j) {
+        for (int64_t j = 0; j < n_base; ++j) {
             if (j == r) continue;
             float l = oracle_distance(x, points + j * (int64_t)d, d, metric);
             if (cnt == k && !key_less(l, (int32_t)j, od[k - 1], oi[k - 1])) continue;

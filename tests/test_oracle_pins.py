@@ -230,6 +230,26 @@ def test_brute_knn_matches_library_topk_on_tie_free_data():
     np.testing.assert_allclose(dd, wd.numpy(), rtol=1e-6)
 
 
+def test_brute_knn_restricted_to_a_base_prefix():
+    # the neighbours, among the first n_base points, of rows inside and outside that prefix:
+    # enumeration in int64 on integer data (ties by id)
+    rng = np.random.default_rng(23)
+    n, n_base, d, k = 90, 50, 5, 6
+    x = rng.integers(-4, 5, (n, d)).astype(np.float32)
+    rows = np.array([0, 49, 50, 89, 7, 63], np.int32)
+    ids, dists = oracle.brute_knn(x, k, oracle.L2SQ, query_rows=rows, n_base=n_base)
+    xi = x.astype(np.int64)
+    for q, r in enumerate(rows):
+        dd = ((xi[:n_base] - xi[r]) ** 2).sum(axis=1)
+        order = sorted((int(dd[j]), j) for j in range(n_base) if j != r)[:k]
+        assert ids[q].tolist() == [j for _, j in order]
+        assert dists[q].tolist() == [float(l) for l, _ in order]
+    with pytest.raises(ValueError):
+        oracle.brute_knn(x, k, oracle.L2SQ, query_rows=rows, n_base=n + 1)
+    with pytest.raises(ValueError):
+        oracle.brute_knn(x, 6, oracle.L2SQ, query_rows=rows, n_base=6)
+
+
 def test_brute_knn_query_rows_subset_and_argument_checks():
     x, w = workloads.make(0, n=500)
     full_i, full_d = oracle.brute_knn(x, 7, w.metric)
