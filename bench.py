@@ -165,8 +165,8 @@ def bench_search(a):
     elif a.elem != "f32":
         print("bench.py: --op search takes --elem f32 or u8", file=sys.stderr)
         sys.exit(2)
-    pa, qb = x[:n].contiguous(), x[n:2 * n].contiguous()      # fp32 values: ground truth and the oracle use them
-    del x
+    x = x[:2 * n].contiguous()                              # fp32 values: ground truth and the oracle use them
+    pa, qb = x[:n], x[n:]
     sa, sq = (pa.to(torch.uint8), qb.to(torch.uint8)) if a.elem == "u8" else (pa, qb)
     nq = qb.shape[0]
     d_out = a.d_out or k
@@ -194,22 +194,19 @@ def bench_search(a):
     # vector, start ids and result
     alg_bytes = tot_evals * elem_bytes * d + tot_iters * a.width * 4 * d_out + nq * (elem_bytes * d + 4 * a.n_starts + 8 * k)
     achieved = alg_bytes / (dev_ms * 1e-3) / 1e9
-    # recall on a sample: exact neighbours among the first half by fp32 products in chunks (outside
-    # the timed region; quality only, nothing is compared bit for bit with it)
-    ns = min(2000, nq)
-    sel = torch.from_numpy(workloads.sample_rows(nq, ns)).to(dev).long()
-    qn = qb[sel]
-    if w.metric == 0:
-        sc = (pa * pa).sum(1)[None, :] - 2.0 * (qn @ pa.T)
-    else:
-        sc = -(qn @ pa.T)
-    ex = sc.topk(k, dim=1, largest=False).indices
-    got = ids[sel].long()
-    recall = float((got[:, :, None] == ex[:, None, :]).any(2).float().mean())
-    del sc
+    # recall on a sample (outside the timed region): the exact neighbours, in the first half, of
+    # sampled points of the second half
+    ns = min(a.recall_rows, nq)
+    rows_s = workloads.sample_rows(nq, ns)
+    sel = torch.from_numpy(rows_s).to(dev).long()
+    ex_i, ex_d = knng.knng_brute_knn(x, k, w.metric, (sel + n).int(), n_base=n)
+    recall = knng.knng_graph_recall(ids[sel].contiguous(), dists[sel].contiguous(), ex_i, ex_d, k, 0)
     import oracle
     no = min(a.oracle_queries, nq)
     pa_h, gs_h = pa.cpu().numpy(), gs.cpu().numpy()
+    chk = np.arange(0, ns, max(1, ns // 64))[:64]            # a few exact rows against the oracle's
+    o_ei, o_ed = oracle.brute_knn(x.cpu().numpy(), k, w.metric, query_rows=(rows_s[chk] + n).astype(np.int32), n_base=n)
+    brute_ok = bool(np.array_equal(o_ei, ex_i[chk].cpu().numpy()) and np.array_equal(o_ed, ex_d[chk].cpu().numpy()))
     t1 = time.perf_counter()
     o_i, o_d, o_it, o_ev = oracle.graph_search(pa_h, gs_h, qb[:no].cpu().numpy(), starts[:no].cpu().numpy(), k, a.itopk,
                                                 a.width, a.max_search_iters, w.metric, want_evals=True)
@@ -227,7 +224,7 @@ def bench_search(a):
                    "max_iters": a.max_search_iters, "metric": ["l2sq", "ip_unit"][w.metric]},
         "recall_at_k": recall, "recall_rows": ns,
         "mean_iterations": tot_iters / nq, "mean_distance_evaluations": tot_evals / nq,
-        "oracle_check": {"identical_to_oracle": same, "queries": no},
+        "oracle_check": {"identical_to_oracle": same, "queries": no, "exact_rows_bit_exact": brute_ok},
         "roofline": {"kernel": "k_graph_search", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      # profiles/k_graph_search_manifold16_500k_d128.txt (FETCH_SIZE + WRITE_SIZE), default arguments
@@ -241,8 +238,8 @@ def bench_search(a):
                          "sample": f"oracle_graph_search on the first {no} queries, {cpu_sec:.1f} s"},
     }
     print(json.dumps(res))
-    if not same:
-        print("bench.py: the search results differ from the oracle's", file=sys.stderr)
+    if not same or not brute_ok:
+        print("bench.py: the search results or the exact rows differ from the oracle's", file=sys.stderr)
         sys.exit(1)
 
 

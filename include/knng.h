@@ -212,6 +212,19 @@ int knng_merge_graphs(const int32_t *ids_a_dev, const float *dists_a_dev, int32_
                       int64_t n, int32_t k_out, int32_t *ids_out_dev, float *dists_out_dev,
                       void *stream);
 
+/*
+ * The same with the candidates restricted to the first n_base of the n points:
+ * the exact neighbours, in one partition, of points that may lie in another (the
+ * ground truth for the cross-partition search of Sec. 4.3).  Query rows are any
+ * of the n points; for row r every j < n_base, j != r, is scored.
+ * 2 <= n_base <= n, k <= min(n_base - 1, KNNG_MAX_K); workspace:
+ * knng_brute_workspace_bytes(n, d, k, nq).  Everything else as knng_brute_knn.
+ */
+int knng_brute_knn_base(const float *points_dev, int64_t n, int64_t n_base, int32_t d, int32_t k,
+                        int32_t metric, const int32_t *query_rows_dev, int64_t nq,
+                        int32_t *ids_out_dev, float *dists_out_dev,
+                        void *workspace_dev, uint64_t workspace_bytes, void *stream);
+
 /* Device scratch needed by knng_optimize_graph (0 on bad arguments). */
 uint64_t knng_optimize_workspace_bytes(int64_t n, int32_t k, int32_t d_out);
 

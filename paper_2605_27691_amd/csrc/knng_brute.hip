@@ -449,18 +449,18 @@ extern "C" __attribute__((visibility("default"))) uint64_t knng_brute_workspace_
     return b + (((uint64_t)n * 4u + 255u) & ~255ull);
 }
 
-extern "C" __attribute__((visibility("default"))) int knng_brute_knn(const float* points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,
-                              const int32_t* query_rows_dev, int64_t nq,
-                              int32_t* ids_out_dev, float* dists_out_dev,
-                              void* workspace_dev, uint64_t workspace_bytes, void* stream)
+// candidates: the first n_base of the n_all points; query rows: any of the n_all points
+static int brute_impl(const float* points_dev, int64_t n_all, int64_t n, int32_t d, int32_t k, int32_t metric,
+                      const int32_t* query_rows_dev, int64_t nq, int32_t* ids_out_dev, float* dists_out_dev,
+                      void* workspace_dev, uint64_t workspace_bytes, void* stream)
 {
-    if (!points_dev || n < 2 || n > 2147483647LL || d < 1 || k < 1 || k > KNNG_MAX_K ||
+    if (!points_dev || n < 2 || n > n_all || n_all > 2147483647LL || d < 1 || k < 1 || k > KNNG_MAX_K ||
         (int64_t)k > n - 1 || nq < 0 || (metric != KNNG_METRIC_L2SQ && metric != KNNG_METRIC_IP_UNIT))
         return KNNG_EINVAL;
     if (nq == 0) return KNNG_OK;
     if (!ids_out_dev || !dists_out_dev) return KNNG_EINVAL;
-    if (!query_rows_dev && nq > n) return KNNG_EINVAL;
-    const uint64_t need = knng_brute_workspace_bytes(n, d, k, nq);
+    if (!query_rows_dev && nq > n_all) return KNNG_EINVAL;
+    const uint64_t need = knng_brute_workspace_bytes(n_all, d, k, nq);
     if (!workspace_dev || workspace_bytes < need) return KNNG_EWORKSPACE;
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -475,7 +475,7 @@ extern "C" __attribute__((visibility("default"))) int knng_brute_knn(const float
     if (vec) {
         const uint64_t part_bytes = ((uint64_t)nq * (uint64_t)nsplit * (uint64_t)k * 8u + 255u) & ~255ull;
         float* nrm = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace_dev) + part_bytes);
-        hipLaunchKernelGGL(k_row_norms, dim3((unsigned)((n * 8 + 255) / 256)), dim3(256), 0, st, points_dev, n, d, nrm);
+        hipLaunchKernelGGL(k_row_norms, dim3((unsigned)((n_all * 8 + 255) / 256)), dim3(256), 0, st, points_dev, n_all, d, nrm);
         if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e, "k_row_norms launch");
         const int mlds = 2 * BT * MLD * 4 + SQCAP * 8 + BT * k * 8 + BT * 8 + 256 * 8 + 256 * 4 + 4 * BT * 4 + 16;
         if (metric == 0) {
@@ -510,4 +510,22 @@ extern "C" __attribute__((visibility("default"))) int knng_brute_knn(const float
     if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e, "k_brute_reduce launch");
     if ((e = hipStreamSynchronize(st)) != hipSuccess) return set_hip_error(e, "hipStreamSynchronize");
     return KNNG_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int knng_brute_knn(const float* points_dev, int64_t n, int32_t d, int32_t k, int32_t metric,
+                              const int32_t* query_rows_dev, int64_t nq,
+                              int32_t* ids_out_dev, float* dists_out_dev,
+                              void* workspace_dev, uint64_t workspace_bytes, void* stream)
+{
+    return brute_impl(points_dev, n, n, d, k, metric, query_rows_dev, nq, ids_out_dev, dists_out_dev,
+                      workspace_dev, workspace_bytes, stream);
+}
+
+extern "C" __attribute__((visibility("default"))) int knng_brute_knn_base(const float* points_dev, int64_t n, int64_t n_base, int32_t d, int32_t k,
+                                   int32_t metric, const int32_t* query_rows_dev, int64_t nq,
+                                   int32_t* ids_out_dev, float* dists_out_dev,
+                                   void* workspace_dev, uint64_t workspace_bytes, void* stream)
+{
+    return brute_impl(points_dev, n, n_base, d, k, metric, query_rows_dev, nq, ids_out_dev, dists_out_dev,
+                      workspace_dev, workspace_bytes, stream);
 }

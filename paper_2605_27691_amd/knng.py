@@ -49,7 +49,7 @@ class Params(ctypes.Structure):
 
 EXPORTS = ("knng_build_workspace_bytes", "knng_build_knn_graph", "knng_build_knn_graph_u8", "knng_build_knn_graph_f16",
            "knng_brute_workspace_bytes",
-           "knng_brute_knn", "knng_graph_recall", "knng_merge_graphs", "knng_optimize_workspace_bytes",
+           "knng_brute_knn", "knng_brute_knn_base", "knng_graph_recall", "knng_merge_graphs", "knng_optimize_workspace_bytes",
            "knng_optimize_graph", "knng_graph_search", "knng_graph_search_u8", "knng_strerror", "knng_version")
 
 _lib = None
@@ -80,6 +80,8 @@ def load():
     L.knng_brute_workspace_bytes.argtypes = [i64, i32, i32, i64]
     L.knng_brute_knn.restype = ctypes.c_int
     L.knng_brute_knn.argtypes = [_P, i64, i32, i32, i32, _P, i64, _P, _P, _P, u64, _P]
+    L.knng_brute_knn_base.restype = ctypes.c_int
+    L.knng_brute_knn_base.argtypes = [_P, i64, i64, i32, i32, i32, _P, i64, _P, _P, _P, u64, _P]
     L.knng_graph_recall.restype = ctypes.c_int
     L.knng_graph_recall.argtypes = [_P, _P, i32, _P, _P, i32, i64, i32, i32,
                                     ctypes.POINTER(ctypes.c_double), _P]
@@ -216,8 +218,9 @@ def knng_brute_workspace_bytes(n, d, k, nq) -> int:
     return int(load().knng_brute_workspace_bytes(n, d, k, nq))
 
 
-def knng_brute_knn(points, k, metric=L2SQ, query_rows=None, workspace=None):
-    """Exact k-NN rows of all points, or of `query_rows` (int32 GPU tensor).  -> (ids, dists)."""
+def knng_brute_knn(points, k, metric=L2SQ, query_rows=None, workspace=None, n_base=None):
+    """Exact k-NN rows of all points, or of `query_rows` (int32 GPU tensor), among all points or
+    (knng_brute_knn_base) the first `n_base`.  -> (ids, dists)."""
     L = load()
     points = _dev(points, torch.float32, "points")
     n, d = points.shape
@@ -231,8 +234,12 @@ def knng_brute_knn(points, k, metric=L2SQ, query_rows=None, workspace=None):
     workspace = _dev(workspace, torch.uint8, "workspace")
     ids = torch.empty((nq, k), dtype=torch.int32, device=points.device)
     dists = torch.empty((nq, k), dtype=torch.float32, device=points.device)
-    _check(L.knng_brute_knn(_ptr(points), n, d, k, metric, _ptr(query_rows), nq, _ptr(ids), _ptr(dists),
-                            _ptr(workspace), workspace.numel(), _stream()))
+    if n_base is None:
+        _check(L.knng_brute_knn(_ptr(points), n, d, k, metric, _ptr(query_rows), nq, _ptr(ids), _ptr(dists),
+                                _ptr(workspace), workspace.numel(), _stream()))
+    else:
+        _check(L.knng_brute_knn_base(_ptr(points), n, n_base, d, k, metric, _ptr(query_rows), nq, _ptr(ids),
+                                     _ptr(dists), _ptr(workspace), workspace.numel(), _stream()))
     return ids, dists
 
 

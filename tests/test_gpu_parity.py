@@ -98,6 +98,25 @@ def test_brute_query_rows_and_split_reduction():
     assert ei.shape == (0, 4)
 
 
+@pytest.mark.parametrize("n,n_base,d,k,metric", [(3000, 1700, 32, 16, 0), (5000, 65, 8, 64, 0), (2500, 2500, 96, 10, 1),
+                                                (1200, 700, 13, 7, 0)])
+def test_brute_restricted_to_a_base_prefix_bit_exact(n, n_base, d, k, metric):
+    # the ground truth of a cross-partition search: candidates are the first n_base points,
+    # queries come from both sides of that boundary
+    rng = np.random.default_rng(n + n_base)
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    if metric == 1:
+        x = (x / np.linalg.norm(x, axis=1, keepdims=True)).astype(np.float32)
+    rows = np.unique(np.concatenate([rng.integers(0, n, 300), [0, n_base - 1, min(n_base, n - 1), n - 1]])).astype(np.int32)
+    gi, gd = knng.knng_brute_knn(_gpu(x), k, metric, _gpu(rows), n_base=n_base)
+    oi, od = oracle.brute_knn(x, k, metric, query_rows=rows, n_base=n_base)
+    assert np.array_equal(gi.cpu().numpy(), oi)
+    assert np.array_equal(gd.cpu().numpy().view(np.uint32), od.view(np.uint32))
+    assert int(gi.max()) < n_base
+    with pytest.raises(knng.KnngError):
+        knng.knng_brute_knn(_gpu(x), k, metric, _gpu(rows), n_base=n + 1)
+
+
 def test_brute_argument_errors():
     x = _gpu(np.zeros((10, 4), np.float32))
     with pytest.raises(knng.KnngError):

@@ -88,8 +88,9 @@ def test_search_on_the_search_graph_of_a_built_graph_two_partitions():
     st = rng.integers(0, len(a), (len(b), 64)).astype(np.int32)
     got, want = _both(a, gs, b, st, 16, 64, 1, 100, w.metric)
     _assert_same(got, want)
-    ex = np.argsort(((b[:2000, None, :].astype(np.float64) - a[None, :, :]) ** 2).sum(-1), axis=1)[:, :16]
-    rec = np.mean([len(set(p.tolist()) & set(e.tolist())) / 16 for p, e in zip(got[0][:2000], ex)])
+    rows = (np.arange(2000) + len(a)).astype(np.int32)       # the first 2000 points of B, as rows of x
+    ex_i, ex_d = knng.knng_brute_knn(_gpu(x), 16, w.metric, _gpu(rows), n_base=len(a))
+    rec = knng.knng_graph_recall(_gpu(got[0][:2000]), _gpu(got[1][:2000]), ex_i, ex_d, 16, 0)
     assert rec >= 0.95, rec
 
 
