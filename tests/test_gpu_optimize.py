@@ -116,3 +116,20 @@ def test_optimize_full_size_config1_graph_bit_exact():
         assert not bool((got == torch.arange(w.n, device=DEV, dtype=torch.int32)[:, None]).any())
         srt = got.sort(dim=1).values
         assert not bool((srt[:, 1:] == srt[:, :-1]).any())
+
+
+def test_optimize_random_sizes_and_graphs_against_the_oracle():
+    rng = np.random.default_rng(2024)
+    for t in range(24):
+        n = int(rng.integers(2, 3000))
+        k = int(rng.integers(1, min(64, n - 1) + 1))
+        d_out = int(rng.integers(1, k + 1))
+        if t % 3 == 0:
+            ids = rng.integers(-2, n + 2, (n, k)).astype(np.int32)          # arbitrary entries
+        else:
+            x = rng.standard_normal((n, int(rng.integers(1, 6)))).astype(np.float32)
+            ids = oracle.brute_knn(x, k, oracle.L2SQ)[0]
+            if t % 3 == 2:
+                ids[rng.random(ids.shape) < 0.1] = -1
+        got, want = _both(ids, d_out)
+        assert np.array_equal(got, want), (n, k, d_out)

@@ -183,3 +183,27 @@ def test_search_u8_argument_errors():
         knng.knng_graph_search_u8(xg, gg, qg, sg, 4, 8, metric=1)
     with pytest.raises(knng.KnngError):
         knng.knng_graph_search_u8(xg[:, :30].contiguous(), gg, qg[:, :30].contiguous(), sg, 4, 8)
+
+
+def test_search_random_parameters_against_the_oracle():
+    rng = np.random.default_rng(2025)
+    for t in range(24):
+        n = int(rng.integers(2, 4000))
+        d = int(rng.choice([1, 3, 4, 8, 13, 32, 100]))
+        deg = int(rng.integers(1, min(64, n - 1) + 1))
+        nq = int(rng.integers(1, 200))
+        L = int(rng.integers(1, 65))
+        k_s = int(rng.integers(1, L + 1))
+        width = int(rng.integers(1, 6))
+        cap = int(rng.integers(0, 80))
+        ns = int(rng.integers(1, 65))
+        metric = int(rng.integers(0, 2))
+        x = rng.standard_normal((n, d)).astype(np.float32)
+        q = rng.standard_normal((nq, d)).astype(np.float32)
+        if metric == 1:
+            x /= np.maximum(np.linalg.norm(x, axis=1, keepdims=True), 1e-6)
+            q /= np.maximum(np.linalg.norm(q, axis=1, keepdims=True), 1e-6)
+        g = oracle.brute_knn(x, deg, metric)[0] if t % 2 == 0 else rng.integers(-1, n + 1, (n, deg)).astype(np.int32)
+        st = rng.integers(-1, n + 1, (nq, ns)).astype(np.int32)
+        got, want = _both(x, g, q, st, k_s, L, width, cap, metric)
+        _assert_same(got, want)
