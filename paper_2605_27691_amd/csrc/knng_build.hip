@@ -970,19 +970,126 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
 
 // ------------------------------------------------------------------------------------------
 // k_finalize: lane i of a group of Kp = pow2 >= K lanes owns neighbour i of one point, 64/Kp
-// points per wavefront.  The lane walks its neighbour's vector and the point's own (the same
-// address across the group: one fetch) in index order with the fp64 recipe, so the value
-// written equals a sequential fp64 evaluation bit for bit.  A lane's 16-byte loads run along
-// one row and rely on the caches for the rest of each line.  Rows are then ranked by
-// (distance, id) and the first k written as ids / distances.
+// points per wavefront.  The lane evaluates its neighbour's distance in index order with the
+// fp64 recipe, so the value written equals a sequential fp64 evaluation bit for bit.  Rows are
+// then ranked by (distance, id) and the first k written as ids / distances.
+//
+// How a neighbour's vector reaches its lane: not by the lane streaming its own row.  Then one
+// load instruction touches 64 rows, and on a point set beyond about 2 GB the address
+// translations, not the bytes, bound the kernel (1M x 960 fp32: 2 TB/s; a micro-benchmark of
+// the pattern falls from 5 to 1.3 TB/s between 2 and 16 GB, while eight lanes per row keep
+// 6.2 TB/s).  Instead eight lanes read 128 consecutive bytes of one row (eight rows per
+// instruction, like the gathers of k_init and the join), the 64 x 128-byte step goes through
+// the wavefront's own LDS region (padded rows: conflict-free 16-byte accesses), and every lane
+// picks up its own row's 32 words.  The loads of the next step are in flight while the chain
+// runs.  No workgroup barriers: a wavefront only touches its own region, in program order.
+// Needs rows of whole, aligned 16-byte pieces; other shapes take k_finalize_scalar.
+//
+// ELEM 0: fp32 rows.  ELEM 2: fp16 rows, the fp64 recipe on the converted values.  ELEM 1: uint8
+// rows, the sum of squared differences is an integer below 2^32, evaluated exactly and rounded
+// once to fp32 -- what the fp64 recipe gives on these values.  dw = 32-bit words per row.
 // ------------------------------------------------------------------------------------------
-// ELEM 1 (uint8 rows of d bytes): the sum of squared differences is an integer below 2^32,
-// evaluated exactly and rounded once to fp32 -- what the fp64 recipe gives on these values.
-template <int METRIC, bool VEC, int ELEM>
+constexpr int FIN_CH = 32;                            // words per row and step
+constexpr int FIN_LD = FIN_CH + 4;                    // LDS row stride (words)
+template <int METRIC, int ELEM>
 __global__ void __launch_bounds__(256)
-k_finalize(const float* __restrict__ pts, int64_t n, int d, int K, int Kp, int k,
+k_finalize(const float* __restrict__ pts, int64_t n, int dw, int K, int Kp, int k,
            const u64* __restrict__ G, int32_t* __restrict__ ids_out, float* __restrict__ dists_out)
 {
+    static_assert(ELEM == 0 || METRIC == 0, "uint8 and fp16 rows: squared L2 only");
+    __shared__ __attribute__((aligned(16))) float stage[4][WAVE * FIN_LD];
+    const int lane = lane_id(), w = threadIdx.x >> 6;
+    const int sub = lane / Kp, i = lane & (Kp - 1);
+    const int64_t v = ((int64_t)blockIdx.x * 4 + w) * (WAVE / Kp) + sub;
+    const bool live = v < n && i < K;
+    const int64_t vv = v < n ? v : n - 1;
+    const u64 key = live ? G[vv * K + i] : EMPTY_KEY;
+    const int id = live ? key_id(key) : (int)vv;
+    float* st = stage[w];
+    const int g = lane >> 3, c = lane & 7;            // load role: row 8q + g, piece c of the step
+    // eight row pointers and eight pieces in flight, as named variables (one per load of a step)
+#define KNNG_REP8(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7)
+#define KNNG_FIN_DECL(q) const float* rp##q = pts + (int64_t)__shfl(id, 8 * q + g) * dw + 4 * c; float4 b##q;
+#define KNNG_FIN_LOAD(q) b##q = *reinterpret_cast<const float4*>(rp##q + off);
+#define KNNG_FIN_STORE(q) *reinterpret_cast<float4*>(st + (8 * q + g) * FIN_LD + 4 * c) = b##q;
+    KNNG_REP8(KNNG_FIN_DECL)
+    const float* __restrict__ a = pts + vv * dw;
+    // pieces past the end of a row are loaded from its last piece (never used: the chain stops at dw)
+    {
+        const int off = 4 * c < dw ? 0 : dw - 4 - 4 * c;
+        KNNG_REP8(KNNG_FIN_LOAD)
+    }
+    double acc = 0.0;
+    uint32_t acc_u = 0u;
+    for (int t = 0; t < dw; t += FIN_CH) {
+        KNNG_REP8(KNNG_FIN_STORE)
+        wave_lds_sync();
+        if (t + FIN_CH < dw) {                        // uniform
+            const int tn = t + FIN_CH;
+            const int off = tn + 4 * c < dw ? tn : dw - 4 - 4 * c;
+            KNNG_REP8(KNNG_FIN_LOAD)
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {                 // two halves of 16 words
+            if (t + 16 * h < dw) {                    // uniform
+                float4 av[4], bv[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int tt = t + 16 * h + 4 * j;
+                    bv[j] = *reinterpret_cast<const float4*>(st + lane * FIN_LD + 16 * h + 4 * j);
+                    av[j] = *reinterpret_cast<const float4*>(a + (tt < dw ? tt : 0));
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (t + 16 * h + 4 * j < dw) {    // uniform
+                        if constexpr (ELEM == 1) {
+                            acc_u += sqdiff16_u8(uint4{__float_as_uint(av[j].x), __float_as_uint(av[j].y), __float_as_uint(av[j].z), __float_as_uint(av[j].w)},
+                                                 uint4{__float_as_uint(bv[j].x), __float_as_uint(bv[j].y), __float_as_uint(bv[j].z), __float_as_uint(bv[j].w)});
+                        } else if constexpr (ELEM == 2) {
+                            const uint32_t x[4] = {__float_as_uint(av[j].x), __float_as_uint(av[j].y), __float_as_uint(av[j].z), __float_as_uint(av[j].w)};
+                            const uint32_t y[4] = {__float_as_uint(bv[j].x), __float_as_uint(bv[j].y), __float_as_uint(bv[j].z), __float_as_uint(bv[j].w)};
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                acc = exact_step<0>(acc, h_lo(x[e]), h_lo(y[e]));
+                                acc = exact_step<0>(acc, h_hi(x[e]), h_hi(y[e]));
+                            }
+                        } else {
+                            acc = exact_step<METRIC>(acc, av[j].x, bv[j].x);
+                            acc = exact_step<METRIC>(acc, av[j].y, bv[j].y);
+                            acc = exact_step<METRIC>(acc, av[j].z, bv[j].z);
+                            acc = exact_step<METRIC>(acc, av[j].w, bv[j].w);
+                        }
+                    }
+                }
+            }
+        }
+        wave_lds_sync();
+    }
+#undef KNNG_FIN_STORE
+#undef KNNG_FIN_LOAD
+#undef KNNG_FIN_DECL
+#undef KNNG_REP8
+    const float dist = ELEM == 1 ? (float)acc_u : exact_finish<METRIC>(acc);
+    const u64 fk = live ? pack_key(dist, id, 0) : EMPTY_KEY;
+    int rank = 0;
+    for (int j = 0; j < K; ++j) rank += ((u64)__shfl((unsigned long long)fk, sub * Kp + j) < fk) ? 1 : 0;
+    if (live && rank < k) {
+        ids_out[v * k + rank] = id;
+        dists_out[v * k + rank] = dist;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// k_finalize_scalar: the same for rows that are not made of aligned 16-byte pieces (fp32: any d;
+// uint8: d % 4 == 0; fp16: d % 2 == 0, rows 4-byte aligned).  Every lane walks its neighbour's
+// row and the point's own straight from global memory, one word at a time.  d = coordinates.
+// ------------------------------------------------------------------------------------------
+template <int METRIC, int ELEM>
+__global__ void __launch_bounds__(256)
+k_finalize_scalar(const float* __restrict__ pts, int64_t n, int d, int K, int Kp, int k,
+                  const u64* __restrict__ G, int32_t* __restrict__ ids_out, float* __restrict__ dists_out)
+{
+    static_assert(ELEM == 0 || METRIC == 0, "uint8 and fp16 rows: squared L2 only");
     const int lane = lane_id(), w = threadIdx.x >> 6;
     const int sub = lane / Kp, i = lane & (Kp - 1);
     const int64_t v = ((int64_t)blockIdx.x * 4 + w) * (WAVE / Kp) + sub;
@@ -992,92 +1099,26 @@ k_finalize(const float* __restrict__ pts, int64_t n, int d, int K, int Kp, int k
     const int id = live ? key_id(key) : (int)vv;
     float dist;
     if constexpr (ELEM == 1) {
-        const unsigned char* __restrict__ a = reinterpret_cast<const unsigned char*>(pts) + vv * d;
-        const unsigned char* __restrict__ b = reinterpret_cast<const unsigned char*>(pts) + (int64_t)id * d;
+        const uint32_t* __restrict__ a = reinterpret_cast<const uint32_t*>(pts) + vv * (int64_t)(d >> 2);
+        const uint32_t* __restrict__ b = reinterpret_cast<const uint32_t*>(pts) + (int64_t)id * (d >> 2);
         uint32_t acc = 0u;
-        if (VEC) {                                   // d % 16 == 0
-            int t = 0;
-            for (; t + 64 <= d; t += 64) {
-                uint4 av[4], bv[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    av[q] = *reinterpret_cast<const uint4*>(a + t + 16 * q);
-                    bv[q] = *reinterpret_cast<const uint4*>(b + t + 16 * q);
-                }
-#pragma unroll
-                for (int q = 0; q < 4; ++q) acc += sqdiff16_u8(av[q], bv[q]);
-            }
-            for (; t < d; t += 16)
-                acc += sqdiff16_u8(*reinterpret_cast<const uint4*>(a + t), *reinterpret_cast<const uint4*>(b + t));
-        } else {                                     // d % 4 == 0
-            for (int t = 0; t < d; t += 4)
-                acc += sqdiff4_u8(*reinterpret_cast<const uint32_t*>(a + t), *reinterpret_cast<const uint32_t*>(b + t));
-        }
+        for (int t = 0; t < (d >> 2); ++t) acc += sqdiff4_u8(a[t], b[t]);
         dist = (float)acc;
     } else if constexpr (ELEM == 2) {
-        // fp16 rows of d halves: the fp64 recipe on the converted values, in index order
         const uint32_t* __restrict__ a = reinterpret_cast<const uint32_t*>(pts) + vv * (int64_t)(d >> 1);
         const uint32_t* __restrict__ b = reinterpret_cast<const uint32_t*>(pts) + (int64_t)id * (d >> 1);
         double acc = 0.0;
-        auto word = [&](uint32_t x, uint32_t y) {
-            acc = exact_step<0>(acc, h_lo(x), h_lo(y));
-            acc = exact_step<0>(acc, h_hi(x), h_hi(y));
-        };
-        if (VEC) {                                   // d % 8 == 0
-            int t = 0;
-            for (; t + 16 <= (d >> 1); t += 16) {
-                uint4 av[4], bv[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    av[q] = *reinterpret_cast<const uint4*>(a + t + 4 * q);
-                    bv[q] = *reinterpret_cast<const uint4*>(b + t + 4 * q);
-                }
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    word(av[q].x, bv[q].x); word(av[q].y, bv[q].y); word(av[q].z, bv[q].z); word(av[q].w, bv[q].w);
-                }
-            }
-            for (; t < (d >> 1); t += 4) {
-                const uint4 av = *reinterpret_cast<const uint4*>(a + t), bv = *reinterpret_cast<const uint4*>(b + t);
-                word(av.x, bv.x); word(av.y, bv.y); word(av.z, bv.z); word(av.w, bv.w);
-            }
-        } else {                                     // d % 2 == 0
-            for (int t = 0; t < (d >> 1); ++t) word(a[t], b[t]);
+        for (int t = 0; t < (d >> 1); ++t) {
+            acc = exact_step<0>(acc, h_lo(a[t]), h_lo(b[t]));
+            acc = exact_step<0>(acc, h_hi(a[t]), h_hi(b[t]));
         }
         dist = exact_finish<0>(acc);
     } else {
-    const float* __restrict__ a = pts + vv * d;
-    const float* __restrict__ b = pts + (int64_t)id * d;
-    double acc = 0.0;
-    if (VEC) {
-        int t = 0;
-        for (; t + 16 <= d; t += 16) {
-            float4 av[4], bv[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                av[q] = *reinterpret_cast<const float4*>(a + t + 4 * q);
-                bv[q] = *reinterpret_cast<const float4*>(b + t + 4 * q);
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                acc = exact_step<METRIC>(acc, av[q].x, bv[q].x);
-                acc = exact_step<METRIC>(acc, av[q].y, bv[q].y);
-                acc = exact_step<METRIC>(acc, av[q].z, bv[q].z);
-                acc = exact_step<METRIC>(acc, av[q].w, bv[q].w);
-            }
-        }
-        for (; t < d; t += 4) {
-            const float4 av = *reinterpret_cast<const float4*>(a + t);
-            const float4 bv = *reinterpret_cast<const float4*>(b + t);
-            acc = exact_step<METRIC>(acc, av.x, bv.x);
-            acc = exact_step<METRIC>(acc, av.y, bv.y);
-            acc = exact_step<METRIC>(acc, av.z, bv.z);
-            acc = exact_step<METRIC>(acc, av.w, bv.w);
-        }
-    } else {
+        const float* __restrict__ a = pts + vv * d;
+        const float* __restrict__ b = pts + (int64_t)id * d;
+        double acc = 0.0;
         for (int t = 0; t < d; ++t) acc = exact_step<METRIC>(acc, a[t], b[t]);
-    }
-    dist = exact_finish<METRIC>(acc);
+        dist = exact_finish<METRIC>(acc);
     }
     const u64 fk = live ? pack_key(dist, id, 0) : EMPTY_KEY;
     int rank = 0;
@@ -1358,12 +1399,19 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
         while (Kp < bp.K) Kp <<= 1;
         const int64_t per_block = 4 * (WAVE / Kp);
         const dim3 grid((unsigned)((n + per_block - 1) / per_block)), block(256);
-#define KNNG_FIN(M, V, E) hipLaunchKernelGGL((k_finalize<M, V, E>), grid, block, 0, st, points_dev, n, d, bp.K, Kp, k, \
-                                             G, ids_out_dev, dists_out_dev)
-        if (elem == 1) { if (vec) KNNG_FIN(0, true, 1); else KNNG_FIN(0, false, 1); }
-        else if (elem == 2) { if (vec) KNNG_FIN(0, true, 2); else KNNG_FIN(0, false, 2); }
-        else if (metric == 0) { if (vec) KNNG_FIN(0, true, 0); else KNNG_FIN(0, false, 0); }
-        else { if (vec) KNNG_FIN(1, true, 0); else KNNG_FIN(1, false, 0); }
+        // rows of whole 16-byte pieces: the staged kernel (dw = 32-bit words per row)
+        const int dw = elem == 1 ? d / 4 : elem == 2 ? d / 2 : d;
+#define KNNG_FIN(M, E)                                                                                            \
+    do {                                                                                                          \
+        if (vec) hipLaunchKernelGGL((k_finalize<M, E>), grid, block, 0, st, points_dev, n, dw, bp.K, Kp, k, G,   \
+                                    ids_out_dev, dists_out_dev);                                                  \
+        else hipLaunchKernelGGL((k_finalize_scalar<M, E>), grid, block, 0, st, points_dev, n, d, bp.K, Kp, k, G, \
+                                ids_out_dev, dists_out_dev);                                                      \
+    } while (0)
+        if (elem == 1) KNNG_FIN(0, 1);
+        else if (elem == 2) KNNG_FIN(0, 2);
+        else if (metric == 0) KNNG_FIN(0, 0);
+        else KNNG_FIN(1, 0);
 #undef KNNG_FIN
         HIPCHK(hipGetLastError());
     }
