@@ -1206,11 +1206,11 @@ static hipError_t launch_join_k(hipStream_t st, const JoinArgs& a)
     return hipGetLastError();
 }
 
-template <int METRIC, int S16, bool VEC, int ELEM = 0>
+template <int METRIC, int S16, bool VEC, int ELEM = 0, bool SPLIT = false>
 static hipError_t launch_join_w(hipStream_t st, const JoinArgs& a)
 {
     const int lds = 4 * WaveCfg<S16, ELEM>::WBYTES;
-    auto kern = k_join_wave<METRIC, S16, VEC, ELEM>;
+    auto kern = k_join_wave<METRIC, S16, VEC, ELEM, SPLIT>;
     static int blocks_per_cu = 0;            // per instantiation: resident workgroups per CU
     if (blocks_per_cu == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1228,6 +1228,10 @@ static hipError_t launch_join_w(hipStream_t st, const JoinArgs& a)
     return hipGetLastError();
 }
 
+#ifndef KNNG_SPLIT_MIN_D
+#define KNNG_SPLIT_MIN_D 256      // fp32 rows from this length on: bf16-split Gram pass in the wavefront join
+#endif
+
 // uint8 (ELEM 1) or fp16 (ELEM 2) rows, squared L2; a.d counts 32-bit words
 template <int ELEM>
 static hipError_t launch_join_compact(hipStream_t st, bool vec, int S16, const JoinArgs& a)
@@ -1242,6 +1246,10 @@ template <int METRIC>
 static hipError_t launch_join(hipStream_t st, bool vec, int S16, const JoinArgs& a)
 {
     // s <= 16: one wavefront per point; larger samples: one workgroup per point
+    // long fp32 rows: the Gram pass on the bf16 matrix instructions (two halves per value)
+    const bool split = vec && a.d >= KNNG_SPLIT_MIN_D;
+    if (S16 == 1 && split) return launch_join_w<METRIC, 1, true, 0, true>(st, a);
+    if (S16 == 2 && split) return launch_join_w<METRIC, 2, true, 0, true>(st, a);
     if (S16 == 1) return vec ? launch_join_w<METRIC, 1, true>(st, a) : launch_join_w<METRIC, 1, false>(st, a);
     if (S16 == 2) return vec ? launch_join_w<METRIC, 2, true>(st, a) : launch_join_w<METRIC, 2, false>(st, a);
 #define KNNG_JOIN_CASE(S, DSV)                                                      \

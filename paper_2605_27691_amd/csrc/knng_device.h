@@ -89,6 +89,7 @@ template <int METRIC> __device__ __forceinline__ float exact_finish(double acc)
 // fp16 rows: two halves per 32-bit word
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef short short4v __attribute__((ext_vector_type(4)));   // four bf16 bit patterns (operand of the 16x16x16 bf16 MFMA)
 // a - b on the two halves of each word (v_pk_add_f16)
 __device__ __forceinline__ uint32_t sub_h2(uint32_t a, uint32_t b)
 {

@@ -76,7 +76,19 @@ template <int S16, int ELEM = 0> struct WaveCfg {
 // in 168 registers, and the fp16 kernel spills 39 there).
 template <int S16, int ELEM> struct WaveOcc { static constexpr int V = (ELEM != 0 && S16 == 2) ? 2 : KNNG_WAVE_OCC; };
 
-template <int METRIC, int S16, bool VEC, int ELEM = 0>
+// Two bf16 halves of four fp32 values: hi = the upper 16 bits (truncation), lo = the upper 16 bits of
+// x - hi (that difference is exact in fp32).  hi + lo misses x by less than 2^-14 |x|.
+__device__ __forceinline__ void split_bf16(float4 x, short4v& hi, short4v& lo)
+{
+    const uint32_t b0 = __float_as_uint(x.x), b1 = __float_as_uint(x.y), b2 = __float_as_uint(x.z), b3 = __float_as_uint(x.w);
+    const float l0 = x.x - __uint_as_float(b0 & 0xffff0000u), l1 = x.y - __uint_as_float(b1 & 0xffff0000u);
+    const float l2 = x.z - __uint_as_float(b2 & 0xffff0000u), l3 = x.w - __uint_as_float(b3 & 0xffff0000u);
+    hi = __builtin_bit_cast(short4v, uint2{__builtin_amdgcn_perm(b1, b0, 0x07060302u), __builtin_amdgcn_perm(b3, b2, 0x07060302u)});
+    lo = __builtin_bit_cast(short4v, uint2{__builtin_amdgcn_perm(__float_as_uint(l1), __float_as_uint(l0), 0x07060302u),
+                                           __builtin_amdgcn_perm(__float_as_uint(l3), __float_as_uint(l2), 0x07060302u)});
+}
+
+template <int METRIC, int S16, bool VEC, int ELEM = 0, bool SPLIT = false>
 __global__ void __launch_bounds__(256)
 __attribute__((amdgpu_waves_per_eu(WaveOcc<S16, ELEM>::V, WaveOcc<S16, ELEM>::V)))
 k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
@@ -87,6 +99,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
 {
     // ELEM 1 / 2: pts points at uint8 / fp16 rows of 4 d bytes, d counts 32-bit words
     static_assert(ELEM == 0 || METRIC == 0, "uint8 and fp16 rows: squared L2 only");
+    static_assert(ELEM == 0 || !SPLIT, "the bf16 split is for fp32 rows");
     using Cfg = WaveCfg<S16, ELEM>;
     using accv = typename std::conditional<ELEM == 1, intx4, floatx4>::type;
     constexpr int NCOLS = Cfg::NCOLS, CT = Cfg::CT, DS = Cfg::DS, LD = Cfg::LD, LDD = Cfg::LDD,
@@ -246,7 +259,17 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                     else if (ELEM == 2) x = sub_h2x4(x, pv);
                     else { x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w; }
                     if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
-                    *reinterpret_cast<float4*>(xdst + RPW * i * LD) = x;
+                    if constexpr (SPLIT) {
+                        // a row of the slab: 16 words of hi halves (two coordinates each), then 16 of lo
+                        short4v hi, lo;
+                        split_bf16(x, hi, lo);
+                        float* xrow = X + (rsub + RPW * i) * LD;
+                        *reinterpret_cast<short4v*>(xrow + 2 * c4) = hi;
+                        *reinterpret_cast<short4v*>(xrow + DS / 2 + 2 * c4) = lo;
+                        __builtin_amdgcn_sched_barrier(0);      // one piece at a time: keeps the split's temporaries few
+                    } else {
+                        *reinterpret_cast<float4*>(xdst + RPW * i * LD) = x;
+                    }
                 }
             }
             if (ELEM == 1 && rsub == 0) {                       // the pivot's own row
@@ -323,6 +346,42 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
 #pragma unroll
                     for (int ct = S16; ct < CT; ++ct, ++q) {
                         if (ct < nct) acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x[ct], x[ct], acc[q], 0, 0, 0);
+                    }
+                }
+            } else if constexpr (SPLIT) {
+                // fp32 rows, long: the centred values sit in LDS as two bf16 halves (split when the
+                // slab is stored) and <a,b> is taken as hi.hi + hi.lo + lo.hi on
+                // v_mfma_f32_16x16x16_bf16 -- three instructions of 8 cycles where fp32 needs four
+                // of 32, for a relative error below 2^-13 of |a||b| in what the join compares
+                for (int kk = 0; kk < len16; kk += 16) {
+                    short4v xh[CT], xl[CT];
+#pragma unroll
+                    for (int t = 0; t < CT; ++t) {
+                        if (t < nct) {
+                            const float* xrow = X + (t * 16 + r16) * LD + (kk >> 1) + 2 * kq;
+                            xh[t] = *reinterpret_cast<const short4v*>(xrow);
+                            xl[t] = *reinterpret_cast<const short4v*>(xrow + DS / 2);
+                        }
+                    }
+                    int q = 0;
+#pragma unroll
+                    for (int rt = 0; rt < S16; ++rt) {
+#pragma unroll
+                        for (int ct = rt; ct < CT; ++ct, ++q) {
+                            if (ct < nct && (rt < nrt || rt == ct)) {
+                                acc[q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(xh[rt], xh[ct], acc[q], 0, 0, 0);
+                                acc[q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(xh[rt], xl[ct], acc[q], 0, 0, 0);
+                                acc[q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(xl[rt], xh[ct], acc[q], 0, 0, 0);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int ct = S16; ct < CT; ++ct, ++q) {
+                        if (ct < nct) {
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(xh[ct], xh[ct], acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(xh[ct], xl[ct], acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(xl[ct], xh[ct], acc[q], 0, 0, 0);
+                        }
                     }
                 }
             } else {
