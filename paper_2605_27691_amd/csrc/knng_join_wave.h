@@ -44,6 +44,13 @@
 // operand read, and everything after it is the fp32 kernel's.  The centring rounds to fp16, so
 // the distances the join compares carry a relative error of about 1e-3: search-time precision
 // only, what is written to the caller is recomputed exactly from the fp16 values.
+//
+// SPLIT (fp32 rows of 256 coordinates or more, where the fp32 matrix instruction is the busiest
+// unit of the kernel): the centred values are split into two bf16 halves when the slab is stored
+// (a slab row = 16 words of hi halves, then 16 of lo halves: the same bytes), and the Gram pass
+// takes <a,b> as hi.hi + hi.lo + lo.hi on v_mfma_f32_16x16x16_bf16 -- three instructions of 8
+// cycles where fp32 needs four of 32.  The products miss <a,b> by less than 2^-13 |a||b| of the
+// centred vectors; like the fp16 kernel's rounding this only touches the ranking of candidates.
 #pragma once
 
 namespace knng {

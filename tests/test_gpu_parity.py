@@ -187,6 +187,28 @@ def test_build_other_shapes_and_metrics(idx, n, kb, rho):
     _check_build(x, k, w.metric, ids, dists, exact, min_recall=0.95)
 
 
+@pytest.mark.parametrize("n,d,k,kb,rho,metric", [
+    (4000, 256, 16, 16, 0.5, 0),       # the shortest rows that take it, samples of 8 (32 member slots)
+    (3000, 260, 16, 32, 0.5, 0),       # a ragged last slab (4 coordinates)
+    (3000, 512, 32, 32, 0.5, 1),       # inner product on unit rows
+    (2500, 1000, 10, 24, 0.67, 0),     # 31.25 slabs
+    (3000, 258, 8, 16, 0.5, 0),        # d % 4 != 0: stays on the fp32 matrix instruction
+])
+def test_build_long_fp32_rows_bf16_split_gram(n, d, k, kb, rho, metric):
+    # rows of 256 coordinates or more: the join compares distances from bf16-split products; what is
+    # written is still the exact recipe (checked at tolerance 0) and the recall bar is the same
+    # points near an 8-dimensional subspace (isotropic noise in hundreds of dimensions is beyond
+    # NN-Descent at these list lengths: the CPU reference stops at 0.93 there)
+    rng = np.random.default_rng(d + kb)
+    a = rng.standard_normal((8, d))
+    x = (rng.standard_normal((n, 8)) @ a + 0.05 * rng.standard_normal((n, d))).astype(np.float32)
+    if metric == 1:
+        x = (x / np.linalg.norm(x.astype(np.float64), axis=1, keepdims=True)).astype(np.float32)
+    exact = oracle.brute_knn(x, k, metric)
+    ids, dists, _ = knng.knng_build_knn_graph(_gpu(x), k, metric, k_build=kb, rho=rho, seed=4)
+    _check_build(x, k, metric, ids, dists, exact, min_recall=0.95)
+
+
 def test_build_odd_dimension_uses_the_scalar_path():
     rng = np.random.default_rng(9)
     x = rng.standard_normal((3000, 13)).astype(np.float32)
