@@ -47,7 +47,8 @@
 //
 // SPLIT (fp32 rows of 256 coordinates or more, where the fp32 matrix instruction is the busiest
 // unit of the kernel): the centred values are split into two bf16 halves when the slab is stored
-// (a slab row = 16 words of hi halves, then 16 of lo halves: the same bytes), and the Gram pass
+// (a 16-byte piece = two words of hi halves, then two of lo halves: the same bytes, the same LDS
+// addresses and bank pattern as the fp32 slab), and the Gram pass
 // takes <a,b> as hi.hi + hi.lo + lo.hi on v_mfma_f32_16x16x16_bf16 -- three instructions of 8
 // cycles where fp32 needs four of 32.  The products miss <a,b> by less than 2^-13 |a||b| of the
 // centred vectors; like the fp16 kernel's rounding this only touches the ranking of candidates.
@@ -267,13 +268,11 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                     else { x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w; }
                     if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
                     if constexpr (SPLIT) {
-                        // a row of the slab: 16 words of hi halves (two coordinates each), then 16 of lo
+                        // the piece keeps its place: two words of hi halves, then two of lo halves
                         short4v hi, lo;
                         split_bf16(x, hi, lo);
-                        float* xrow = X + (rsub + RPW * i) * LD;
-                        *reinterpret_cast<short4v*>(xrow + 2 * c4) = hi;
-                        *reinterpret_cast<short4v*>(xrow + DS / 2 + 2 * c4) = lo;
-                        __builtin_amdgcn_sched_barrier(0);      // one piece at a time: keeps the split's temporaries few
+                        const uint2 h2 = __builtin_bit_cast(uint2, hi), l2 = __builtin_bit_cast(uint2, lo);
+                        *reinterpret_cast<uint4*>(xdst + RPW * i * LD) = uint4{h2.x, h2.y, l2.x, l2.y};
                     } else {
                         *reinterpret_cast<float4*>(xdst + RPW * i * LD) = x;
                     }
@@ -365,9 +364,9 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
 #pragma unroll
                     for (int t = 0; t < CT; ++t) {
                         if (t < nct) {
-                            const float* xrow = X + (t * 16 + r16) * LD + (kk >> 1) + 2 * kq;
-                            xh[t] = *reinterpret_cast<const short4v*>(xrow);
-                            xl[t] = *reinterpret_cast<const short4v*>(xrow + DS / 2);
+                            const uint4 p = *reinterpret_cast<const uint4*>(X + (t * 16 + r16) * LD + 4 * kq + kk);
+                            xh[t] = __builtin_bit_cast(short4v, uint2{p.x, p.y});
+                            xl[t] = __builtin_bit_cast(short4v, uint2{p.z, p.w});
                         }
                     }
                     int q = 0;
