@@ -158,8 +158,8 @@ int knng_build_knn_graph_f16(const uint16_t *points_dev, int64_t n, int32_t d, i
 uint64_t knng_brute_workspace_bytes(int64_t n, int32_t d, int32_t k, int64_t nq);
 
 /*
- * Exact k-NN rows by brute force (Sec. 2.1: the exact kNNG recall is measured
- * against; Sec. 5.3.1: ground truth "computed by a brute-force method").
+ * Exact k-NN rows by brute force (Sec. 2.1: the exact graph recall is measured
+ * against; Sec. 5.3.1: the ground truth of the single-GPU experiments).
  *
  * For query q the source point is r = query_rows_dev ? query_rows_dev[q] : q;
  * every j != r is scored and the k smallest under (fp32 distance, id) are
@@ -280,7 +280,9 @@ int knng_optimize_graph(const int32_t *ids_dev, int64_t n, int32_t k, int32_t d_
  * [nq][n_starts] int32: device, read-only.  ids_out_dev [nq][k_s] int32,
  * dists_out_dev [nq][k_s] fp32: device, written in full.  iters_out_dev [nq] int32
  * and evals_out_dev [nq] int32 (optional, NULL to skip): iterations performed and
- * distances evaluated per query.
+ * distances evaluated per query.  A row (or the start ids) is offered as one batch:
+ * the ids of the batch that are valid, distinct and not in the list before the batch
+ * are evaluated, which is never more than offering them one at a time evaluates.
  * 1 <= k_s <= itopk <= KNNG_MAX_K; deg, n_starts, width in [1, KNNG_MAX_K];
  * max_iters >= 0; d <= 8192; nq = 0 is a no-op.  Needs no workspace.
  * Errors: KNNG_EINVAL, KNNG_EHIP.

@@ -36,6 +36,9 @@ def lib():
         L.oracle_nn_descent.restype = ctypes.c_int
         L.oracle_nn_descent.argtypes = [P, c_i64, c_i32, c_i32, c_i32, c_i32, c_f64, c_f64,
                                         c_i32, c_i32, c_u64, P, P, P]
+        L.oracle_nn_descent_trace.restype = ctypes.c_int
+        L.oracle_nn_descent_trace.argtypes = [P, c_i64, c_i32, c_i32, c_i32, c_i32, c_f64, c_f64,
+                                              c_i32, c_i32, c_u64, P, P, P, P, P, P, P, P, P, P]
         L.oracle_merge_rows.restype = ctypes.c_int
         L.oracle_merge_rows.argtypes = [P, P, c_i32, P, P, c_i32, c_i64, c_i32, P, P]
         L.oracle_optimize_graph.restype = ctypes.c_int
@@ -219,3 +222,49 @@ def nn_descent(points, k, metric=L2SQ, k_build=None, rho=0.5, delta=1e-4, max_it
     it = int(stats[0])
     return ids, dists, {"iterations": it, "distance_evals": int(stats[1]),
                         "dropped": int(stats[2]), "updates": stats[3:3 + it].tolist()}
+
+
+def nn_descent_trace(points, metric=L2SQ, k_build=8, rho=0.5, max_iters=1, cand_cap=0, seed=0):
+    """The reference NN-Descent run for exactly max_iters iterations (no stop rule), with the
+    lists of its last iteration written out.  -> dict: rows [n][K] ids, dists [n][K], flags
+    [n][K] (new-flags of the final rows), s, distance_evals, updates, and for the last iteration
+    fwd_new / fwd_old / rev_new / rev_old / NEW / OLD as lists of Python lists per point."""
+    x = _f32(points)
+    n, d = x.shape
+    K = k_build
+    smax = K                                               # room for any reading of the sample size
+    ids = np.empty((n, K), dtype=np.int32)
+    dists = np.empty((n, K), dtype=np.float32)
+    stats = np.zeros(3 + max(max_iters, 1), dtype=np.int64)
+    # the C side lays the traces out with its own s; find it from the counts it reports
+    fwd = np.full((2, n, smax), -1, np.int32)
+    rev = np.full((2, n, smax), -1, np.int32)
+    cnt = np.zeros((n, 4), np.int32)
+    full = np.full((2, n, 2 * smax), -1, np.int32)
+    fcnt = np.zeros((n, 2), np.int32)
+    flags = np.zeros((n, K), np.uint8)
+    rows = np.empty((n, K), np.int32)
+    rc = lib().oracle_nn_descent_trace(_p(x), n, d, K, metric, K, rho, 0.0, max_iters, cand_cap, seed,
+                                       _p(ids), _p(dists), _p(stats), _p(fwd), _p(rev), _p(cnt),
+                                       _p(full), _p(fcnt), _p(flags), _p(rows))
+    if rc != 0:
+        raise ValueError(f"oracle_nn_descent_trace failed (rc={rc})")
+    return {"ids": rows, "dists": dists, "flags": flags.astype(bool), "cnt": cnt, "fcnt": fcnt,
+            "raw_fwd": fwd.reshape(-1), "raw_rev": rev.reshape(-1), "raw_full": full.reshape(-1),
+            "distance_evals": int(stats[1]), "updates": stats[3:3 + int(stats[0])].tolist(),
+            "iterations": int(stats[0])}
+
+
+def trace_lists(tr, n, s):
+    """Unpack the flat trace buffers of nn_descent_trace for sample size s.
+    -> dict of lists of lists: fwd_new, fwd_old, rev_new, rev_old, NEW, OLD."""
+    cnt, fcnt = tr["cnt"], tr["fcnt"]
+    f = tr["raw_fwd"][:2 * n * s].reshape(2, n, s)
+    r = tr["raw_rev"][:2 * n * s].reshape(2, n, s)
+    u = tr["raw_full"][:2 * n * 2 * s].reshape(2, n, 2 * s)
+    return {"fwd_new": [f[0, v, :cnt[v, 0]].tolist() for v in range(n)],
+            "fwd_old": [f[1, v, :cnt[v, 1]].tolist() for v in range(n)],
+            "rev_new": [r[0, v, :cnt[v, 2]].tolist() for v in range(n)],
+            "rev_old": [r[1, v, :cnt[v, 3]].tolist() for v in range(n)],
+            "NEW": [u[0, v, :fcnt[v, 0]].tolist() for v in range(n)],
+            "OLD": [u[1, v, :fcnt[v, 1]].tolist() for v in range(n)]}

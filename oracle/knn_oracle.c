@@ -89,8 +89,9 @@ static int key_less(float da, int32_t ia, float db, int32_t ib)
 }
 
 /* ------------------------------------------------------------------------ */
-/* Exact k-NN graph (Sec. 2.1: "the exact kNNG computed by brute force";     */
-/* exactly k neighbours per source point).  For query row r (= query_rows[q] */
+/* Exact k-NN graph (Sec. 2.1: the graph recall is measured against, found   */
+/* by scoring every pair; k neighbours per source point, no more, no fewer). */
+/* For query row r (= query_rows[q]                                          */
 /* or q when query_rows is NULL) every j != r is scored with sigma and the k */
 /* smallest under (fp32 dist, id) are written in ascending order.            */
 /* The only parallelism is one query row per OpenMP iteration.               */
@@ -353,11 +354,25 @@ static void append_unique(int32_t *dst, int32_t *cnt, int32_t id)
  * stats (optional, int64[3 + max_iters]): [0] iterations run, [1] distance
  * evaluations, [2] candidates dropped by full lists, [3+i] accepted updates
  * of iteration i.  Returns 0, -1 on bad arguments, -2 on allocation failure.
+ *
+ * oracle_nn_descent_trace is the same function with the intermediate lists of the
+ * LAST iteration it ran written out, so that tests can check steps 2 and 3 against
+ * their definitions from outside (no arithmetic differs).  Every pointer may be
+ * NULL.  With s = the sample size and the last iteration's lists:
+ *   tr_fwd  int32 [2][n][s]   forward new sample, forward old sample     (step 2)
+ *   tr_rev  int32 [2][n][s]   reverse new sample, reverse old sample     (step 3)
+ *   tr_cnt  int32 [n][4]      their lengths: fwd new, fwd old, rev new, rev old
+ *   tr_full int32 [2][n][2s]  NEW[v], OLD[v] as the neighbour check uses them
+ *   tr_fcnt int32 [n][2]      |NEW[v]|, |OLD[v]|
+ *   flags_out uint8 [n][K]    the new-flags of the final rows (all K entries)
+ *   rows_out int32 [n][K]     the ids of the final rows (all K entries)
  */
-int oracle_nn_descent(const float *points, int64_t n, int32_t d, int32_t k, int32_t metric,
-                      int32_t K, double rho, double delta, int32_t max_iters,
-                      int32_t cand_cap, uint64_t seed,
-                      int32_t *ids_out, float *dists_out, int64_t *stats)
+int oracle_nn_descent_trace(const float *points, int64_t n, int32_t d, int32_t k, int32_t metric,
+                            int32_t K, double rho, double delta, int32_t max_iters,
+                            int32_t cand_cap, uint64_t seed,
+                            int32_t *ids_out, float *dists_out, int64_t *stats,
+                            int32_t *tr_fwd, int32_t *tr_rev, int32_t *tr_cnt,
+                            int32_t *tr_full, int32_t *tr_fcnt, uint8_t *flags_out, int32_t *rows_out)
 {
     if (!points || !ids_out || !dists_out || n < 2 || d < 1 || k < 1 || K < k ||
         (int64_t)K > n - 1 || metric < 0 || metric > 2 || !(rho > 0.0) || rho > 1.0 ||
@@ -488,6 +503,8 @@ int oracle_nn_descent(const float *points, int64_t n, int32_t d, int32_t k, int3
                 int32_t rc = (int32_t)(rev_off[u + 1] - rev_off[u]);
                 int32_t *src = rev_src + rev_off[u];
                 int32_t m = choose_uniform(src, rc, s, &r);
+                if (tr_rev) memcpy(tr_rev + ((int64_t)pass * n + u) * s, src, sizeof(int32_t) * (size_t)m);
+                if (tr_cnt) tr_cnt[u * 4 + 2 + pass] = m;
                 for (int32_t i = 0; i < m; ++i) {
                     int32_t id = src[i];
                     int skip = 0;
@@ -499,6 +516,16 @@ int oracle_nn_descent(const float *points, int64_t n, int32_t d, int32_t k, int3
                 FCNT[u] = c;
             }
         }
+        if (tr_fwd) {
+            memcpy(tr_fwd, newf, sizeof(int32_t) * (size_t)n * s);
+            memcpy(tr_fwd + n * s, oldf, sizeof(int32_t) * (size_t)n * s);
+        }
+        if (tr_cnt) for (int64_t v = 0; v < n; ++v) { tr_cnt[v * 4] = newf_cnt[v]; tr_cnt[v * 4 + 1] = oldf_cnt[v]; }
+        if (tr_full) {
+            memcpy(tr_full, NEW, sizeof(int32_t) * (size_t)n * 2 * s);
+            memcpy(tr_full + n * 2 * s, OLD, sizeof(int32_t) * (size_t)n * 2 * s);
+        }
+        if (tr_fcnt) for (int64_t v = 0; v < n; ++v) { tr_fcnt[v * 2] = NEW_cnt[v]; tr_fcnt[v * 2 + 1] = OLD_cnt[v]; }
         /* ---- step 4: neighbour check, offers into candidate lists ---- */
         for (int64_t v0 = 0; v0 < n; v0 += BATCH) {
             int64_t v1 = v0 + BATCH < n ? v0 + BATCH : n;
@@ -534,6 +561,8 @@ int oracle_nn_descent(const float *points, int64_t n, int32_t d, int32_t k, int3
         memcpy(ids_out + v * k, g.ids + v * K, sizeof(int32_t) * (size_t)k);
         memcpy(dists_out + v * k, g.dist + v * K, sizeof(float) * (size_t)k);
     }
+    if (flags_out) memcpy(flags_out, g.isnew, (size_t)n * K);
+    if (rows_out) memcpy(rows_out, g.ids, sizeof(int32_t) * (size_t)n * K);
     for (int64_t a = 0; a < n; ++a) free(g.cand[a].v);
     free(g.cand); free(g.ids); free(g.dist); free(g.isnew);
     free(newf); free(oldf); free(newf_cnt); free(oldf_cnt);
@@ -542,12 +571,21 @@ int oracle_nn_descent(const float *points, int64_t n, int32_t d, int32_t k, int3
     return 0;
 }
 
+int oracle_nn_descent(const float *points, int64_t n, int32_t d, int32_t k, int32_t metric,
+                      int32_t K, double rho, double delta, int32_t max_iters,
+                      int32_t cand_cap, uint64_t seed,
+                      int32_t *ids_out, float *dists_out, int64_t *stats)
+{
+    return oracle_nn_descent_trace(points, n, d, k, metric, K, rho, delta, max_iters, cand_cap, seed,
+                                   ids_out, dists_out, stats, NULL, NULL, NULL, NULL, NULL, NULL, NULL);
+}
+
 /* ------------------------------------------------------------------------ */
 /* Update of a k-NN graph's rows with neighbour candidates found elsewhere   */
-/* (Sec. 4.3 step 4: a rank "updates G_{i->i} accordingly" with the k        */
-/* candidates per point found on a remote graph; Sec. 4.4: G_{0->0} becomes  */
-/* G_{0->0:1} "using R_{0->1}").  R has the layout of a graph: ids and       */
-/* distances per query point (Sec. 4.4).                                     */
+/* (Sec. 4.3 step 4: a rank brings its own graph up to date with the k       */
+/* candidates per point it found on a remote graph; Sec. 4.4: the search     */
+/* result R_{0->1} turns G_{0->0} into G_{0->0:1}).  R has the layout of a   */
+/* graph: ids and distances per query point (Sec. 4.4).                      */
 /* Row i of the result = the k_out smallest entries under (distance, id) of  */
 /* row i of A and row i of B taken together, one entry per id (of several    */
 /* entries with one id the smallest stays); entries with id < 0 are padding  */
@@ -722,9 +760,10 @@ int oracle_optimize_graph(const int32_t *ids, int64_t n, int32_t k, int32_t d_ou
 /*   expanded, then for each of them in list order offer its graph row in    */
 /*   row order.                                                              */
 /* Result: the first k_s entries (padded with id -1 and distance +inf).      */
-/* iters_out, evals_out (optional): iterations performed per query, and the   */
-/* distances a batch-wise evaluation needs: per batch (the start ids; one     */
-/* graph row) the valid, distinct ids that are not in the list before it.     */
+/* iters_out, evals_out (optional): iterations performed per query, and how   */
+/* often "offer x" evaluated sigma for it.  (An implementation that offers a   */
+/* whole row at once may skip a repeat inside the row, or an id the row itself */
+/* has just pushed out of the list: it evaluates at most this many.)           */
 /* Returns 0, or -1 on bad arguments.                                        */
 /* ------------------------------------------------------------------------ */
 int oracle_graph_search(const float *points, int64_t n, int32_t d, int32_t metric,
@@ -754,6 +793,7 @@ int oracle_graph_search(const float *points, int64_t n, int32_t d, int32_t metri
             for (int32_t t_ = 0; t_ < len; ++t_) in_ |= lid[t_] == x_;                          \
             if (in_) break;                                                                     \
             const float dx_ = oracle_distance(qv, points + (int64_t)x_ * d, d, metric);         \
+            ++evals;                                                                            \
             int32_t pos_ = len;                                                                 \
             while (pos_ > 0 && key_less(dx_, x_, ld[pos_ - 1], lid[pos_ - 1])) --pos_;          \
             if (pos_ >= L) break;                                                               \
@@ -762,28 +802,16 @@ int oracle_graph_search(const float *points, int64_t n, int32_t d, int32_t metri
             lid[pos_] = x_; ld[pos_] = dx_; lex[pos_] = 0;                                      \
             if (len < L) ++len;                                                                 \
         } while (0)
-#define ORACLE_COUNT(row, cnt)                                                              \
-        for (int32_t a_ = 0; a_ < (cnt); ++a_) {                                                \
-            const int32_t x_ = (row)[a_];                                                       \
-            int skip_ = x_ < 0 || (int64_t)x_ >= n;                                             \
-            for (int32_t b_ = 0; b_ < a_ && !skip_; ++b_) skip_ = (row)[b_] == x_;              \
-            for (int32_t t_ = 0; t_ < len && !skip_; ++t_) skip_ = lid[t_] == x_;               \
-            evals += !skip_;                                                                    \
-        }
-        ORACLE_COUNT(starts + q * n_starts, n_starts)
         for (int32_t t = 0; t < n_starts; ++t) ORACLE_OFFER(starts[q * n_starts + t]);
         for (; iters < max_iters; ++iters) {
             int32_t np = 0;
             for (int32_t t = 0; t < len && np < width; ++t)
                 if (!lex[t]) { lex[t] = 1; par[np++] = lid[t]; }
             if (np == 0) break;
-            for (int32_t a = 0; a < np; ++a) {
-                ORACLE_COUNT(graph + (int64_t)par[a] * deg, deg)
+            for (int32_t a = 0; a < np; ++a)
                 for (int32_t j = 0; j < deg; ++j) ORACLE_OFFER(graph[(int64_t)par[a] * deg + j]);
-            }
         }
 #undef ORACLE_OFFER
-#undef ORACLE_COUNT
         for (int32_t t = 0; t < k_s; ++t) {
             ids_out[q * k_s + t] = t < len ? lid[t] : -1;
             dists_out[q * k_s + t] = t < len ? ld[t] : INFINITY;

@@ -30,7 +30,10 @@ def _assert_same(a, b):
     assert np.array_equal(a[0], b[0])
     assert np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
     assert np.array_equal(a[2], b[2])
-    assert np.array_equal(a[3], b[3])                          # the same distances were evaluated
+    # distances evaluated: the kernel offers a row at once and so may skip a repeat inside the
+    # row or an id the row itself has just pushed out, which offering one id at a time evaluates
+    # again; it never evaluates more, and every listed id was evaluated at least once
+    assert np.all(a[3] <= b[3]) and np.all(a[3] >= (a[0] >= 0).sum(1))
 
 
 def _data(n, d, nq, metric, seed):

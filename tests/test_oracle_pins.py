@@ -422,6 +422,140 @@ def test_nn_descent_fixed_size_candidate_lists_drop():
     assert rec[4] <= rec[64] + 0.01 and rec[64] >= rec[0] - 0.05
 
 
+# ---------------------------------------------------- NN-Descent, steps 2-5 restated in Python
+def _sample_size(rho, K):
+    """s = ceil(rho K), in exact rational arithmetic (Sec. 3.1: rho is the share of the
+    neighbours a point looks at; rho = 1 looks at all K)."""
+    from fractions import Fraction
+    import math
+    return max(1, min(K, math.ceil(Fraction(rho).limit_denominator(1000) * K)))
+
+
+def _int_points(n, d, seed):
+    # small integers: every distance is an exact integer in any arithmetic, with many ties
+    return np.random.default_rng(seed).integers(0, 12, (n, d)).astype(np.float32)
+
+
+def _int_dist(x, a, b):
+    return int(((x[a].astype(np.int64) - x[b].astype(np.int64)) ** 2).sum())
+
+
+def _check_one_iteration(x, K, rho, before, after, lists):
+    """`before`: rows and flags going into an iteration, `lists`: the samples the reference drew
+    in it, `after`: rows and flags coming out.  Checks steps 2 to 5 of Sec. 3.1 / 3.1.1 as plain
+    statements about sets and returns the number of distances the neighbour check must evaluate."""
+    n = x.shape[0]
+    s = _sample_size(rho, K)
+    rows0 = [r.tolist() for r in before["ids"]]
+    flag0 = [f.tolist() for f in before["flags"]]
+    fn, fo, rn, ro = lists["fwd_new"], lists["fwd_old"], lists["rev_new"], lists["rev_old"]
+    for v in range(n):
+        flagged = {u for u, f in zip(rows0[v], flag0[v]) if f}
+        plain = set(rows0[v]) - flagged
+        # step 2: a subset, without repeats, of the right kind and of size min(s, available)
+        assert len(set(fn[v])) == len(fn[v]) == min(s, len(flagged)) and set(fn[v]) <= flagged
+        assert len(set(fo[v])) == len(fo[v]) == min(s, len(plain)) and set(fo[v]) <= plain
+    for kind, (fwd, rev) in enumerate(((fn, rn), (fo, ro))):
+        holders = [[] for _ in range(n)]                  # who holds u in its forward sample
+        for v in range(n):
+            for u in fwd[v]:
+                holders[u].append(v)
+        for u in range(n):
+            # step 3: a subset of the points that sampled u, of size min(s, their number)
+            assert len(set(rev[u])) == len(rev[u]) == min(s, len(holders[u])), (kind, u)
+            assert set(rev[u]) <= set(holders[u])
+    evals = 0
+    offers = [dict() for _ in range(n)]
+    worst = [(_int_dist(x, v, rows0[v][K - 1]), rows0[v][K - 1]) for v in range(n)]
+    for v in range(n):
+        NEW, OLD = lists["NEW"][v], lists["OLD"][v]
+        # the lists the neighbour check uses: forward and reverse together, no repeats, and
+        # nothing in OLD that is also in NEW
+        assert len(set(NEW)) == len(NEW) and set(NEW) == set(fn[v]) | set(rn[v])
+        assert len(set(OLD)) == len(OLD) and set(OLD) == (set(fo[v]) | set(ro[v])) - set(NEW)
+        pairs = [(a, b) for i, a in enumerate(NEW) for b in NEW[i + 1:]] + [(a, b) for a in NEW for b in OLD]
+        evals += len(pairs)
+        for a, b in pairs:                                # step 4 (Sec. 3.1.1): gate on the farthest neighbour
+            l = _int_dist(x, a, b)
+            for p, q in ((a, b), (b, a)):
+                if (l, q) < worst[p]:
+                    offers[p][q] = l
+    rows1 = [r.tolist() for r in after["ids"]]
+    flag1 = [f.tolist() for f in after["flags"]]
+    accepted_min = 0
+    for v in range(n):
+        # step 5: with lists that never fill up, the row becomes the K smallest of its entries
+        # and its candidates, one entry per id, whatever order the candidates came in
+        pool = {u: _int_dist(x, v, u) for u in rows0[v]}
+        for u, l in offers[v].items():
+            pool.setdefault(u, l)
+        want = [u for _, u in sorted((l, u) for u, l in pool.items())[:K]]
+        assert rows1[v] == want, v
+        assert after["dists"][v].tolist() == [float(pool[u]) for u in want]
+        # flags: what entered is new; what stayed keeps its flag unless it was sampled (step 2)
+        was = dict(zip(rows0[v], flag0[v]))
+        for u, f in zip(rows1[v], flag1[v]):
+            assert f == ((u not in was) or (was[u] and u not in fn[v])), (v, u)
+        accepted_min += len(set(want) - set(rows0[v]))
+    return evals, accepted_min
+
+
+@pytest.mark.parametrize("rho,K", [(0.5, 7), (1.0, 6), (0.3, 10), (0.5, 8)])
+def test_nn_descent_sampling_reverse_lists_join_and_merge_follow_their_definitions(rho, K):
+    # Runs with the same seed share their history, so the run capped at t iterations is the
+    # state going into iteration t of the run capped at t + 1.
+    n, d = 60, 3
+    x = _int_points(n, d, 77 + K)
+    s = _sample_size(rho, K)
+    runs = [oracle.nn_descent_trace(x, k_build=K, rho=rho, max_iters=t, seed=11) for t in range(5)]
+    assert runs[0]["flags"].all() and runs[0]["distance_evals"] == n * K       # step 1
+    assert sum(oracle.check_graph(x, runs[0]["ids"], runs[0]["dists"], rel_tol=0.0).values()) == 0
+    for t in range(4):
+        lists = oracle.trace_lists(runs[t + 1], n, s)
+        evals, accepted_min = _check_one_iteration(x, K, rho, runs[t], runs[t + 1], lists)
+        assert runs[t + 1]["distance_evals"] - runs[t]["distance_evals"] == evals
+        assert runs[t + 1]["updates"][t] >= accepted_min
+        assert runs[t + 1]["updates"][:t] == runs[t]["updates"]
+
+
+def test_nn_descent_sample_size_rounds_up():
+    # rho K = 1.5.  Rounded down (s = 1) a point would join at most two members, one pair, so
+    # the first neighbour check could evaluate at most n distances; rounded up (s = 2) every
+    # point has its two forward members plus, almost always, somebody's reverse edge.
+    n, K = 200, 3
+    x = _int_points(n, 4, 5)
+    r0 = oracle.nn_descent_trace(x, k_build=K, rho=0.5, max_iters=0, seed=3)
+    r1 = oracle.nn_descent_trace(x, k_build=K, rho=0.5, max_iters=1, seed=3)
+    first = r1["distance_evals"] - r0["distance_evals"]
+    assert n < first <= n * 6                              # C(4, 2) pairs at most with s = 2
+    assert (r1["cnt"][:, 0] == 2).all()                    # every forward new sample has ceil(1.5) entries
+
+
+def test_nn_descent_samples_are_uniform():
+    # "chosen uniformly": over many seeds every flagged entry of a row is picked equally often
+    # (s of K = 2 of 6 at iteration 0), and so is every holder in a reverse sample
+    n, K, rho, trials = 30, 6, 1.0 / 3.0, 600
+    x = _int_points(n, 3, 9)
+    s = _sample_size(rho, K)
+    assert s == 2
+    hits = np.zeros(K)
+    rev_ratio = []
+    for seed in range(trials):
+        tr = oracle.nn_descent_trace(x, k_build=K, rho=rho, max_iters=1, seed=seed)
+        before = oracle.nn_descent_trace(x, k_build=K, rho=rho, max_iters=0, seed=seed)
+        lists = oracle.trace_lists(tr, n, s)
+        row = before["ids"][0].tolist()
+        for u in lists["fwd_new"][0]:
+            hits[row.index(u)] += 1
+        holders = [v for v in range(n) if 0 in lists["fwd_new"][v]]
+        if len(holders) > s:
+            rev_ratio.append(holders.index(lists["rev_new"][0][0]) / (len(holders) - 1))
+    # each position expected trials * s / K = 200 times; 5 sigma of a binomial is about 58
+    assert np.all(np.abs(hits - trials * s / K) < 60), hits
+    # the kept holder's place among the holders has no preference for early or late ones
+    assert len(rev_ratio) > 50 and 0.35 < float(np.mean(rev_ratio)) < 0.65
+
+
 # ------------------------------------------------------------------ merge_rows (Sec. 4.3 step 4, 4.4)
 def test_merge_rows_hand_example_padding_and_repeated_ids():
     ia = np.array([[4, 9, 2], [7, -1, -1]], np.int32)
