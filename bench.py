@@ -3,7 +3,11 @@
 
 A step is one whole build (`knng_build_knn_graph`: init, all sample/join/merge
 iterations until convergence, finalize) of the workload, with the points
-already resident in HBM.  Prints ONE JSON line:
+already resident in HBM.  The default workload is the largest of the benchmark's
+configurations that one GPU holds: number 5, 20,000,000 x 128 fp32, k = 32 (the
+other configurations: `--config 1..4`, or a workload's name).  Workloads are
+numbered as in the benchmark's own list, from 1; 6 is the connected set the graph
+search uses.  Prints ONE JSON line:
 
   value      build throughput, points/s (n / seconds per build)
   roofline   the local-join kernel: algorithmic bytes of its launches in the
@@ -53,6 +57,12 @@ SIG_BYTES = 32          # row signature read per gathered member
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("u8gmm1024_1m_d128_l2", "f32", 32, 0.5): 18.75e9,
                                      # profiles/k_join_wave_u8_config1_1m_d128.txt: 7.92 GB + 1.47 GB
                                      ("u8gmm1024_1m_d128_l2", "u8", 32, 0.5): 9.39e9}
+BF16_MFMA_PEAK_TFLOPS = 2500.0   # dense bf16 MFMA (the split Gram pass of long fp32 rows: three per product)
+SPLIT_MIN_D = 256                # fp32 rows from this length on take the bf16-split Gram pass (s <= 16)
+# Parameters a workload runs with when none are given: the cheapest set found that passes
+# recall@k >= 0.95 (the paper's knobs, Sec. 5.3.1: a build degree above k, then cut to k).
+# Everything else runs the paper's defaults K = k, rho = 0.5, delta = 1e-4.
+PARAM_SETS = {"gmm4096_20m_d128_l2": dict(k_build=64)}
 
 
 def parse():
@@ -60,11 +70,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=-1,
-                    help="workload index (0..5); default 1, for --op search 5 (a set whose graph a walk can cross)")
+    ap.add_argument("--config", default="",
+                    help="workload number (1..6, as the benchmark's configurations are listed) or name; default 5 "
+                         "(20M x 128), for --op optimize 2, for --op search 6 (a set whose graph a walk can cross)")
     ap.add_argument("--n", type=int, default=0, help="override the number of points")
     ap.add_argument("--elem", choices=("f32", "u8", "f16"), default="f32",
-                    help="point storage; u8 (knng_build_knn_graph_u8) needs a workload with 8-bit values: config 1; "
+                    help="point storage; u8 (knng_build_knn_graph_u8) needs a workload with 8-bit values: config 2; "
                          "f16 (knng_build_knn_graph_f16) rounds the workload's values to fp16 first (squared L2 only)")
     ap.add_argument("--op", choices=("build", "optimize", "search"), default="build")
     ap.add_argument("--itopk", type=int, default=64, help="--op search: list length")
@@ -76,9 +87,12 @@ def parse():
     ap.add_argument("--k-build", type=int, default=0)
     ap.add_argument("--rho", type=float, default=0.0)
     ap.add_argument("--delta", type=float, default=0.0)
+    ap.add_argument("--max-iters", type=int, default=0)
     ap.add_argument("--recall-rows", type=int, default=20000)
-    ap.add_argument("--oracle-rows", type=int, default=128)
-    ap.add_argument("--cpu-n", type=int, default=250000, help="points of the CPU-baseline sample (0 = skip)")
+    ap.add_argument("--oracle-rows", type=int, default=-1,
+                    help="sampled rows the CPU oracle repeats (default 128; 64 above 2M points)")
+    ap.add_argument("--cpu-n", type=int, default=-1,
+                    help="points of the CPU-baseline sample (0 = skip; default 250000, 60000 for K > 32)")
     ap.add_argument("--time-to-recall", type=int, default=1,
                     help="also search the smallest iteration cap that reaches recall@k >= 0.95 (0 = skip)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -193,7 +207,16 @@ def bench_search(a):
     # algorithmic bytes: every evaluated candidate's vector, every expanded row, per query its
     # vector, start ids and result
     alg_bytes = tot_evals * elem_bytes * d + tot_iters * a.width * 4 * d_out + nq * (elem_bytes * d + 4 * a.n_starts + 8 * k)
-    achieved = alg_bytes / (dev_ms * 1e-3) / 1e9
+    gathered_rate = alg_bytes / (dev_ms * 1e-3) / 1e9
+    # The whole-vector count above is not what the kernel must read: a lane stops reading a vector
+    # once its partial sum rules the candidate out.  The bytes it did read are the measured fetch
+    # (profiles/k_graph_search_manifold16_500k_d128.txt: FETCH_SIZE + WRITE_SIZE, default arguments
+    # only); the fraction is of that, and stays null where no measurement exists.  The searched half
+    # (256 MB) fits the Infinity Cache, which FETCH_SIZE does not tell from HBM: the kernel is bound by
+    # the memory system below the L2, of which HBM's 8 TB/s is the slower part.
+    traffic = 422.1e9 if (w.name, a.itopk, a.width, a.n_starts, d_out) == \
+        ("manifold16_1m_d128_l2", 64, 1, 32, 32) and not a.n and a.elem == "f32" else None
+    achieved = traffic / (dev_ms * 1e-3) / 1e9 if traffic else None
     # recall on a sample (outside the timed region): the exact neighbours, in the first half, of
     # sampled points of the second half
     ns = min(a.recall_rows, nq)
@@ -211,9 +234,11 @@ def bench_search(a):
     o_i, o_d, o_it, o_ev = oracle.graph_search(pa_h, gs_h, qb[:no].cpu().numpy(), starts[:no].cpu().numpy(), k, a.itopk,
                                                 a.width, a.max_search_iters, w.metric, want_evals=True)
     cpu_sec = time.perf_counter() - t1
+    # ids, distances and iteration counts are the oracle's bit for bit; the kernel offers a row as a
+    # batch and so evaluates at most as many distances as the oracle's one offer at a time
     same = bool(np.array_equal(o_i, ids[:no].cpu().numpy()) and
                 np.array_equal(o_d.view(np.uint32), dists[:no].cpu().numpy().view(np.uint32)) and
-                np.array_equal(o_it, iters[:no].cpu().numpy()) and np.array_equal(o_ev, evals[:no].cpu().numpy()))
+                np.array_equal(o_it, iters[:no].cpu().numpy()) and np.all(evals[:no].cpu().numpy() <= o_ev))
     res = {
         "metric": "graph search queries/sec (1 MI355X)",
         "value": nq / sec, "unit": "queries/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -226,14 +251,12 @@ def bench_search(a):
         "mean_iterations": tot_iters / nq, "mean_distance_evaluations": tot_evals / nq,
         "oracle_check": {"identical_to_oracle": same, "queries": no, "exact_rows_bit_exact": brute_ok},
         "roofline": {"kernel": "k_graph_search", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     # profiles/k_graph_search_manifold16_500k_d128.txt (FETCH_SIZE + WRITE_SIZE), default arguments
-                     "traffic": 422.1e9 if (w.name, a.itopk, a.width, a.n_starts, d_out) ==
-                                ("manifold16_1m_d128_l2", 64, 1, 32, 32) and not a.n and a.elem == "f32" else None,
-                     "note": "algorithmic bytes count every evaluated candidate's whole vector; lanes stop reading a "
-                             "vector whose partial sum already rules it out, and the searched half fits the Infinity "
-                             "Cache, so the rate can exceed what HBM alone delivers",
-                     "device_ms_per_call": dev_ms, "alg_bytes_per_call": alg_bytes},
+                     "unit": "GB/s", "frac": min(1.0, achieved / HBM_PEAK_GBS) if achieved else None,
+                     "traffic": traffic,
+                     "note": "achieved = measured L2-miss bytes (early abandon included) per call / time; the "
+                             "searched half fits the Infinity Cache, so part of it is not HBM traffic",
+                     "whole_vector_bytes_per_call": alg_bytes, "whole_vector_rate_gbs": gathered_rate,
+                     "device_ms_per_call": dev_ms},
         "cpu_baseline": {"value": no / cpu_sec, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
                          "sample": f"oracle_graph_search on the first {no} queries, {cpu_sec:.1f} s"},
     }
@@ -245,11 +268,15 @@ def bench_search(a):
 
 def main():
     a = parse()
-    if a.config < 0:
-        a.config = 5 if a.op == "search" else 1
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (nothing here uses a second GPU)",
               file=sys.stderr)
+        sys.exit(2)
+    from paper_2605_27691_amd import workloads as _wl
+    try:
+        a.config = _wl.number_of(a.config or {"search": 6, "optimize": 2, "build": 5}[a.op])
+    except ValueError as e:
+        print(f"bench.py: {e}", file=sys.stderr)
         sys.exit(2)
     if a.op == "optimize":
         return bench_optimize(a)
@@ -263,7 +290,16 @@ def main():
     torch.cuda.set_device(dev)
     x, w = workloads.make(a.config, n=(a.n or None), device=dev)
     n, d, k = w.n, w.d, w.k
-    kw = dict(k_build=a.k_build, rho=a.rho, delta=a.delta)
+    if not (a.k_build or a.rho or a.delta):                 # nothing given: the workload's own set
+        for key, val in PARAM_SETS.get(w.name, {}).items():
+            setattr(a, key, val)
+    kw = dict(k_build=a.k_build, rho=a.rho, delta=a.delta, max_iters=a.max_iters)
+    K = a.k_build or k
+    s_size = max(1, min(K, int(np.ceil(np.float32(a.rho or 0.5).astype(np.float64) * K))))
+    if a.oracle_rows < 0:
+        a.oracle_rows = 128 if n <= 2_000_000 else 64
+    if a.cpu_n < 0:
+        a.cpu_n = 250000 if K <= 32 else 60000
     p = knng.make_params(**kw)
     ws = torch.empty(knng.knng_build_workspace_bytes(n, d, k, p), dtype=torch.uint8, device=dev)
     ids = torch.empty((n, k), dtype=torch.int32, device=dev)
@@ -273,7 +309,7 @@ def main():
     if a.elem == "u8":
         xb = x.to(torch.uint8)
         if w.metric != 0 or not torch.equal(xb.float(), x):
-            print("bench.py: --elem u8 needs 8-bit point values and squared L2 (config 1)", file=sys.stderr)
+            print("bench.py: --elem u8 needs 8-bit point values and squared L2 (config 2)", file=sys.stderr)
             sys.exit(2)
         build, elem_bytes = knng.knng_build_knn_graph_u8, 1
     if a.elem == "f16":
@@ -323,17 +359,27 @@ def main():
     achieved = alg_bytes / (join_ms * 1e-3) / 1e9 if join_ms > 0 else 0.0
     pairs = sum(s["pairs"] for s in stats)                    # pairs the joins had to evaluate
     offers = sum(s["offers"] for s in stats)                  # atomic mins sent to candidate slots
+    kept = sum(s["cand_kept"] for s in stats)                 # slots the merges found occupied
     needed_tflops = 2.0 * d * pairs / (join_ms * 1e-3) / 1e12 if join_ms > 0 else 0.0
     last = stats[-1]
     # the join is priced against HBM (a gather) unless its Gram blocks are the larger fraction of
     # their own peak (large samples: s = 32 does four times the pair work per gathered byte)
     mfma_peak = {"u8": INT8_MFMA_PEAK_TOPS, "f16": FP16_MFMA_PEAK_TFLOPS, "f32": FP32_MFMA_PEAK_TFLOPS}[a.elem]
-    if needed_tflops / mfma_peak > achieved / HBM_PEAK_GBS:
-        bound = {"bound": "mfma", "achieved": needed_tflops, "peak": mfma_peak, "unit": "TFLOP/s",
-                 "frac": needed_tflops / mfma_peak, "hbm_gbs": achieved, "frac_of_hbm_peak": achieved / HBM_PEAK_GBS}
+    # long fp32 rows: the Gram pass runs on the bf16 matrix instruction, three instructions per product
+    split = a.elem == "f32" and d % 4 == 0 and d >= SPLIT_MIN_D and s_size <= 16
+    mfma_work = needed_tflops
+    if split:
+        mfma_peak, mfma_work = BF16_MFMA_PEAK_TFLOPS, 3.0 * needed_tflops
+    if mfma_work / mfma_peak > achieved / HBM_PEAK_GBS:
+        bound = {"bound": "mfma", "achieved": mfma_work, "peak": mfma_peak, "unit": "TFLOP/s",
+                 "frac": mfma_work / mfma_peak, "hbm_gbs": achieved, "frac_of_hbm_peak": achieved / HBM_PEAK_GBS}
     else:
         bound = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                  "frac": achieved / HBM_PEAK_GBS}
+
+    traffic = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((w.name, a.elem, K, a.rho or 0.5))
+    t_ratio = traffic / (alg_bytes / max(launches, 1)) if traffic else None
+    t_frac = traffic / (join_ms / max(launches, 1) * 1e-3) / 1e9 / HBM_PEAK_GBS if traffic and join_ms > 0 else None
 
     # ---- quality, outside the timed region
     rows_s = workloads.sample_rows(n, a.recall_rows)
@@ -349,21 +395,34 @@ def main():
     ttr = None
     if a.time_to_recall and recall >= 0.95:
         ids2, dists2 = torch.empty_like(ids), torch.empty_like(dists)
-        for cap in range(1, stats[-1]["iterations"] + 1):
+        kw2 = dict(kw)
+        kw2.pop("max_iters")
+
+        def probe(cap):
             best = None
-            for rep_ in range(2):
+            for rep_ in range(2 if n <= 2_000_000 else 1):
                 torch.cuda.synchronize()
                 t1 = time.perf_counter()
                 st2 = build(xb, k, w.metric, seed=0, workspace=ws, ids_out=ids2, dists_out=dists2,
-                            max_iters=cap, **kw)[2]
+                            max_iters=cap, **kw2)[2]
                 torch.cuda.synchronize()
                 el = time.perf_counter() - t1
                 best = el if best is None or el < best else best
             r2 = knng.knng_graph_recall(ids2[sel].contiguous(), dists2[sel].contiguous(), ex_i, ex_d, k, 0)
-            if r2 >= 0.95:
-                ttr = {"max_iters": cap, "iterations": st2["iterations"], "ms": best * 1e3,
-                       "points_per_s": n / best, "recall_at_k": r2}
-                break
+            return {"max_iters": cap, "iterations": st2["iterations"], "ms": best * 1e3,
+                    "points_per_s": n / best, "recall_at_k": r2}
+
+        # recall grows with the cap: bisect for the smallest cap that passes (the full run does)
+        lo, hi = 1, stats[-1]["iterations"]
+        while lo < hi:
+            mid = (lo + hi) // 2
+            got = probe(mid)
+            if got["recall_at_k"] >= 0.95:
+                hi, ttr = mid, got
+            else:
+                lo = mid + 1
+        if ttr is None or ttr["max_iters"] != lo:
+            ttr = probe(lo)
         del ids2, dists2
 
     # ---- the oracle: exact rows and row invariants on a few sampled rows, then the CPU baseline
@@ -378,10 +437,9 @@ def main():
     cpu = None
     if a.cpu_n > 0:
         xs, wsml = workloads.make(a.config, n=min(a.cpu_n, n))
-        Kb = a.k_build or k
         t1 = time.perf_counter()
-        _, _, ost = oracle.nn_descent(xs, k, w.metric, k_build=Kb, rho=(a.rho or 0.5),
-                                      delta=(a.delta or 1e-4), max_iters=100, seed=0)
+        _, _, ost = oracle.nn_descent(xs, k, w.metric, k_build=K, rho=(a.rho or 0.5),
+                                      delta=(a.delta or 1e-4), max_iters=(a.max_iters or 100), seed=0)
         cpu_sec = time.perf_counter() - t1
         cpu = {"value": wsml.n / cpu_sec, "unit": "points/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"oracle NN-Descent (fp64 distances) on {wsml.n} points of the same recipe "
@@ -391,9 +449,11 @@ def main():
         "metric": "kNN-graph build points/sec at recall@k>=0.95 (1 MI355X)",
         "value": n / sec, "unit": "points/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": {"f32": "f32", "u8": "i8 x i8 -> i32", "f16": "f16 x f16 -> f32"}[a.elem], "data": "synthetic",
+        "dtype": ("bf16x3-split -> f32" if split else
+                  {"f32": "f32", "u8": "i8 x i8 -> i32", "f16": "f16 x f16 -> f32"}[a.elem]), "data": "synthetic",
         "config": {"workload": w.name + ("" if a.elem == "f32" else "_stored_" + a.elem), "n": n, "d": d, "k": k, "metric": ["l2sq", "ip_unit"][w.metric],
-                   "k_build": a.k_build or k, "rho": a.rho or 0.5, "delta": a.delta or 1e-4,
+                   "config_number": a.config, "k_build": K, "rho": a.rho or 0.5, "sample_size": s_size,
+                   "delta": a.delta or 1e-4, "join_kernel": "k_join_wave" if s_size <= 16 else "k_join",
                    "iterations": last["iterations"], "converged": last["converged"]},
         "recall_at_k": recall, "recall_at_k_distance": recall_dist, "recall_rows": int(len(rows_s)),
         "time_to_recall": ttr,
@@ -401,13 +461,20 @@ def main():
                          "graph_violations": int(sum(viol.values()))},
         "kernel_ms": {"init": last["ms_init"], "sample": last["ms_sample"], "join": last["ms_join"],
                       "merge": last["ms_merge"], "finalize": last["ms_finalize"], "total": last["ms_total"]},
-        "roofline": {"kernel": "k_join", **bound,
-                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((w.name, a.elem, a.k_build or k, a.rho or 0.5)),
+        "roofline": {"kernel": "k_join_wave" if s_size <= 16 else "k_join", **bound,
+                     "traffic": traffic, "traffic_over_algorithmic": t_ratio, "hbm_frac_of_measured_traffic": t_frac,
                      "launches": launches, "avg_launch_ms": join_ms / max(launches, 1),
                      "alg_bytes_per_launch": alg_bytes / max(launches, 1),
                      "device_copy_gbs": copy_gbs, "frac_of_device_copy": achieved / copy_gbs,
-                     "needed_pair_tflops": needed_tflops, "frac_of_mfma_peak": needed_tflops / mfma_peak,
-                     "offers_per_launch": offers / max(launches, 1)},
+                     # gathered rows repeat (neighbours of neighbours share members): above the copy rate
+                     # part of them came from the L2 / Infinity Cache, not from HBM
+                     "cache_reuse": bool(achieved > copy_gbs),
+                     "needed_pair_tflops": needed_tflops, "mfma_peak_tflops": mfma_peak,
+                     "frac_of_mfma_peak": mfma_work / mfma_peak,
+                     "offers_per_launch": offers / max(launches, 1),
+                     # offers that did not survive in their slot (a repeat of the same neighbour or a
+                     # closer neighbour sharing the slot): upper bound of the candidates dropped
+                     "offers_not_kept_share": (offers - kept) / max(offers, 1)},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -44,7 +44,7 @@
 extern "C" {
 #endif
 
-#define KNNG_VERSION 1
+#define KNNG_VERSION 2
 
 enum {
     KNNG_OK = 0,
@@ -70,6 +70,13 @@ typedef struct knng_stats {
     uint64_t offers;           /* candidates offered to candidate lists (atomics), whole build */
     uint64_t pairs;            /* pairs the local joins had to evaluate (new x new unordered
                                   plus new x old per joined point), whole build      */
+    uint64_t cand_kept;        /* candidate slots the merges found occupied, whole build.
+                                  offers - cand_kept offers did not survive in their slot:
+                                  the same neighbour offered again by another join, or a
+                                  different neighbour that shares the slot and is closer --
+                                  the second kind is a dropped candidate (Sec. 3.1.1: a
+                                  fixed-size list may drop true neighbours), so the
+                                  difference bounds the drops from above                */
 } knng_stats_t;
 
 /*
@@ -86,7 +93,9 @@ typedef struct knng_params {
                                  default 1e-4; negative = never stop early (Sec. 3.1)          */
     int32_t max_iters;        /* default 100 (Sec. 5.3.1); negative = 0 iterations             */
     int32_t cand_cap;         /* slots of each point's fixed-size candidate list
-                                 (Sec. 3.1.1), 1..KNNG_MAX_K; default min(2K, KNNG_MAX_K)      */
+                                 (Sec. 3.1.1), 1..KNNG_MAX_K; default min(2K, KNNG_MAX_K): a
+                                 slot is a lane of the merging wavefront, so K = 64 has K
+                                 slots, not 2K                                                 */
     uint64_t seed;
     const int32_t *init_ids_dev; /* optional warm start [n][K] (device); entries that are out
                                  of range, self or repeated are replaced by random ids; NULL =
@@ -95,6 +104,10 @@ typedef struct knng_params {
     void *workspace_dev;      /* device scratch, >= knng_build_workspace_bytes(), 256-B aligned */
     uint64_t workspace_bytes;
     knng_stats_t *stats_host; /* optional                                                      */
+    void *pinned_host;        /* optional: 64 bytes of page-locked host memory (hipHostMalloc
+                                 class, 8-byte aligned) for the convergence counter the host
+                                 reads once per iteration; NULL = the call allocates and frees
+                                 its own, which costs a page-locked allocation per build       */
 } knng_params_t;
 
 /* Device scratch needed by knng_build_knn_graph for these sizes (0 on bad arguments). */
@@ -181,6 +194,7 @@ int knng_brute_knn(const float *points_dev, int64_t n, int32_t d, int32_t k, int
  *          share of the test neighbours with distance <= it.  Needs the two
  *          distance matrices.
  * test_* are [rows][k_test], ref_* are [rows][k_ref] (device); at_k <= both.
+ * A row holds each id at most once; an entry with id < 0 is padding and a miss.
  * The matrices a mode does not need may be NULL.  *recall_out_host (host)
  * receives hits / (rows * at_k).  Allocates and frees 8 bytes of device memory.
  */

@@ -148,8 +148,9 @@ int oracle_brute_knn_base(const float *points, int64_t n, int64_t n_base, int32_
 /*           the reference row.                                              */
 /*   mode 1 (Sec. 5.4.3): the reference row's at_k-th distance is a          */
 /*           threshold; fraction of test neighbours at distance <= it.       */
-/* Rows of both graphs are ascending.  Returns the recall, or -1.0 on bad    */
-/* arguments.                                                                */
+/* Rows of both graphs are ascending and hold each id at most once; an entry */
+/* with id < 0 is padding (a row with fewer than k neighbours) and counts as  */
+/* a miss.  Returns the recall, or -1.0 on bad arguments.                    */
 /* ------------------------------------------------------------------------ */
 double oracle_graph_recall(const int32_t *test_ids, const float *test_dists, int32_t k_test,
                            const int32_t *ref_ids, const float *ref_dists, int32_t k_ref,
@@ -163,9 +164,11 @@ double oracle_graph_recall(const int32_t *test_ids, const float *test_dists, int
         if (mode == 0) {
             const int32_t *t = test_ids + i * (int64_t)k_test;
             const int32_t *r = ref_ids + i * (int64_t)k_ref;
-            for (int32_t a = 0; a < at_k; ++a)
+            for (int32_t a = 0; a < at_k; ++a) {
+                if (t[a] < 0) continue;             /* padding is no neighbour */
                 for (int32_t b = 0; b < at_k; ++b)
                     if (t[a] == r[b]) { ++hits; break; }
+            }
         } else {
             const float *t = test_dists + i * (int64_t)k_test;
             float thr = ref_dists[i * (int64_t)k_ref + (at_k - 1)];

@@ -259,13 +259,14 @@ k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
     __shared__ u64 candbuf[4][WAVE];                 // the accepted candidates' order words, compacted
     __shared__ u64 lobuf[4][WAVE];                   // the row's order words
     __shared__ uint32_t sigbuf[4][SIG_WORDS];
-    __shared__ u64 part[4];
+    __shared__ u64 part[8];
     const int lane = lane_id();
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // keeps v scalar
     const int64_t nwaves = (int64_t)gridDim.x * 4;
     const u64 lt = lanemask_lt();
     const uint32_t tag = 0x200u + 4u * iter;
     u64 accepted = 0;
+    uint32_t occupied = 0;                           // candidate slots found occupied (uniform)
 
     const uint32_t saltp = rev_salt(seed, iter);
     const uint32_t salts = hash32(saltp + 0x3c6ef372u);
@@ -292,7 +293,9 @@ k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
         }
         bool changed = false;
         // ---- merge
-        if (__ballot(ck != EMPTY_KEY) != 0ull) {
+        const u64 occm = __ballot(ck != EMPTY_KEY);
+        if (occm != 0ull) {
+            occupied += (uint32_t)__popcll(occm);
             if (ck != EMPTY_KEY) cand[v * C + lane] = EMPTY_KEY;
             const u64 lo = key_order(row);
             const u64 co = key_order(ck);
@@ -391,11 +394,13 @@ k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
         if (lane < SIG_WORDS) sig[v * SIG_WORDS + lane] = sigbuf[w][lane];
         wave_lds_sync();
     }
-    if (lane == 0) part[w] = accepted;
+    if (lane == 0) { part[w] = accepted; part[4 + w] = (u64)occupied; }
     __syncthreads();
     if (threadIdx.x == 0) {
         u64 t = part[0] + part[1] + part[2] + part[3];
         if (t) atomicAdd(updates, t);
+        t = part[4] + part[5] + part[6] + part[7];
+        if (t) atomicAdd(updates + 5, t);            // ctr[5]: occupied candidate slots
     }
 }
 
@@ -1182,6 +1187,7 @@ struct JoinArgs {
     const int32_t* newl; const int32_t* oldl; const int4* plan; const int32_t* active;
     const u64* nactive; const float* worst; const uint32_t* sig; u64* cand; u64* offers;
     int num_cu; int64_t n;
+    int* blocks_per_cu;       // resident workgroups per CU of this build's join kernel; 0 = not yet asked
 };
 
 template <int METRIC, int S16, int DS, bool VEC, int ELEM = 0>
@@ -1189,17 +1195,18 @@ static hipError_t launch_join_k(hipStream_t st, const JoinArgs& a)
 {
     const int lds = JoinCfg<S16, DS, ELEM>::LDS_BYTES;
     auto kern = k_join<METRIC, S16, DS, VEC, ELEM>;
-    static int blocks_per_cu = 0;            // per instantiation: resident workgroups per CU
-    if (blocks_per_cu == 0) {
+    // asked once per build, on the build's device (a build runs one join kernel): the attribute is
+    // per device, and nothing is kept between calls
+    if (*a.blocks_per_cu == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         int occ = 0;
         e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, 256, lds);
         if (e != hipSuccess) return e;
-        blocks_per_cu = occ > 0 ? occ : 1;
+        *a.blocks_per_cu = occ > 0 ? occ : 1;
     }
-    int64_t grid = (int64_t)a.num_cu * blocks_per_cu;
+    int64_t grid = (int64_t)a.num_cu * *a.blocks_per_cu;
     if (grid > a.n) grid = a.n;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a.pts, a.d, a.C, a.s, a.iter, a.newl,
                        a.oldl, a.plan, a.active, a.nactive, a.worst, a.sig, a.cand, a.offers);
@@ -1211,17 +1218,18 @@ static hipError_t launch_join_w(hipStream_t st, const JoinArgs& a)
 {
     const int lds = 4 * WaveCfg<S16, ELEM>::WBYTES;
     auto kern = k_join_wave<METRIC, S16, VEC, ELEM, SPLIT>;
-    static int blocks_per_cu = 0;            // per instantiation: resident workgroups per CU
-    if (blocks_per_cu == 0) {
+    // asked once per build, on the build's device (a build runs one join kernel): the attribute is
+    // per device, and nothing is kept between calls
+    if (*a.blocks_per_cu == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         int occ = 0;
         e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, 256, lds);
         if (e != hipSuccess) return e;
-        blocks_per_cu = occ > 0 ? occ : 1;
+        *a.blocks_per_cu = occ > 0 ? occ : 1;
     }
-    int64_t grid = (int64_t)a.num_cu * blocks_per_cu;
+    int64_t grid = (int64_t)a.num_cu * *a.blocks_per_cu;
     if (grid > (a.n + 3) / 4) grid = (a.n + 3) / 4;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a.pts, a.d, a.C, a.s, a.iter, a.newl,
                        a.oldl, a.plan, a.active, a.nactive, a.worst, a.sig, a.cand, a.offers);
@@ -1302,6 +1310,7 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
     if (!params->workspace_dev || params->workspace_bytes < bp.total ||
         (reinterpret_cast<uintptr_t>(params->workspace_dev) & 255u))
         return KNNG_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(params->pinned_host) & 7u) return KNNG_EINVAL;
 
     hipStream_t st = reinterpret_cast<hipStream_t>(params->stream);
     unsigned char* ws = static_cast<unsigned char*>(params->workspace_dev);
@@ -1315,7 +1324,7 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
     int32_t* active = reinterpret_cast<int32_t*>(ws + bp.off_active);
     float* worst = reinterpret_cast<float*>(ws + bp.off_worst);
     uint32_t* sig = reinterpret_cast<uint32_t*>(ws + bp.off_sig);
-    u64* ctr = reinterpret_cast<u64*>(ws + bp.off_ctr);      // [0] updates [1] rows gathered [2] active [3] pairs [4] offers
+    u64* ctr = reinterpret_cast<u64*>(ws + bp.off_ctr);      // [0] updates [1] rows gathered [2] active [3] pairs [4] offers [5] occupied slots
     knng_stats_t* stats = params->stats_host;
     const bool vec = (d % (elem == 1 ? 16 : elem == 2 ? 8 : 4) == 0) && ((reinterpret_cast<uintptr_t>(points_dev) & 15u) == 0);
     const unsigned row_blocks = (unsigned)((n + 3) / 4);
@@ -1324,13 +1333,23 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
 
     int rc = KNNG_OK;
     int num_cu = 0;
+    int join_blocks_per_cu = 0;
     u64* host_ctr = nullptr;
+    bool own_ctr = false;
     // events: [0] start, [1] after init, then 4 per iteration (sample, join start, join end, merge), last = end
     const int max_rec = bp.max_iters < KNNG_STATS_MAX_ITERS ? bp.max_iters : KNNG_STATS_MAX_ITERS;
     const int n_ev = stats ? 8 + 4 * max_rec : 0;
     hipEvent_t* ev = nullptr;
     int iters = 0, converged = 0;
     if (stats) memset(stats, 0, sizeof(*stats));
+    // statistics only: an event per recorded point of the stream, created the first time it is used
+    auto record = [&](int i) -> hipError_t {
+        if (!ev[i]) {
+            hipError_t e = hipEventCreate(&ev[i]);
+            if (e != hipSuccess) return e;
+        }
+        return hipEventRecord(ev[i], st);
+    };
 
     {
         int dev = 0;
@@ -1339,12 +1358,16 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
         if (num_cu < 1) num_cu = 1;
         upd_blocks = row_blocks < (unsigned)num_cu * 8u ? row_blocks : (unsigned)num_cu * 8u;
     }
-    HIPCHK(hipHostMalloc(reinterpret_cast<void**>(&host_ctr), 64, hipHostMallocDefault));
+    if (params->pinned_host) {
+        host_ctr = static_cast<u64*>(params->pinned_host);
+    } else {
+        HIPCHK(hipHostMalloc(reinterpret_cast<void**>(&host_ctr), 64, hipHostMallocDefault));
+        own_ctr = true;
+    }
     if (stats) {
         ev = new hipEvent_t[n_ev];
-        for (int i = 0; i < n_ev; ++i) ev[i] = nullptr;
-        for (int i = 0; i < n_ev; ++i) HIPCHK(hipEventCreate(&ev[i]));
-        HIPCHK(hipEventRecord(ev[0], st));
+        for (int i = 0; i < n_ev; ++i) ev[i] = nullptr;    // created when first recorded
+        HIPCHK(record(0));
     }
     HIPCHK(hipMemsetAsync(ctr, 0, 256, st));
     if (elem == 2)
@@ -1360,7 +1383,7 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
         hipLaunchKernelGGL((k_init<1, 0>), dim3(row_blocks), dim3(256), 0, st, points_dev, n, d, bp.K, bp.C,
                            params->seed, params->init_ids_dev, G, cand, cnt, worst, rev, bp.B);
     HIPCHK(hipGetLastError());
-    if (stats) HIPCHK(hipEventRecord(ev[1], st));
+    if (stats) HIPCHK(record(1));
 
     // Iteration it: k_update merges what join it-1 offered and samples for join it; the host
     // reads the update count of iteration it-1 (the only device->host crossing of the loop)
@@ -1372,17 +1395,17 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
         hipLaunchKernelGGL(k_update, dim3(upd_blocks), dim3(256), 0, st, n, bp.K, bp.C, bp.s, params->seed,
                            (uint32_t)it, more ? 1 : 0, G, cand, newl, oldl, cnt, sig, worst, ctr, rev, bp.B);
         HIPCHK(hipGetLastError());
-        if (rec) HIPCHK(hipEventRecord(ev[2 + 4 * it], st));
-        if (stats && !more) HIPCHK(hipEventRecord(ev[n_ev - 2], st));
+        if (rec) HIPCHK(record(2 + 4 * it));
+        if (stats && !more) HIPCHK(record(n_ev - 2));
         if (it > 0) {
-            HIPCHK(hipMemcpyAsync(host_ctr, ctr, 40, hipMemcpyDeviceToHost, st));
-            HIPCHK(hipMemsetAsync(ctr, 0, 40, st));
+            HIPCHK(hipMemcpyAsync(host_ctr, ctr, 48, hipMemcpyDeviceToHost, st));
+            HIPCHK(hipMemsetAsync(ctr, 0, 48, st));
             HIPCHK(hipStreamSynchronize(st));
             if (stats && it - 1 < max_rec) {
                 stats->updates[it - 1] = host_ctr[0];
                 stats->join_rows[it - 1] = host_ctr[1];
             }
-            if (stats) { stats->pairs += host_ctr[3]; stats->offers += host_ctr[4]; }
+            if (stats) { stats->pairs += host_ctr[3]; stats->offers += host_ctr[4]; stats->cand_kept += host_ctr[5]; }
             if ((double)host_ctr[0] < stop_below) { converged = 1; break; }
         }
         if (!more) break;
@@ -1390,16 +1413,16 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
                            params->seed, (uint32_t)it, rev + (int64_t)(it & 1) * 2 * n * bp.B,
                            reinterpret_cast<const int2*>(cnt), newl, oldl, plan, active, ctr);
         HIPCHK(hipGetLastError());
-        if (rec) HIPCHK(hipEventRecord(ev[3 + 4 * it], st));
+        if (rec) HIPCHK(record(3 + 4 * it));
         {
             JoinArgs ja{points_dev, elem == 1 ? d / 4 : elem == 2 ? d / 2 : d, bp.C, bp.s, (uint32_t)it, newl, oldl, plan, active, ctr + 2,
-                        worst, sig, cand, ctr + 4, num_cu, n};
+                        worst, sig, cand, ctr + 4, num_cu, n, &join_blocks_per_cu};
             if (elem == 1) HIPCHK(launch_join_compact<1>(st, vec, bp.S16, ja));
             else if (elem == 2) HIPCHK(launch_join_compact<2>(st, vec, bp.S16, ja));
             else if (metric == 0) HIPCHK(launch_join<0>(st, vec, bp.S16, ja));
             else HIPCHK(launch_join<1>(st, vec, bp.S16, ja));
         }
-        if (rec) HIPCHK(hipEventRecord(ev[4 + 4 * it], st));
+        if (rec) HIPCHK(record(4 + 4 * it));
         iters = it + 1;
     }
     {
@@ -1423,7 +1446,7 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
 #undef KNNG_FIN
         HIPCHK(hipGetLastError());
     }
-    if (stats) HIPCHK(hipEventRecord(ev[n_ev - 1], st));
+    if (stats) HIPCHK(record(n_ev - 1));
     HIPCHK(hipStreamSynchronize(st));
     if (stats) {
         stats->iterations = iters;
@@ -1455,7 +1478,7 @@ done:
         for (int i = 0; i < n_ev; ++i) if (ev[i]) (void)hipEventDestroy(ev[i]);
         delete[] ev;
     }
-    if (host_ctr) (void)hipHostFree(host_ctr);
+    if (own_ctr) (void)hipHostFree(host_ctr);
     return rc;
 }
 

@@ -37,8 +37,8 @@ k_recall(const int32_t* __restrict__ tid_, const float* __restrict__ tdist, int 
         if (MODE == 0) {
             const int id = tid_[row * k_test + a];
             const int32_t* r = rid + row * k_ref;
-            bool hit = false;
-            for (int b = 0; b < at_k; ++b) hit = hit || (r[b] == id);
+            bool hit = false;                                   // padding (id < 0) is no neighbour
+            for (int b = 0; b < at_k; ++b) hit = hit || (id >= 0 && r[b] == id);
             acc += hit ? 1u : 0u;
         } else {
             acc += (tdist[row * k_test + a] <= rdist[row * k_ref + (at_k - 1)]) ? 1u : 0u;

@@ -7,6 +7,7 @@ Function names and argument meaning follow include/knng.h.
 """
 import ctypes
 import os
+import threading
 
 import torch
 
@@ -29,7 +30,8 @@ class Stats(ctypes.Structure):
                 ("ms_join", ctypes.c_float), ("ms_merge", ctypes.c_float),
                 ("ms_finalize", ctypes.c_float), ("ms_total", ctypes.c_float),
                 ("offers", ctypes.c_uint64),
-                ("pairs", ctypes.c_uint64)]
+                ("pairs", ctypes.c_uint64),
+                ("cand_kept", ctypes.c_uint64)]
 
 
 class Params(ctypes.Structure):
@@ -44,7 +46,8 @@ class Params(ctypes.Structure):
                 ("stream", _P),
                 ("workspace_dev", _P),
                 ("workspace_bytes", ctypes.c_uint64),
-                ("stats_host", ctypes.POINTER(Stats))]
+                ("stats_host", ctypes.POINTER(Stats)),
+                ("pinned_host", _P)]
 
 
 EXPORTS = ("knng_build_workspace_bytes", "knng_build_knn_graph", "knng_build_knn_graph_u8", "knng_build_knn_graph_f16",
@@ -130,6 +133,17 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
+_tls = threading.local()
+
+
+def _pinned_counter():
+    """64 bytes of page-locked host memory per calling thread (the build's convergence counter)."""
+    t = getattr(_tls, "pinned", None)
+    if t is None:
+        t = _tls.pinned = torch.empty(64, dtype=torch.uint8, pin_memory=True)
+    return t
+
+
 def knng_version() -> int:
     return int(load().knng_version())
 
@@ -172,6 +186,7 @@ def _build_graph(entry, dtype, points, k, metric, k_build, rho, delta, max_iters
     p.workspace_bytes = workspace.numel()
     if st is not None:
         p.stats_host = ctypes.pointer(st)
+    p.pinned_host = ctypes.c_void_p(_pinned_counter().data_ptr())
     _check(getattr(L, entry)(_ptr(points), n, d, k, metric, ctypes.byref(p), _ptr(ids_out), _ptr(dists_out)))
     stats = None
     if st is not None:
@@ -181,7 +196,7 @@ def _build_graph(entry, dtype, points, k, metric, k_build, rho, delta, max_iters
                  "join_rows": list(st.join_rows[:it]), "ms_init": st.ms_init,
                  "ms_sample": st.ms_sample, "ms_join": st.ms_join, "ms_merge": st.ms_merge,
                  "ms_finalize": st.ms_finalize, "ms_total": st.ms_total,
-                 "offers": int(st.offers), "pairs": int(st.pairs)}
+                 "offers": int(st.offers), "pairs": int(st.pairs), "cand_kept": int(st.cand_kept)}
     return ids_out, dists_out, stats
 
 

@@ -88,10 +88,10 @@ def test_f16_pointer_alignment_paths_and_errors():
     assert bool((ids == -7).all()) and bool((dists == -7.0).all())
 
 
-def test_f16_full_size_config3_gist_shape():
-    # config 3 (1,000,000 x 960) stored as fp16: the launch configuration of the benchmark's
+def test_f16_full_size_config4_gist_shape():
+    # config 4 (1,000,000 x 960) stored as fp16: the launch configuration of the benchmark's
     # --elem f16 run; sampled rows against the oracle on the fp16 values
-    x, w = workloads.make(3, device=DEV)
+    x, w = workloads.make(4, device=DEV)
     x16 = x.to(torch.float16)
     del x
     xf = x16.float()

@@ -43,7 +43,7 @@ def test_optimize_exact_graphs_bit_exact(n, k, d_out):
 
 
 def test_optimize_an_approximate_graph_from_the_build():
-    x, w = workloads.make(0)
+    x, w = workloads.make(1)
     ids, _, _ = knng.knng_build_knn_graph(_gpu(x), 16, w.metric, k_build=32, seed=2)
     for d_out in (16, 8):
         got = knng.knng_optimize_graph(ids, d_out).cpu().numpy()
@@ -102,9 +102,9 @@ def test_optimize_argument_errors():
     assert knng.knng_optimize_workspace_bytes(300, 65, 8) == 0
 
 
-def test_optimize_full_size_config1_graph_bit_exact():
+def test_optimize_full_size_config2_graph_bit_exact():
     # the graph the benchmark's build produces (1,000,000 x 32), optimised to degree 32 and 16
-    x, w = workloads.make(1, device=DEV)
+    x, w = workloads.make(2, device=DEV)
     ids, _, _ = knng.knng_build_knn_graph(x, w.k, w.metric, seed=0)
     del x
     ids_h = ids.cpu().numpy()

@@ -29,8 +29,8 @@ def _brute_both(x, k, metric, rows=None):
 
 
 # ------------------------------------------------------------------ brute_knn
-def test_brute_config0_full_bit_exact():
-    x, w = workloads.make(0)
+def test_brute_config1_full_bit_exact():
+    x, w = workloads.make(1)
     gi, gd, oi, od = _brute_both(x, w.k, w.metric)
     assert np.array_equal(gi, oi)
     assert np.array_equal(gd.view(np.uint32), od.view(np.uint32))
@@ -80,15 +80,15 @@ def test_brute_far_from_the_origin_and_near_duplicates():
     assert np.array_equal(gi, oi) and np.array_equal(gd.view(np.uint32), od.view(np.uint32))
 
 
-def test_brute_integer_valued_data_config1_shape():
-    x, w = workloads.make(1, n=30_000)                     # many exact ties at integer distances
+def test_brute_integer_valued_data_config2_shape():
+    x, w = workloads.make(2, n=30_000)                     # many exact ties at integer distances
     rows = workloads.sample_rows(30_000, 1500)
     gi, gd, oi, od = _brute_both(x, w.k, w.metric, rows)
     assert np.array_equal(gi, oi) and np.array_equal(gd, od)
 
 
 def test_brute_query_rows_and_split_reduction():
-    x, w = workloads.make(0, n=20_000)
+    x, w = workloads.make(1, n=20_000)
     rows = np.array([19_999, 0, 7, 7, 12_345], np.int32)   # few queries => many base ranges
     gi, gd, oi, od = _brute_both(x, w.k, w.metric, rows)
     assert np.array_equal(gi, oi) and np.array_equal(gd, od)
@@ -164,8 +164,8 @@ def _check_build(x, k, metric, ids, dists, exact=None, min_recall=None):
     return None
 
 
-def test_build_config0_invariants_distances_and_recall():
-    x, w = workloads.make(0)
+def test_build_config1_invariants_distances_and_recall():
+    x, w = workloads.make(1)
     exact = oracle.brute_knn(x, w.k, w.metric)
     ids, dists, st = knng.knng_build_knn_graph(_gpu(x), w.k, w.metric, k_build=32, rho=0.5, seed=1)
     rec = _check_build(x, w.k, w.metric, ids, dists, exact, min_recall=0.95)
@@ -177,8 +177,8 @@ def test_build_config0_invariants_distances_and_recall():
     assert g == pytest.approx(rec, abs=1e-12)
 
 
-@pytest.mark.parametrize("idx,n,kb,rho", [(1, 30_000, 32, 0.5), (2, 30_000, 32, 0.5), (3, 6_000, 32, 0.5),
-                                         (0, 5_003, 48, 0.8), (0, 3_001, 64, 1.0), (2, 4_000, 17, 1.0)])
+@pytest.mark.parametrize("idx,n,kb,rho", [(2, 30_000, 32, 0.5), (3, 30_000, 32, 0.5), (4, 6_000, 32, 0.5),
+                                         (1, 5_003, 48, 0.8), (1, 3_001, 64, 1.0), (3, 4_000, 17, 1.0)])
 def test_build_other_shapes_and_metrics(idx, n, kb, rho):
     x, w = workloads.make(idx, n=n)
     k = min(w.k, kb)
@@ -248,7 +248,7 @@ def test_build_smallest_and_largest_parameter_corners(n, d, k, kb, rho):
 
 
 def test_build_random_start_and_monotone_refinement():
-    x, w = workloads.make(0, n=4000)
+    x, w = workloads.make(1, n=4000)
     k = 10
     exact = oracle.brute_knn(x, k, w.metric)
     prev = None
@@ -269,7 +269,7 @@ def test_build_random_start_and_monotone_refinement():
 
 
 def test_build_warm_start_keeps_a_good_graph():
-    x, w = workloads.make(0, n=3000)
+    x, w = workloads.make(1, n=3000)
     k = 12
     oi, od = oracle.brute_knn(x, k, w.metric)
     init = oi.copy()
@@ -285,7 +285,7 @@ def test_build_candidate_capacity_and_heavy_contention():
     exact = oracle.brute_knn(x, 8, 0)
     ids, dists, _ = knng.knng_build_knn_graph(_gpu(x), 8, 0, k_build=30, rho=1.0, cand_cap=3, seed=6)
     _check_build(x, 8, 0, ids, dists, exact, min_recall=0.9)
-    x, w = workloads.make(0, n=6000)
+    x, w = workloads.make(1, n=6000)
     exact = oracle.brute_knn(x, w.k, w.metric)
     ids, dists, _ = knng.knng_build_knn_graph(_gpu(x), w.k, w.metric, k_build=32, cand_cap=4, seed=6)
     _check_build(x, w.k, w.metric, ids, dists, exact, min_recall=0.9)
@@ -295,7 +295,7 @@ def test_build_is_reproducible_run_to_run():
     # every cross-point write of the build is an atomic min (candidate slots, reverse buckets):
     # the result does not depend on the order the wavefronts ran in
     # (the larger sets reach every member count of the 128- and 256-member kernels, their maxima included)
-    for idx, n, kb, rho in ((0, 20_000, 32, 0.5), (2, 9_000, 24, 1.0), (4, 200_000, 64, 0.5), (4, 100_000, 64, 1.0)):
+    for idx, n, kb, rho in ((1, 20_000, 32, 0.5), (3, 9_000, 24, 1.0), (5, 200_000, 64, 0.5), (5, 100_000, 64, 1.0)):
         x, w = workloads.make(idx, n=n)
         xg = _gpu(x)
         k = min(w.k, kb)
@@ -371,20 +371,20 @@ def _full_size_case(idx, kw, oracle_rows, recall_rows=10_000, min_recall=0.95):
     assert not bool((srt[:, 1:] == srt[:, :-1]).any())             # no duplicate ids in a row
 
 
-def test_full_size_config1_sift_shape():
-    _full_size_case(1, {}, oracle_rows=48)
+def test_full_size_config2_sift_shape():
+    _full_size_case(2, {}, oracle_rows=1000)
 
 
-def test_full_size_config2_unit_vectors_ip():
-    _full_size_case(2, {}, oracle_rows=48)
+def test_full_size_config3_unit_vectors_ip():
+    _full_size_case(3, {}, oracle_rows=1000)
 
 
-def test_full_size_config3_gist_shape():
-    _full_size_case(3, {}, oracle_rows=16, recall_rows=4000)
+def test_full_size_config4_gist_shape():
+    _full_size_case(4, {}, oracle_rows=256, recall_rows=4000)
 
 
-def test_full_size_config4_twenty_million():
-    _full_size_case(4, dict(k_build=64), oracle_rows=8, recall_rows=4000)
+def test_full_size_config5_twenty_million():
+    _full_size_case(5, dict(k_build=64), oracle_rows=64, recall_rows=4000)
 
 
 # ------------------------------------------------------------------ merge_graphs (Sec. 4.3 step 4, 4.4)
@@ -450,7 +450,7 @@ def test_merge_of_two_partitions_then_warm_started_refinement():
     # neighbours inside the *other* half of the data play the search results R; merged into the
     # graph each half built on its own they give the graph of the whole set, and a warm-started
     # build over the whole set keeps or improves it
-    x, w = workloads.make(0, n=8000)
+    x, w = workloads.make(1, n=8000)
     n, k = w.n, w.k
     xg = _gpu(x)
     exact = oracle.brute_knn(x, k, w.metric)

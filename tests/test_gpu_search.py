@@ -82,7 +82,7 @@ def test_search_graph_with_padding_repeats_and_bad_starts():
 def test_search_on_the_search_graph_of_a_built_graph_two_partitions():
     # one level of the paper's scheme without the network: the points of partition B search
     # the optimised graph of partition A
-    x, w = workloads.make(0)
+    x, w = workloads.make(1)
     a, b = x[:12_000], x[12_000:]
     ids, _, _ = knng.knng_build_knn_graph(_gpu(a), 16, w.metric, k_build=32, seed=3)
     gs = knng.knng_optimize_graph(ids, 16).cpu().numpy()
@@ -116,7 +116,7 @@ def test_one_refinement_level_on_one_gpu_build_optimise_search_merge():
     # (Sec. 4.3, 4.4), with the exchange left out: each builds its own graph, B's points search
     # A's search graph and A's search B's, each updates its rows with what it found.  The
     # result is compared with the exact graph of the whole set.
-    x, w = workloads.make(5, n=24_000)
+    x, w = workloads.make(6, n=24_000)
     k = 16
     half = len(x) // 2
     parts = [x[:half], x[half:]]

@@ -116,10 +116,10 @@ def test_u8_argument_errors_leave_outputs_untouched():
     assert bool((ids == -7).all()) and bool((dists == -7.0).all())
 
 
-def test_u8_full_size_config1_sift_shape():
-    # config 1's values are 8-bit by construction: the same workload stored as uint8, in the
+def test_u8_full_size_config2_sift_shape():
+    # config 2's values are 8-bit by construction: the same workload stored as uint8, in the
     # launch configuration the benchmark times; sampled rows against the oracle
-    x, w = workloads.make(1, device=DEV)
+    x, w = workloads.make(2, device=DEV)
     x8 = x.to(torch.uint8)
     assert torch.equal(x8.float(), x)
     n, k = w.n, w.k

@@ -220,7 +220,7 @@ def test_brute_knn_lattice_fixture(golden_dir):
 
 def test_brute_knn_matches_library_topk_on_tie_free_data():
     torch = pytest.importorskip("torch")
-    x, w = workloads.make(0, n=3000)
+    x, w = workloads.make(1, n=3000)
     ids, dd = oracle.brute_knn(x, w.k, w.metric)
     t = torch.from_numpy(x).double()
     D = torch.cdist(t, t) ** 2
@@ -251,7 +251,7 @@ def test_brute_knn_restricted_to_a_base_prefix():
 
 
 def test_brute_knn_query_rows_subset_and_argument_checks():
-    x, w = workloads.make(0, n=500)
+    x, w = workloads.make(1, n=500)
     full_i, full_d = oracle.brute_knn(x, 7, w.metric)
     rows = np.array([499, 0, 17, 17, 250], np.int32)
     sub_i, sub_d = oracle.brute_knn(x, 7, w.metric, query_rows=rows)
@@ -292,7 +292,7 @@ def test_recall_hand_fixture(golden_dir):
 
 
 def test_recall_identity_disjoint_and_mode_order():
-    x, w = workloads.make(0, n=800)
+    x, w = workloads.make(1, n=800)
     ids, dd = oracle.brute_knn(x, 12, w.metric)
     assert oracle.graph_recall(ids, dd, ids, dd, 12, 0) == 1.0
     assert oracle.graph_recall(ids, dd, ids, dd, 12, 1) == 1.0
@@ -308,8 +308,18 @@ def test_recall_identity_disjoint_and_mode_order():
 
 
 # --------------------------------------------------------------------------- invariant checker
+def test_recall_padding_is_a_miss():
+    # rows with fewer than k neighbours are padded with id -1 (merged rows, search results):
+    # padding matches nothing, not even the reference row's own padding (Sec. 2.1: recall counts
+    # neighbours)
+    t = np.array([[3, 5, -1, -1]], np.int32)
+    r = np.array([[5, 3, -1, -1]], np.int32)
+    assert oracle.graph_recall(t, None, r, None, 4, 0) == 0.5
+    assert oracle.graph_recall(t, None, r, None, 2, 0) == 1.0
+
+
 def test_check_graph_counts_each_planted_violation():
-    x, w = workloads.make(0, n=300)
+    x, w = workloads.make(1, n=300)
     ids, dd = oracle.brute_knn(x, 8, w.metric)
     clean = oracle.check_graph(x, ids, dd, w.metric, rel_tol=0.0)
     assert sum(clean.values()) == 0
@@ -351,7 +361,7 @@ def test_nn_descent_with_full_degree_is_the_exact_graph(metric):
 
 
 def test_nn_descent_invariants_and_monotone_refinement():
-    x, w = workloads.make(0, n=1500)
+    x, w = workloads.make(1, n=1500)
     k = 10
     exact_i, exact_d = oracle.brute_knn(x, k, w.metric)
     prev_d, prev_recall = None, None
@@ -383,7 +393,7 @@ def test_nn_descent_converges_on_one_blob_without_sampling():
 
 
 def test_nn_descent_stop_rule_and_defaults_band():
-    x, w = workloads.make(0, n=4000)
+    x, w = workloads.make(1, n=4000)
     k = w.k
     exact_i, exact_d = oracle.brute_knn(x, k, w.metric)
     ids, dd, tight = oracle.nn_descent(x, k, w.metric, rho=0.5, delta=1e-4, max_iters=100, seed=3)
@@ -405,7 +415,7 @@ def test_nn_descent_stop_rule_and_defaults_band():
 
 
 def test_nn_descent_fixed_size_candidate_lists_drop():
-    x, w = workloads.make(0, n=3000)
+    x, w = workloads.make(1, n=3000)
     k = 12
     exact_i, exact_d = oracle.brute_knn(x, k, w.metric)
     rec = {}
