@@ -50,7 +50,8 @@ enum {
     KNNG_OK = 0,
     KNNG_EINVAL = -1,      /* bad argument (null pointer, n < 2, k < 1, k > n-1, ...) */
     KNNG_EWORKSPACE = -2,  /* workspace missing or smaller than knng_*_workspace_bytes */
-    KNNG_EHIP = -3         /* a HIP call failed; knng_strerror(KNNG_EHIP) has its text */
+    KNNG_EHIP = -3,        /* a HIP call failed; knng_strerror(KNNG_EHIP) has its text */
+    KNNG_ETOOLARGE = -4    /* more input than an entry point with fixed scratch memory takes */
 };
 
 enum { KNNG_METRIC_L2SQ = 0, KNNG_METRIC_IP_UNIT = 1 };
@@ -202,6 +203,27 @@ int knng_graph_recall(const int32_t *test_ids_dev, const float *test_dists_dev, 
                       const int32_t *ref_ids_dev, const float *ref_dists_dev, int32_t k_ref,
                       int64_t rows, int32_t at_k, int32_t mode,
                       double *recall_out_host, void *stream);
+
+/*
+ * knng_graph_recall for callers that cannot allocate or wait: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The same recall,
+ * bit for bit, but the call allocates nothing, copies nothing to the host and does
+ * not synchronise: it enqueues two kernels on `stream` and returns; *recall_out_dev
+ * (DEVICE memory, one double, 8-byte aligned) holds hits / (rows * at_k) once they
+ * have run.  The per-workgroup partial counts live in a fixed 64 KiB device array
+ * inside the library (every GPU the library runs on holds it until the process
+ * ends); its address is looked up on the first call on a device.  Nothing in it has
+ * to start at zero, and no memset is enqueued.
+ * Limits: rows * at_k <= KNNG_RECALL_STATIC_MAX_ENTRIES, else KNNG_ETOOLARGE and
+ * nothing is enqueued.  All calls on one GPU share the array: calls that overlap in
+ * time on one GPU (different streams, different threads) race and must be ordered by
+ * the caller.  Other arguments and errors as knng_graph_recall.
+ */
+#define KNNG_RECALL_STATIC_MAX_ENTRIES (1ll << 36)
+int knng_graph_recall_static(const int32_t *test_ids_dev, const float *test_dists_dev, int32_t k_test,
+                             const int32_t *ref_ids_dev, const float *ref_dists_dev, int32_t k_ref,
+                             int64_t rows, int32_t at_k, int32_t mode,
+                             double *recall_out_dev, void *stream);
 
 /*
  * Update of a graph's rows with neighbour candidates found elsewhere: the local

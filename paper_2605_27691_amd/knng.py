@@ -52,7 +52,7 @@ class Params(ctypes.Structure):
 
 EXPORTS = ("knng_build_workspace_bytes", "knng_build_knn_graph", "knng_build_knn_graph_u8", "knng_build_knn_graph_f16",
            "knng_brute_workspace_bytes",
-           "knng_brute_knn", "knng_brute_knn_base", "knng_graph_recall", "knng_merge_graphs", "knng_optimize_workspace_bytes",
+           "knng_brute_knn", "knng_brute_knn_base", "knng_graph_recall", "knng_graph_recall_static", "knng_merge_graphs", "knng_optimize_workspace_bytes",
            "knng_optimize_graph", "knng_graph_search", "knng_graph_search_u8", "knng_strerror", "knng_version")
 
 _lib = None
@@ -88,6 +88,8 @@ def load():
     L.knng_graph_recall.restype = ctypes.c_int
     L.knng_graph_recall.argtypes = [_P, _P, i32, _P, _P, i32, i64, i32, i32,
                                     ctypes.POINTER(ctypes.c_double), _P]
+    L.knng_graph_recall_static.restype = ctypes.c_int
+    L.knng_graph_recall_static.argtypes = [_P, _P, i32, _P, _P, i32, i64, i32, i32, _P, _P]
     L.knng_merge_graphs.restype = ctypes.c_int
     L.knng_merge_graphs.argtypes = [_P, _P, i32, _P, _P, i32, i64, i32, _P, _P, _P]
     L.knng_optimize_workspace_bytes.restype = u64
@@ -274,6 +276,26 @@ def knng_graph_recall(test_ids, test_dists, ref_ids, ref_dists, at_k, mode=0) ->
                                _ptr(ref_dists), r.shape[1], t.shape[0], at_k, mode,
                                ctypes.byref(out), _stream()))
     return float(out.value)
+
+
+def knng_graph_recall_static(test_ids, test_dists, ref_ids, ref_dists, at_k, mode=0, out=None):
+    """The same recall without allocation, host copy or synchronisation inside the library.
+    -> `out`, a float64 GPU tensor of one element, valid once the current stream has run."""
+    L = load()
+    test_ids = _dev(test_ids, torch.int32, "test_ids")
+    ref_ids = _dev(ref_ids, torch.int32, "ref_ids")
+    test_dists = _dev(test_dists, torch.float32, "test_dists")
+    ref_dists = _dev(ref_dists, torch.float32, "ref_dists")
+    t = test_ids if test_ids is not None else test_dists
+    r = ref_ids if ref_ids is not None else ref_dists
+    if t is None or r is None or t.shape[0] != r.shape[0]:
+        raise KnngError(-1)
+    if out is None:
+        out = torch.empty(1, dtype=torch.float64, device=t.device)
+    out = _dev(out, torch.float64, "out")
+    _check(L.knng_graph_recall_static(_ptr(test_ids), _ptr(test_dists), t.shape[1], _ptr(ref_ids),
+                                      _ptr(ref_dists), r.shape[1], t.shape[0], at_k, mode, _ptr(out), _stream()))
+    return out
 
 
 def knng_merge_graphs(ids_a, dists_a, ids_b, dists_b, k_out, ids_out=None, dists_out=None):
