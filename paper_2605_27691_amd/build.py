@@ -21,25 +21,34 @@ def up_to_date() -> bool:
     return all(os.path.getmtime(p) <= t for p in deps)
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile every HIP source and link libknng.so; returns its path."""
-    if not force and up_to_date():
+def build(force: bool = True, verbose: bool = False, defines=(), lib: str = LIB) -> str:
+    """Compile every HIP source and link the shared library; returns its path.
+
+    `defines` ("NAME=value" strings) and `lib` build a variant of the library somewhere else
+    (tuning experiments); the default builds libknng.so in-tree."""
+    if not force and lib == LIB and not defines and up_to_date():
         return LIB
+    objdir = CSRC if lib == LIB else os.path.dirname(os.path.abspath(lib))
+    tag = "" if lib == LIB else os.path.splitext(os.path.basename(lib))[0] + "_"
     objs = []
     procs = []
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(objdir, tag + src.replace(".hip", ".o"))
+        cmd = [HIPCC, *FLAGS, *("-D" + d for d in defines), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd))
-        procs.append((cmd, subprocess.Popen(cmd)))
+        procs.append((cmd, subprocess.Popen(cmd, stderr=subprocess.PIPE, text=True)))
         objs.append(obj)
     for cmd, p in procs:
-        if p.wait() != 0:
+        err = p.communicate()[1]
+        err = "\n".join(l for l in err.splitlines() if "packed-fp32-ops" not in l)   # the host pass does not know the feature
+        if err:
+            print(err)
+        if p.returncode != 0:
             raise RuntimeError("hipcc failed: " + " ".join(cmd))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":

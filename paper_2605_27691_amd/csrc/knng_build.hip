@@ -621,9 +621,14 @@ __device__ __forceinline__ int member_of_slot(int t, int s, int4 c)
 // the compiler parks the accumulators in 32 AGPRs on top of 152 VGPRs, which allows two; told to
 // fit three it needs 149 registers and no spill, and the join runs 28 % faster).  256 member
 // slots: one workgroup per CU by LDS (the distance block alone is 132 KB).
-template <int S16> struct JoinOcc { static constexpr int V = S16 == 4 ? 3 : 1; };
+#ifndef KNNG_JOIN3_OCC
+#define KNNG_JOIN3_OCC 4
+#endif
+template <int S16, int ELEM> struct JoinOcc {
+    static constexpr int V = S16 == 4 ? 3 : S16 == 3 ? (ELEM == 1 ? 3 : KNNG_JOIN3_OCC) : 1;
+};
 template <int METRIC, int S16, int DS_, bool VEC, int ELEM = 0>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(JoinOcc<S16>::V, JoinOcc<S16>::V)))
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(JoinOcc<S16, ELEM>::V, JoinOcc<S16, ELEM>::V)))
 k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
        const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl, const int4* __restrict__ plan,
        const int32_t* __restrict__ active, const u64* __restrict__ nactive_ptr,
@@ -1160,7 +1165,7 @@ static bool make_plan(int64_t n, int32_t d, int32_t k, const knng_params_t* p, B
     if (s > K) s = K;
     bp->K = K; bp->C = C; bp->s = s; bp->rho = rho; bp->delta = delta; bp->max_iters = max_iters;
     bp->B = (KNNG_REV_MULT * s + 3) & ~3; if (bp->B > 128) bp->B = 128;              // reverse buckets per point and kind (>= 2s, % 4 == 0)
-    bp->S16 = (2 * s <= 16) ? 1 : (2 * s <= 32) ? 2 : (2 * s <= 64) ? 4 : 8;
+    bp->S16 = (2 * s <= 16) ? 1 : (2 * s <= 32) ? 2 : (2 * s <= 48) ? 3 : (2 * s <= 64) ? 4 : 8;
     uint64_t off = 0;
     auto take = [&](uint64_t bytes) { uint64_t o = off; off = (off + bytes + 255) & ~255ull; return o; };
     bp->off_G = take((uint64_t)n * K * 8);
@@ -1246,6 +1251,7 @@ static hipError_t launch_join_compact(hipStream_t st, bool vec, int S16, const J
 {
     if (S16 == 1) return vec ? launch_join_w<0, 1, true, ELEM>(st, a) : launch_join_w<0, 1, false, ELEM>(st, a);
     if (S16 == 2) return vec ? launch_join_w<0, 2, true, ELEM>(st, a) : launch_join_w<0, 2, false, ELEM>(st, a);
+    if (S16 == 3) return vec ? launch_join_k<0, 3, 64, true, ELEM>(st, a) : launch_join_k<0, 3, 64, false, ELEM>(st, a);
     if (S16 == 4) return vec ? launch_join_k<0, 4, 64, true, ELEM>(st, a) : launch_join_k<0, 4, 64, false, ELEM>(st, a);
     return vec ? launch_join_k<0, 8, 32, true, ELEM>(st, a) : launch_join_k<0, 8, 32, false, ELEM>(st, a);
 }
@@ -1263,6 +1269,7 @@ static hipError_t launch_join(hipStream_t st, bool vec, int S16, const JoinArgs&
 #define KNNG_JOIN_CASE(S, DSV)                                                      \
     return vec ? launch_join_k<METRIC, S, DSV, true>(st, a) : launch_join_k<METRIC, S, DSV, false>(st, a)
     switch (S16) {
+    case 3: KNNG_JOIN_CASE(3, 64);
     case 4: KNNG_JOIN_CASE(4, 64);
     default: KNNG_JOIN_CASE(8, 32);
     }

@@ -67,9 +67,11 @@ def load():
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB):
+    # KNNG_LIBRARY: another build of the library (a tuning variant) instead of the in-tree one
+    path = os.environ.get("KNNG_LIBRARY") or _build.LIB
+    if path == _build.LIB and not os.path.exists(path):
         _build.build(force=True)
-    L = ctypes.CDLL(_build.LIB)
+    L = ctypes.CDLL(path)
     i32, i64, u64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64
     L.knng_build_workspace_bytes.restype = u64
     L.knng_build_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(Params)]

@@ -178,7 +178,8 @@ def test_build_config1_invariants_distances_and_recall():
 
 
 @pytest.mark.parametrize("idx,n,kb,rho", [(2, 30_000, 32, 0.5), (3, 30_000, 32, 0.5), (4, 6_000, 32, 0.5),
-                                         (1, 5_003, 48, 0.8), (1, 3_001, 64, 1.0), (3, 4_000, 17, 1.0)])
+                                         (1, 5_003, 48, 0.8), (1, 3_001, 64, 1.0), (3, 4_000, 17, 1.0),
+                                         (1, 5_001, 48, 0.5), (3, 6_000, 64, 0.375), (2, 9_000, 40, 0.43)])
 def test_build_other_shapes_and_metrics(idx, n, kb, rho):
     x, w = workloads.make(idx, n=n)
     k = min(w.k, kb)
@@ -295,7 +296,8 @@ def test_build_is_reproducible_run_to_run():
     # every cross-point write of the build is an atomic min (candidate slots, reverse buckets):
     # the result does not depend on the order the wavefronts ran in
     # (the larger sets reach every member count of the 128- and 256-member kernels, their maxima included)
-    for idx, n, kb, rho in ((1, 20_000, 32, 0.5), (3, 9_000, 24, 1.0), (5, 200_000, 64, 0.5), (5, 100_000, 64, 1.0)):
+    for idx, n, kb, rho in ((1, 20_000, 32, 0.5), (3, 9_000, 24, 1.0), (5, 200_000, 64, 0.5), (5, 100_000, 64, 1.0),
+                            (5, 150_000, 64, 0.375)):
         x, w = workloads.make(idx, n=n)
         xg = _gpu(x)
         k = min(w.k, kb)

@@ -47,6 +47,8 @@ def _check(x8, k, ids, dists, min_recall=0.95):
     (100, 16, 32, 32, 0.5),        # K close to n
     (2, 4, 1, 1, 1.0),             # smallest
     (3001, 128, 32, 64, 0.5),      # samples of 32: the workgroup kernel with 128 member slots
+    (3003, 128, 32, 48, 0.5),      # samples of 24: the workgroup kernel with 96 member slots
+    (2500, 36, 16, 64, 0.36),      # samples of 24, 4-byte words
     (2000, 64, 16, 64, 1.0),       # samples of 64: 256 member slots
     (1500, 20, 10, 48, 0.8),       # the same kernel on 4-byte words
 ])
