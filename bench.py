@@ -58,11 +58,11 @@ MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("u8gmm1024_1m_d128_l2", "f32", 32, 0.5): 1
                                      # profiles/k_join_wave_u8_config1_1m_d128.txt: 7.92 GB + 1.47 GB
                                      ("u8gmm1024_1m_d128_l2", "u8", 32, 0.5): 9.39e9}
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # dense bf16 MFMA (the split Gram pass of long fp32 rows: three per product)
-SPLIT_MIN_D = 256                # fp32 rows from this length on take the bf16-split Gram pass (s <= 16)
+SPLIT_MIN_D = 256                # fp32 rows from this length on take the bf16-split Gram pass (s <= 16; s > 16: from 64)
 # Parameters a workload runs with when none are given: the cheapest set found that passes
 # recall@k >= 0.95 (the paper's knobs, Sec. 5.3.1: a build degree above k, then cut to k).
 # Everything else runs the paper's defaults K = k, rho = 0.5, delta = 1e-4.
-PARAM_SETS = {"gmm4096_20m_d128_l2": dict(k_build=64)}
+PARAM_SETS = {"gmm4096_20m_d128_l2": dict(k_build=64, rho=0.375)}
 
 
 def parse():
@@ -366,7 +366,7 @@ def main():
     # their own peak (large samples: s = 32 does four times the pair work per gathered byte)
     mfma_peak = {"u8": INT8_MFMA_PEAK_TOPS, "f16": FP16_MFMA_PEAK_TFLOPS, "f32": FP32_MFMA_PEAK_TFLOPS}[a.elem]
     # long fp32 rows: the Gram pass runs on the bf16 matrix instruction, three instructions per product
-    split = a.elem == "f32" and d % 4 == 0 and d >= SPLIT_MIN_D and s_size <= 16
+    split = a.elem == "f32" and d % 4 == 0 and ((d >= SPLIT_MIN_D and s_size <= 16) or (d >= 64 and s_size > 16))
     mfma_work = needed_tflops
     if split:
         mfma_peak, mfma_work = BF16_MFMA_PEAK_TFLOPS, 3.0 * needed_tflops
@@ -474,7 +474,10 @@ def main():
                      "offers_per_launch": offers / max(launches, 1),
                      # offers that did not survive in their slot (a repeat of the same neighbour or a
                      # closer neighbour sharing the slot): upper bound of the candidates dropped
-                     "offers_not_kept_share": (offers - kept) / max(offers, 1)},
+                     "offers_not_kept_share": (offers - kept) / max(offers, 1),
+                     # joins repeated in fp32 because the bf16-split Gram pass chose a partner it could
+                     # not be trusted with (share of the joins of the timed builds)
+                     "rejoined_share": sum(s["rejoined"] for s in stats) / max(sum(s["joined"] for s in stats), 1)},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -78,6 +78,11 @@ typedef struct knng_stats {
                                   the second kind is a dropped candidate (Sec. 3.1.1: a
                                   fixed-size list may drop true neighbours), so the
                                   difference bounds the drops from above                */
+    uint64_t joined;           /* local joins done (points with a new member around them), whole build */
+    uint64_t rejoined;         /* joins done twice, whole build: points whose join in reduced
+                                  precision (long fp32 rows, or samples above 16: the Gram
+                                  block on bf16 halves) chose a partner far closer to a member
+                                  than both are to the point, and was repeated in fp32        */
 } knng_stats_t;
 
 /*

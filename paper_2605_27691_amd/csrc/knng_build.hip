@@ -614,6 +614,40 @@ __device__ __forceinline__ int member_of_slot(int t, int s, int4 c)
     return -1;
 }
 
+// Two bf16 halves of four fp32 values, both rounded to nearest (v_cvt_pk_bf16_f32): hi = bf16(x),
+// lo = bf16(x - hi) (that difference is exact in fp32).  |x - hi| <= 2^-9 |x|, |x - hi - lo| <= 2^-18 |x|.
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+typedef float floatx2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void split_bf16(float4 x, short4v& hi, short4v& lo)
+{
+    const bf16x2v h01 = __builtin_convertvector(floatx2v{x.x, x.y}, bf16x2v);
+    const bf16x2v h23 = __builtin_convertvector(floatx2v{x.z, x.w}, bf16x2v);
+    const floatx2v f01 = __builtin_convertvector(h01, floatx2v), f23 = __builtin_convertvector(h23, floatx2v);
+    const bf16x2v l01 = __builtin_convertvector(floatx2v{x.x - f01.x, x.y - f01.y}, bf16x2v);
+    const bf16x2v l23 = __builtin_convertvector(floatx2v{x.z - f23.x, x.w - f23.y}, bf16x2v);
+    hi = __builtin_bit_cast(short4v, uint2{__builtin_bit_cast(uint32_t, h01), __builtin_bit_cast(uint32_t, h23)});
+    lo = __builtin_bit_cast(short4v, uint2{__builtin_bit_cast(uint32_t, l01), __builtin_bit_cast(uint32_t, l23)});
+}
+
+// When is a distance from the bf16-split Gram pass good enough?  hi.hi + hi.lo + lo.hi misses <a,b>
+// by the dropped lo.lo and by what the two halves do not hold: at most 3 * 2^-18 |a||b| of the
+// pivot-centred vectors, and much less on average (the roundings are unbiased, so the terms of
+// the sum mostly cancel).  The distance the join compares, |a|^2 + |b|^2 - 2<a,b>, is then off by
+// at most 12 * 2^-18 N ~ 2^-14.4 N, N = max(|a - v|^2, |b - v|^2): nothing next to a distance of
+// the size of N, but as large as the distance itself for a pair that is tens of thousands of
+// times closer to each other than to the pivot (tight clusters far apart, near-duplicate rows).
+// Such a value would enter a row as it is and stay there: an id that sits in a row is never
+// offered again.  So a chosen partner whose distance is below 2^-9 N is not trusted (above, the
+// error is under 2.5 % of the distance in the worst case and a few 1e-4 of it typically); a point
+// with such a choice is appended to a list and joined again, whole, by the fp32 kernel in a
+// second launch.
+// n_a, n_b: |a - v|^2, |b - v|^2; scale: what the compared value is of |a - b|^2 (1, or 1/2 for 1 - <a,b>).
+__device__ __forceinline__ bool split_untrusted(uint32_t l_bits, float n_a, float n_b, float scale)
+{
+    const float nmax = n_a > n_b ? n_a : n_b;
+    return __uint_as_float(l_bits) < nmax * (scale * 0.001953125f);
+}
+
 // ELEM 1: uint8 rows handled as d 32-bit words, signed bytes x - 128 in LDS, integer Gram tiles
 // (v_mfma_i32_16x16x64_i8) -- see knng_join_wave.h; here wavefront w also owns the products of
 // the pivot with the member tiles w, w + 4, ... (one accumulator, a column per tile).
@@ -621,21 +655,28 @@ __device__ __forceinline__ int member_of_slot(int t, int s, int4 c)
 // the compiler parks the accumulators in 32 AGPRs on top of 152 VGPRs, which allows two; told to
 // fit three it needs 149 registers and no spill, and the join runs 28 % faster).  256 member
 // slots: one workgroup per CU by LDS (the distance block alone is 132 KB).
+#ifndef KNNG_JOIN4_OCC
+#define KNNG_JOIN4_OCC 3
+#endif
 #ifndef KNNG_JOIN3_OCC
 #define KNNG_JOIN3_OCC 4
 #endif
 template <int S16, int ELEM> struct JoinOcc {
-    static constexpr int V = S16 == 4 ? 3 : S16 == 3 ? (ELEM == 1 ? 3 : KNNG_JOIN3_OCC) : 1;
+    static constexpr int V = S16 == 4 ? KNNG_JOIN4_OCC : S16 == 3 ? (ELEM == 1 ? 3 : KNNG_JOIN3_OCC) : 1;
 };
-template <int METRIC, int S16, int DS_, bool VEC, int ELEM = 0>
+// SPLIT (fp32 rows): the centred values are stored as two bf16 halves and the Gram pass runs on
+// v_mfma_f32_16x16x16_bf16 (hi.hi + hi.lo + lo.hi), as in the wavefront kernel: with samples above
+// 16 the fp32 matrix instruction is busy for a third of the join, the bf16 one for a fifteenth.
+template <int METRIC, int S16, int DS_, bool VEC, int ELEM = 0, bool SPLIT = false>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(JoinOcc<S16, ELEM>::V, JoinOcc<S16, ELEM>::V)))
 k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
        const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl, const int4* __restrict__ plan,
        const int32_t* __restrict__ active, const u64* __restrict__ nactive_ptr,
        const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand,
-       u64* __restrict__ offers_ctr)
+       u64* __restrict__ offers_ctr, int32_t* __restrict__ redo, u64* __restrict__ redo_ctr)
 {
     static_assert(ELEM == 0 || METRIC == 0, "uint8 and fp16 rows: squared L2 only");
+    static_assert(ELEM == 0 || !SPLIT, "the bf16 split is for fp32 rows");
     using Cfg = JoinCfg<S16, DS_, ELEM>;
     using accv = typename std::conditional<ELEM == 1, intx4, floatx4>::type;
     uint32_t n_offers = 0;                                     // this thread's, summed per wavefront at exit
@@ -647,8 +688,14 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
     // [NCOLS] bits of |x_m - x_v|^2 (fp32); ELEM 1: of |x_m - 128|^2 (integer)
     uint32_t* nrm = reinterpret_cast<uint32_t*>(mh + NCOLS);
     float* thr = reinterpret_cast<float*>(nrm + NCOLS);        // [NCOLS] farthest-neighbour distance
-    uint32_t* sg = reinterpret_cast<uint32_t*>(thr + NCOLS);   // [NCOLS + 1][SIG_WORDS] row signatures
+    // row signatures, word-major [SIG_WORDS][NCOLS + 1] (column NCOLS: the pivot's): the lanes of a
+    // wavefront that read one word of different members' signatures hit different banks
+    uint32_t* sg = reinterpret_cast<uint32_t*>(thr + NCOLS);
+    constexpr int SGLD = NCOLS + 1;
     float* thr_v = reinterpret_cast<float*>(sg + (NCOLS + 1) * SIG_WORDS);  // [0] the pivot's threshold, [1] ELEM 1: its norm
+    // SPLIT: [2] "a chosen distance of this point is not trusted" (see split_untrusted), one flag per
+    // parity of the point, since a point's offers are sent while the next point is worked on
+    int* untrusted = reinterpret_cast<int*>(thr_v + 2);
     float* PZ = thr_v + 4;                                     // ELEM 1: [2][LD] pivot row, zeros
     float* dpv = PZ + 2 * LD;                                  // ELEM 1: [NCOLS] |x_m - x_v|^2
     if (ELEM == 1 && threadIdx.x < LD) PZ[LD + threadIdx.x] = 0.0f;
@@ -726,6 +773,38 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
     int rid_n = 0;
     if (v_nx >= 0) { rc_n = plan[v_nx]; rid_n = load_slot(v_nx); }
 
+    // Offers of the previous point, sent one point late: right after the last Gram pass, so that
+    // their round trip to memory runs under the norm / distance-block / scan work, which never
+    // waits for memory.  (Sent right after the scan they would be waited for at the very next use
+    // of prefetched data: loads and atomics share one in-order counter.)  One offer per thread and
+    // scan pass: member id, partner id (-1: none), distance bits.
+    constexpr int NPASS = (NCOLS * OFFERS_PER_MEMBER + 255) / 256;
+    int pend_mid[NPASS], pend_pid[NPASS];
+    uint32_t pend_l[NPASS];
+#pragma unroll
+    for (int ps = 0; ps < NPASS; ++ps) { pend_mid[ps] = 0; pend_pid[ps] = -1; pend_l[ps] = 0u; }
+    int v_pend = -1;                                           // the point the pending offers belong to
+    // `flag`: the pending point's entry of `untrusted` (its scan lies at least one barrier back)
+    auto send_offers = [&](const int* flag) {
+        if constexpr (SPLIT) {
+            if (v_pend >= 0 && *flag != 0) {
+                // left to the fp32 kernel, which runs over the points listed here after this launch
+#pragma unroll
+                for (int ps = 0; ps < NPASS; ++ps) pend_pid[ps] = -1;
+                if (tid == 0) redo[atomicAdd(redo_ctr, 1ull)] = (int32_t)v_pend;
+            }
+        }
+#pragma unroll
+        for (int ps = 0; ps < NPASS; ++ps) {
+            if (pend_pid[ps] >= 0) {
+                const uint32_t slot = below(hash32((uint32_t)pend_pid[ps]), (uint32_t)C);
+                ++n_offers;
+                atomicMin(&cand[(int64_t)pend_mid[ps] * C + slot], pack_key(__uint_as_float(pend_l[ps]), pend_pid[ps], 1));
+                pend_pid[ps] = -1;
+            }
+        }
+    };
+
     for (;;) {
         const int* mid = midbuf + cur * NCOLS;
         const int nNew = P.nNew, nTot = P.nTot, nfn = P.nfn, nfo = P.nfo;
@@ -768,16 +847,21 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 // all 256 threads hold members: no thread is left for the pivot (with 128 member
                 // slots thread 128 holds it, and must be the only writer of its threshold)
                 if (NCOLS == 256 && tid == NCOLS - 1 && nTot == NCOLS) thr_v[0] = 0.0f;
+                if (SPLIT && tid == 0) untrusted[cur] = 0;
                 if (tid == nTot) {
                     thr_v[0] = thr_r;
-                    reinterpret_cast<uint4*>(sg)[2 * NCOLS] = sg_r0;
-                    reinterpret_cast<uint4*>(sg)[2 * NCOLS + 1] = sg_r1;
+                    sg[0 * SGLD + NCOLS] = sg_r0.x; sg[1 * SGLD + NCOLS] = sg_r0.y;
+                    sg[2 * SGLD + NCOLS] = sg_r0.z; sg[3 * SGLD + NCOLS] = sg_r0.w;
+                    sg[4 * SGLD + NCOLS] = sg_r1.x; sg[5 * SGLD + NCOLS] = sg_r1.y;
+                    sg[6 * SGLD + NCOLS] = sg_r1.z; sg[7 * SGLD + NCOLS] = sg_r1.w;
                 }
                 if (tid < nTot) {
                     thr[tid] = thr_r;
                     mh[tid] = int2{my_member, (int)sig_bit(my_member, iter)};
-                    reinterpret_cast<uint4*>(sg)[2 * tid] = sg_r0;
-                    reinterpret_cast<uint4*>(sg)[2 * tid + 1] = sg_r1;
+                    sg[0 * SGLD + tid] = sg_r0.x; sg[1 * SGLD + tid] = sg_r0.y;
+                    sg[2 * SGLD + tid] = sg_r0.z; sg[3 * SGLD + tid] = sg_r0.w;
+                    sg[4 * SGLD + tid] = sg_r1.x; sg[5 * SGLD + tid] = sg_r1.y;
+                    sg[6 * SGLD + tid] = sg_r1.z; sg[7 * SGLD + tid] = sg_r1.w;
                 }
             }
             if (sm.col_ok) {
@@ -791,6 +875,13 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                         else if (ELEM == 2) x = sub_h2x4(x, pv);
                         else { x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w; }
                         if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
+                        if constexpr (SPLIT) {
+                            // the piece keeps its place: two words of hi halves, then two of lo halves
+                            short4v hi, lo;
+                            split_bf16(x, hi, lo);
+                            const uint2 h2 = __builtin_bit_cast(uint2, hi), l2 = __builtin_bit_cast(uint2, lo);
+                            x = float4{__uint_as_float(h2.x), __uint_as_float(h2.y), __uint_as_float(l2.x), __uint_as_float(l2.y)};
+                        }
                         if (sm.rsub + i * sm.RP < nTot) *reinterpret_cast<float4*>(xdst + i * sm.RP * LD) = x;
                     }
                 }
@@ -831,6 +922,14 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                             const half8v a = *reinterpret_cast<const half8v*>(xa + kk);
                             const half8v b = *reinterpret_cast<const half8v*>(xb + kk);
                             acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[q], 0, 0, 0);
+                        } else if constexpr (SPLIT) {
+                            const uint4 a = *reinterpret_cast<const uint4*>(xa + kk);
+                            const uint4 b = *reinterpret_cast<const uint4*>(xb + kk);
+                            const short4v ah = __builtin_bit_cast(short4v, uint2{a.x, a.y}), al = __builtin_bit_cast(short4v, uint2{a.z, a.w});
+                            const short4v bh = __builtin_bit_cast(short4v, uint2{b.x, b.y}), bl = __builtin_bit_cast(short4v, uint2{b.z, b.w});
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bh, acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bl, acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(al, bh, acc[q], 0, 0, 0);
                         } else {
                             const float4 a = *reinterpret_cast<const float4*>(xa + kk);
                             const float4 b = *reinterpret_cast<const float4*>(xb + kk);
@@ -872,6 +971,7 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             lds_barrier();                                 // slab consumed by every wavefront
         }
 
+        send_offers(untrusted + (cur ^ 1));                // the previous point's
         // The pivot's reverse members hold v in their rows, so |x_m - x_v|^2 is already known:
         // offer them to v itself (closes v<-m edges into v->m without an extra distance).
         auto reverse_offers = [&]() {
@@ -884,7 +984,7 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 l = nonneg(l);
                 const int2 me = mh[m];
                 const uint32_t h = (uint32_t)me.y;
-                const uint32_t vw = sg[NCOLS * SIG_WORDS + (h >> 5)];
+                const uint32_t vw = sg[(h >> 5) * SGLD + NCOLS];
                 if (l < thr_v[0] && !((vw >> (h & 31u)) & 1u)) {
                     const uint32_t slot = below(hash32((uint32_t)me.x), (uint32_t)C);
                     ++n_offers;
@@ -938,32 +1038,54 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
         // residue class (partner index mod LPM) and offers the closest of its class that beats
         // the member's threshold and is not in the member's signature (branch-free scan)
         constexpr int LPM = OFFERS_PER_MEMBER;
-        for (int m0 = 0; m0 < nTot; m0 += 256 / LPM) {
-            const int m = m0 + tid / LPM, sub = tid % LPM;
+#pragma unroll
+        for (int ps = 0; ps < NPASS; ++ps) {
+            const int m = ps * (256 / LPM) + tid / LPM, sub = tid % LPM;
             if (m >= nTot) continue;
             const int myid = mh[m].x;
-            const uint32_t* msig = sg + m * SIG_WORDS;
+            const uint32_t* msig = sg + m;
             const uint32_t mythr = __float_as_uint(thr[m]);    // non-negative floats order as integers
-            uint32_t best_l = 0xffffffffu, best_j = 0;
+            uint32_t best_l = mythr, best_j = 0xffffffffu;
             const bool isnew = m < nNew;
             const int jend = isnew ? nTot : nNew;
-            for (int j = sub; j < jend; j += LPM) {
-                const bool tr = isnew && ((j >> 4) < (m >> 4));
-                const uint32_t l = __float_as_uint(tr ? D[j * LDD + m] : D[(isnew ? m : j) * LDD + (isnew ? j : m)]);
-                const int2 pj = mh[j];
-                const uint32_t h = (uint32_t)pj.y;
-                const uint32_t known = (msig[h >> 5] >> (h & 31u)) & 1u;
-                const bool ok = (l < mythr) && (l < best_l) && (pj.x != myid) && !known;
-                best_l = ok ? l : best_l;
-                best_j = ok ? (uint32_t)j : best_j;
+            // Four partners of the lane's class per step: their distances and records are read
+            // together, then their signature words -- two LDS round trips per step instead of
+            // three per partner.  D[m][j] sits at [lower tile][higher tile].
+            for (int j0 = sub; j0 < jend; j0 += 4 * LPM) {
+                uint32_t l[4];
+                int2 pj[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int j = j0 + u * LPM;
+                    const bool in = j < jend;
+                    const int jj = in ? j : sub;               // any valid partner: its cell is not used
+                    const bool tr = isnew && ((jj >> 4) < (m >> 4));
+                    const uint32_t v = __float_as_uint(tr ? D[jj * LDD + m] : D[(isnew ? m : jj) * LDD + (isnew ? jj : m)]);
+                    l[u] = in ? v : 0xffffffffu;
+                    pj[u] = mh[jj];
+                }
+                uint32_t wv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) wv[u] = msig[((uint32_t)pj[u].y >> 5) * SGLD];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t known = (wv[u] >> ((uint32_t)pj[u].y & 31u)) & 1u;
+                    const bool ok = (l[u] < best_l) & (pj[u].x != myid) & (known == 0u);
+                    best_l = ok ? l[u] : best_l;
+                    best_j = ok ? (uint32_t)(j0 + u * LPM) : best_j;
+                }
             }
-            if (best_l != 0xffffffffu) {
-                const int pid = mh[best_j].x;
-                const uint32_t slot = below(hash32((uint32_t)pid), (uint32_t)C);
-                ++n_offers;
-                atomicMin(&cand[(int64_t)myid * C + slot], pack_key(__uint_as_float(best_l), pid, 1));
+            if (best_j != 0xffffffffu) {
+                pend_mid[ps] = myid;
+                pend_pid[ps] = mh[best_j].x;
+                pend_l[ps] = best_l;
+                if constexpr (SPLIT) {
+                    if (split_untrusted(best_l, __uint_as_float(nrm[m]), __uint_as_float(nrm[best_j]), METRIC == 1 ? 0.5f : 1.0f))
+                        untrusted[cur] = 1;
+                }
             }
         }
+        v_pend = (int)v;
         // ---- advance to the next point of this workgroup
         if (v_nx < 0) break;
         lds_barrier();                                     // D and the member arrays are free again
@@ -974,6 +1096,8 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
         P = Pn;
         cur ^= 1;
     }
+    lds_barrier();                                         // the last point's flag is complete
+    send_offers(untrusted + cur);                          // the last point's
     for (int o = 32; o > 0; o >>= 1) n_offers += __shfl_xor(n_offers, o);
     if ((tid & 63) == 0 && n_offers) atomicAdd(offers_ctr, (u64)n_offers);
 }
@@ -1145,7 +1269,7 @@ k_finalize_scalar(const float* __restrict__ pts, int64_t n, int d, int K, int Kp
 struct BuildPlan {
     int K, C, s, B, S16, max_iters;
     float rho, delta;
-    uint64_t off_G, off_cand, off_new, off_old, off_rev, off_cnt, off_plan, off_active, off_worst, off_sig, off_ctr, total;
+    uint64_t off_G, off_cand, off_new, off_old, off_rev, off_cnt, off_plan, off_active, off_redo, off_worst, off_sig, off_ctr, total;
 };
 
 static bool make_plan(int64_t n, int32_t d, int32_t k, const knng_params_t* p, BuildPlan* bp)
@@ -1176,6 +1300,7 @@ static bool make_plan(int64_t n, int32_t d, int32_t k, const knng_params_t* p, B
     bp->off_cnt = take((uint64_t)n * 8);
     bp->off_plan = take((uint64_t)n * 16);
     bp->off_active = take((uint64_t)n * 4);
+    bp->off_redo = take((uint64_t)n * 4);              // points a split join kernel leaves to the fp32 kernel
     bp->off_worst = take((uint64_t)n * 4);
     bp->off_sig = take((uint64_t)n * SIG_WORDS * 4);
     bp->off_ctr = take(256);
@@ -1193,13 +1318,14 @@ struct JoinArgs {
     const u64* nactive; const float* worst; const uint32_t* sig; u64* cand; u64* offers;
     int num_cu; int64_t n;
     int* blocks_per_cu;       // resident workgroups per CU of this build's join kernel; 0 = not yet asked
+    int32_t* redo; u64* redo_ctr;   // split kernels: the points left to the fp32 kernel, and their number
 };
 
-template <int METRIC, int S16, int DS, bool VEC, int ELEM = 0>
+template <int METRIC, int S16, int DS, bool VEC, int ELEM = 0, bool SPLIT = false>
 static hipError_t launch_join_k(hipStream_t st, const JoinArgs& a)
 {
     const int lds = JoinCfg<S16, DS, ELEM>::LDS_BYTES;
-    auto kern = k_join<METRIC, S16, DS, VEC, ELEM>;
+    auto kern = k_join<METRIC, S16, DS, VEC, ELEM, SPLIT>;
     // asked once per build, on the build's device (a build runs one join kernel): the attribute is
     // per device, and nothing is kept between calls
     if (*a.blocks_per_cu == 0) {
@@ -1214,7 +1340,7 @@ static hipError_t launch_join_k(hipStream_t st, const JoinArgs& a)
     int64_t grid = (int64_t)a.num_cu * *a.blocks_per_cu;
     if (grid > a.n) grid = a.n;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a.pts, a.d, a.C, a.s, a.iter, a.newl,
-                       a.oldl, a.plan, a.active, a.nactive, a.worst, a.sig, a.cand, a.offers);
+                       a.oldl, a.plan, a.active, a.nactive, a.worst, a.sig, a.cand, a.offers, a.redo, a.redo_ctr);
     return hipGetLastError();
 }
 
@@ -1237,10 +1363,13 @@ static hipError_t launch_join_w(hipStream_t st, const JoinArgs& a)
     int64_t grid = (int64_t)a.num_cu * *a.blocks_per_cu;
     if (grid > (a.n + 3) / 4) grid = (a.n + 3) / 4;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a.pts, a.d, a.C, a.s, a.iter, a.newl,
-                       a.oldl, a.plan, a.active, a.nactive, a.worst, a.sig, a.cand, a.offers);
+                       a.oldl, a.plan, a.active, a.nactive, a.worst, a.sig, a.cand, a.offers, a.redo, a.redo_ctr);
     return hipGetLastError();
 }
 
+#ifndef KNNG_JOINK_SPLIT_MIN_D
+#define KNNG_JOINK_SPLIT_MIN_D 64     // fp32 rows from this length on: bf16-split Gram pass in the workgroup join
+#endif
 #ifndef KNNG_SPLIT_MIN_D
 #define KNNG_SPLIT_MIN_D 256      // fp32 rows from this length on: bf16-split Gram pass in the wavefront join
 #endif
@@ -1256,18 +1385,47 @@ static hipError_t launch_join_compact(hipStream_t st, bool vec, int S16, const J
     return vec ? launch_join_k<0, 8, 32, true, ELEM>(st, a) : launch_join_k<0, 8, 32, false, ELEM>(st, a);
 }
 
+// the fp32 kernel over the points a split kernel did not trust itself with (the launch reads their
+// number on the device; usually none)
+static JoinArgs redo_args(const JoinArgs& a)
+{
+    JoinArgs b = a;
+    b.active = a.redo;
+    b.nactive = a.redo_ctr;
+    b.redo = nullptr;
+    b.redo_ctr = nullptr;
+    b.blocks_per_cu = a.blocks_per_cu + 1;
+    return b;
+}
+
 template <int METRIC>
 static hipError_t launch_join(hipStream_t st, bool vec, int S16, const JoinArgs& a)
 {
     // s <= 16: one wavefront per point; larger samples: one workgroup per point
-    // long fp32 rows: the Gram pass on the bf16 matrix instructions (two halves per value)
+    // long fp32 rows: the Gram pass on the bf16 matrix instructions (two halves per value), then the
+    // fp32 kernel for the points whose choices the narrow pass could not be trusted with
     const bool split = vec && a.d >= KNNG_SPLIT_MIN_D;
-    if (S16 == 1 && split) return launch_join_w<METRIC, 1, true, 0, true>(st, a);
-    if (S16 == 2 && split) return launch_join_w<METRIC, 2, true, 0, true>(st, a);
+    // samples above 16 (the workgroup kernel): from KNNG_JOINK_SPLIT_MIN_D coordinates on
+    const bool ksplit = vec && a.d >= KNNG_JOINK_SPLIT_MIN_D;
+    hipError_t e;
+    if (S16 == 1 && split) {
+        if ((e = launch_join_w<METRIC, 1, true, 0, true>(st, a)) != hipSuccess) return e;
+        return launch_join_w<METRIC, 1, true>(st, redo_args(a));
+    }
+    if (S16 == 2 && split) {
+        if ((e = launch_join_w<METRIC, 2, true, 0, true>(st, a)) != hipSuccess) return e;
+        return launch_join_w<METRIC, 2, true>(st, redo_args(a));
+    }
     if (S16 == 1) return vec ? launch_join_w<METRIC, 1, true>(st, a) : launch_join_w<METRIC, 1, false>(st, a);
     if (S16 == 2) return vec ? launch_join_w<METRIC, 2, true>(st, a) : launch_join_w<METRIC, 2, false>(st, a);
-#define KNNG_JOIN_CASE(S, DSV)                                                      \
-    return vec ? launch_join_k<METRIC, S, DSV, true>(st, a) : launch_join_k<METRIC, S, DSV, false>(st, a)
+#define KNNG_JOIN_CASE(S, DSV)                                                                   \
+    do {                                                                                         \
+        if (ksplit) {                                                                            \
+            if ((e = launch_join_k<METRIC, S, DSV, true, 0, true>(st, a)) != hipSuccess) return e; \
+            return launch_join_k<METRIC, S, DSV, true>(st, redo_args(a));                        \
+        }                                                                                        \
+        return vec ? launch_join_k<METRIC, S, DSV, true>(st, a) : launch_join_k<METRIC, S, DSV, false>(st, a); \
+    } while (0)
     switch (S16) {
     case 3: KNNG_JOIN_CASE(3, 64);
     case 4: KNNG_JOIN_CASE(4, 64);
@@ -1329,9 +1487,10 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
     uint32_t* rev = reinterpret_cast<uint32_t*>(ws + bp.off_rev);
     int4* plan = reinterpret_cast<int4*>(ws + bp.off_plan);
     int32_t* active = reinterpret_cast<int32_t*>(ws + bp.off_active);
+    int32_t* redo = reinterpret_cast<int32_t*>(ws + bp.off_redo);
     float* worst = reinterpret_cast<float*>(ws + bp.off_worst);
     uint32_t* sig = reinterpret_cast<uint32_t*>(ws + bp.off_sig);
-    u64* ctr = reinterpret_cast<u64*>(ws + bp.off_ctr);      // [0] updates [1] rows gathered [2] active [3] pairs [4] offers [5] occupied slots
+    u64* ctr = reinterpret_cast<u64*>(ws + bp.off_ctr);      // [0] updates [1] rows gathered [2] active [3] pairs [4] offers [5] occupied slots [6] points left to the fp32 join
     knng_stats_t* stats = params->stats_host;
     const bool vec = (d % (elem == 1 ? 16 : elem == 2 ? 8 : 4) == 0) && ((reinterpret_cast<uintptr_t>(points_dev) & 15u) == 0);
     const unsigned row_blocks = (unsigned)((n + 3) / 4);
@@ -1340,7 +1499,7 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
 
     int rc = KNNG_OK;
     int num_cu = 0;
-    int join_blocks_per_cu = 0;
+    int join_blocks_per_cu[2] = {0, 0};              // [1]: the fp32 kernel behind a split kernel
     u64* host_ctr = nullptr;
     bool own_ctr = false;
     // events: [0] start, [1] after init, then 4 per iteration (sample, join start, join end, merge), last = end
@@ -1405,14 +1564,14 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
         if (rec) HIPCHK(record(2 + 4 * it));
         if (stats && !more) HIPCHK(record(n_ev - 2));
         if (it > 0) {
-            HIPCHK(hipMemcpyAsync(host_ctr, ctr, 48, hipMemcpyDeviceToHost, st));
-            HIPCHK(hipMemsetAsync(ctr, 0, 48, st));
+            HIPCHK(hipMemcpyAsync(host_ctr, ctr, 56, hipMemcpyDeviceToHost, st));
+            HIPCHK(hipMemsetAsync(ctr, 0, 56, st));
             HIPCHK(hipStreamSynchronize(st));
             if (stats && it - 1 < max_rec) {
                 stats->updates[it - 1] = host_ctr[0];
                 stats->join_rows[it - 1] = host_ctr[1];
             }
-            if (stats) { stats->pairs += host_ctr[3]; stats->offers += host_ctr[4]; stats->cand_kept += host_ctr[5]; }
+            if (stats) { stats->pairs += host_ctr[3]; stats->offers += host_ctr[4]; stats->cand_kept += host_ctr[5]; stats->joined += host_ctr[2]; stats->rejoined += host_ctr[6]; }
             if ((double)host_ctr[0] < stop_below) { converged = 1; break; }
         }
         if (!more) break;
@@ -1423,7 +1582,7 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
         if (rec) HIPCHK(record(3 + 4 * it));
         {
             JoinArgs ja{points_dev, elem == 1 ? d / 4 : elem == 2 ? d / 2 : d, bp.C, bp.s, (uint32_t)it, newl, oldl, plan, active, ctr + 2,
-                        worst, sig, cand, ctr + 4, num_cu, n, &join_blocks_per_cu};
+                        worst, sig, cand, ctr + 4, num_cu, n, join_blocks_per_cu, redo, ctr + 6};
             if (elem == 1) HIPCHK(launch_join_compact<1>(st, vec, bp.S16, ja));
             else if (elem == 2) HIPCHK(launch_join_compact<2>(st, vec, bp.S16, ja));
             else if (metric == 0) HIPCHK(launch_join<0>(st, vec, bp.S16, ja));

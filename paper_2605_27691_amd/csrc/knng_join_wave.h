@@ -50,8 +50,9 @@
 // (a 16-byte piece = two words of hi halves, then two of lo halves: the same bytes, the same LDS
 // addresses and bank pattern as the fp32 slab), and the Gram pass
 // takes <a,b> as hi.hi + hi.lo + lo.hi on v_mfma_f32_16x16x16_bf16 -- three instructions of 8
-// cycles where fp32 needs four of 32.  The products miss <a,b> by less than 2^-13 |a||b| of the
-// centred vectors; like the fp16 kernel's rounding this only touches the ranking of candidates.
+// cycles where fp32 needs four of 32.  The products miss <a,b> by at most 3 * 2^-18 |a||b| of the
+// centred vectors; a choice that this could have decided is not made here: the point goes to a
+// list the fp32 kernel works off afterwards (split_untrusted in knng_build.hip).
 #pragma once
 
 namespace knng {
@@ -84,18 +85,6 @@ template <int S16, int ELEM = 0> struct WaveCfg {
 // in 168 registers, and the fp16 kernel spills 39 there).
 template <int S16, int ELEM> struct WaveOcc { static constexpr int V = (ELEM != 0 && S16 == 2) ? 2 : KNNG_WAVE_OCC; };
 
-// Two bf16 halves of four fp32 values: hi = the upper 16 bits (truncation), lo = the upper 16 bits of
-// x - hi (that difference is exact in fp32).  hi + lo misses x by less than 2^-14 |x|.
-__device__ __forceinline__ void split_bf16(float4 x, short4v& hi, short4v& lo)
-{
-    const uint32_t b0 = __float_as_uint(x.x), b1 = __float_as_uint(x.y), b2 = __float_as_uint(x.z), b3 = __float_as_uint(x.w);
-    const float l0 = x.x - __uint_as_float(b0 & 0xffff0000u), l1 = x.y - __uint_as_float(b1 & 0xffff0000u);
-    const float l2 = x.z - __uint_as_float(b2 & 0xffff0000u), l3 = x.w - __uint_as_float(b3 & 0xffff0000u);
-    hi = __builtin_bit_cast(short4v, uint2{__builtin_amdgcn_perm(b1, b0, 0x07060302u), __builtin_amdgcn_perm(b3, b2, 0x07060302u)});
-    lo = __builtin_bit_cast(short4v, uint2{__builtin_amdgcn_perm(__float_as_uint(l1), __float_as_uint(l0), 0x07060302u),
-                                           __builtin_amdgcn_perm(__float_as_uint(l3), __float_as_uint(l2), 0x07060302u)});
-}
-
 template <int METRIC, int S16, bool VEC, int ELEM = 0, bool SPLIT = false>
 __global__ void __launch_bounds__(256)
 __attribute__((amdgpu_waves_per_eu(WaveOcc<S16, ELEM>::V, WaveOcc<S16, ELEM>::V)))
@@ -103,7 +92,7 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl, const int4* __restrict__ plan,
             const int32_t* __restrict__ active, const u64* __restrict__ nactive_ptr,
             const float* __restrict__ worst, const uint32_t* __restrict__ sig, u64* __restrict__ cand,
-            u64* __restrict__ offers_ctr)
+            u64* __restrict__ offers_ctr, int32_t* __restrict__ redo, u64* __restrict__ redo_ctr)
 {
     // ELEM 1 / 2: pts points at uint8 / fp16 rows of 4 d bytes, d counts 32-bit words
     static_assert(ELEM == 0 || METRIC == 0, "uint8 and fp16 rows: squared L2 only");
@@ -587,6 +576,22 @@ k_join_wave(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             }
 #pragma unroll
             for (int u = NCLS; u < 4; ++u) pend_j |= 0xffu << (8 * u);
+            if constexpr (SPLIT) {
+                // Is every chosen distance good enough?  (See split_untrusted.)  If not the point is
+                // left to the fp32 kernel, which runs over the points listed here after this launch,
+                // and none of its offers is sent from here.
+                bool bad = false;
+                const float n_m = __uint_as_float(nrm[m & (NCOLS - 1)]);
+#pragma unroll
+                for (int u = 0; u < NCLS; ++u) {
+                    const float n_j = __uint_as_float(nrm[bj[u] & (NCOLS - 1)]);
+                    bad = bad | ((bj[u] != 0xffffffffu) & split_untrusted(bl[u], n_m, n_j, METRIC == 1 ? 0.5f : 1.0f));
+                }
+                if (__ballot(bad) != 0ull) {
+                    pend_j = 0xffffffffu;
+                    if (lane == 0) redo[atomicAdd(redo_ctr, 1ull)] = (int32_t)v;
+                }
+            }
         }
         // ---- advance
         if (v_nx < 0) break;

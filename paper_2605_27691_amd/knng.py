@@ -31,7 +31,9 @@ class Stats(ctypes.Structure):
                 ("ms_finalize", ctypes.c_float), ("ms_total", ctypes.c_float),
                 ("offers", ctypes.c_uint64),
                 ("pairs", ctypes.c_uint64),
-                ("cand_kept", ctypes.c_uint64)]
+                ("cand_kept", ctypes.c_uint64),
+                ("joined", ctypes.c_uint64),
+                ("rejoined", ctypes.c_uint64)]
 
 
 class Params(ctypes.Structure):
@@ -200,7 +202,7 @@ def _build_graph(entry, dtype, points, k, metric, k_build, rho, delta, max_iters
                  "join_rows": list(st.join_rows[:it]), "ms_init": st.ms_init,
                  "ms_sample": st.ms_sample, "ms_join": st.ms_join, "ms_merge": st.ms_merge,
                  "ms_finalize": st.ms_finalize, "ms_total": st.ms_total,
-                 "offers": int(st.offers), "pairs": int(st.pairs), "cand_kept": int(st.cand_kept)}
+                 "offers": int(st.offers), "pairs": int(st.pairs), "cand_kept": int(st.cand_kept), "joined": int(st.joined), "rejoined": int(st.rejoined)}
     return ids_out, dists_out, stats
 
 

@@ -58,6 +58,18 @@ def test_f16_build_against_the_oracle(n, d, k, kb, rho):
     _check(x16, k, ids, dists)
 
 
+@pytest.mark.parametrize("d,spread,kb", [(256, 3e-3, 32), (960, 1e-2, 32), (128, 1e-2, 64)])
+def test_f16_tight_clusters_far_apart(d, spread, kb):
+    # small distances next to large ones (the hazard of Sec. 5.3.2) through the fp16 Gram pass:
+    # rows centred in fp16 on a point of another cluster carry errors of the size of the distances
+    # inside a cluster, but nearly the same error for rows that are nearly the same, so the
+    # differences that decide survive; measured, not assumed: the recall bar holds
+    from test_gpu_parity import _tight_far_clusters
+    x16 = _tight_far_clusters(4000, d, False, seed=d, spread=spread).astype(np.float16)
+    ids, dists, _ = knng.knng_build_knn_graph_f16(_gpu(x16), 16, 0, k_build=kb, rho=0.5, seed=8)
+    _check(x16, 16, ids, dists, min_recall=0.95)
+
+
 def test_f16_small_and_large_magnitudes():
     # values near the bottom and the top of the fp16 range: subnormals convert exactly, squared
     # differences of large values stay finite in the fp32 accumulators
