@@ -24,6 +24,13 @@
  *   - Distances (Sec. 2.1: sigma >= 0, smaller = more similar):
  *       KNNG_METRIC_L2SQ     sum_t (a_t - b_t)^2
  *       KNNG_METRIC_IP_UNIT  max(0, 1 - <a,b>); the caller guarantees unit rows
+ *       KNNG_METRIC_COSINE   max(0, 1 - <a,b> / sqrt(|a|^2 |b|^2)) for rows of any length (a
+ *                            similarity turned into a dissimilarity, Sec. 2.1); a zero row is at
+ *                            distance 1 from every row.  <a,b>, |a|^2 and |b|^2 are each
+ *                            accumulated as below; quotient and root in fp64.  Accepted by
+ *                            knng_build_knn_graph and knng_brute_knn[_base] (fp32 rows); the
+ *                            build needs n*d*4 more bytes of workspace for unit-length copies
+ *                            of the rows, which the joins work on.
  *     Every distance WRITTEN to an output is accumulated in fp64 over
  *     t = 0..d-1 in index order with fused multiply-add and rounded once to
  *     fp32.  Inputs must be finite; NaN/Inf inputs give unspecified ordering
@@ -54,7 +61,7 @@ enum {
     KNNG_ETOOLARGE = -4    /* more input than an entry point with fixed scratch memory takes */
 };
 
-enum { KNNG_METRIC_L2SQ = 0, KNNG_METRIC_IP_UNIT = 1 };
+enum { KNNG_METRIC_L2SQ = 0, KNNG_METRIC_IP_UNIT = 1, KNNG_METRIC_COSINE = 2 };
 
 #define KNNG_MAX_K 64            /* largest k / k_build / cand_cap */
 #define KNNG_STATS_MAX_ITERS 128 /* per-iteration records kept in knng_stats_t */
@@ -116,8 +123,10 @@ typedef struct knng_params {
                                  its own, which costs a page-locked allocation per build       */
 } knng_params_t;
 
-/* Device scratch needed by knng_build_knn_graph for these sizes (0 on bad arguments). */
+/* Device scratch needed by knng_build_knn_graph for these sizes (0 on bad arguments).
+ * For KNNG_METRIC_COSINE add knng_build_cosine_extra_bytes(n, d). */
 uint64_t knng_build_workspace_bytes(int64_t n, int32_t d, int32_t k, const knng_params_t *params);
+uint64_t knng_build_cosine_extra_bytes(int64_t n, int32_t d);
 
 /*
  * Approximate k-NN graph of the n points (Sec. 3.1, 3.1.1).

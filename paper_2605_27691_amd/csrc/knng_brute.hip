@@ -37,7 +37,7 @@ template <int METRIC>
 __global__ void __launch_bounds__(256)
 k_brute(const float* __restrict__ pts, int64_t n, int d, int k,
         const int32_t* __restrict__ query_rows, int64_t nq, int64_t base_chunk, int nsplit,
-        u64* __restrict__ part)
+        u64* __restrict__ part, const double* __restrict__ nrm64)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float* QT = reinterpret_cast<float*>(smem);            // [BDC][BLD]
@@ -130,7 +130,10 @@ k_brute(const float* __restrict__ pts, int64_t n, int d, int k,
             for (int j = 0; j < 4; ++j) {
                 const int64_t b = b0 + 4 * tx + j;
                 if (qr >= 0 && b < b_end && b != (int64_t)qr) {
-                    const u64 key = pack_key(exact_finish<METRIC>(acc[i][j]), (int)b, 0);
+                    // METRIC 2: nrm64 holds every row's |x|^2 as the sequential fp64 chain gives it
+                    const float dist = METRIC == 2 ? cosine_finish(acc[i][j], nrm64[qr], nrm64[b])
+                                                   : exact_finish<METRIC == 2 ? 1 : METRIC>(acc[i][j]);
+                    const u64 key = pack_key(dist, (int)b, 0);
                     if (key < t) {
                         int pos = atomicAdd(&pcnt[qi], 1);
                         pend[qi * BT + pos] = key;
@@ -181,6 +184,19 @@ k_row_norms(const float* __restrict__ pts, int64_t n, int d, float* __restrict__
     acc += __shfl_xor(acc, 2);
     acc += __shfl_xor(acc, 4);
     if (row < n && sub == 0) nrm[row] = (float)acc;
+}
+
+// |x_i|^2 of every point as the distance recipe's own chain gives it: fp64, coordinates in index
+// order, fused multiply-add, no rounding to fp32 (general cosine).  One lane per row.
+__global__ void __launch_bounds__(256)
+k_row_norms_exact(const float* __restrict__ pts, int64_t n, int d, double* __restrict__ nrm64)
+{
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= n) return;
+    const float* x = pts + row * d;
+    double acc = 0.0;
+    for (int t = 0; t < d; ++t) acc = exact_step<2>(acc, x[t], x[t]);
+    nrm64[row] = acc;
 }
 
 constexpr int MLD = BDC + 4;      // row stride of a row-major slab: conflict-free 16-byte reads
@@ -445,8 +461,8 @@ extern "C" __attribute__((visibility("default"))) uint64_t knng_brute_workspace_
 {
     if (n < 2 || d < 1 || k < 1 || k > KNNG_MAX_K || (int64_t)k > n - 1 || nq < 0) return 0;
     uint64_t b = (uint64_t)nq * (uint64_t)brute_nsplit(n, nq) * (uint64_t)k * 8u;
-    b = (b + 255u) & ~255ull;                     // partial lists, then |x|^2 of every point
-    return b + (((uint64_t)n * 4u + 255u) & ~255ull);
+    b = (b + 255u) & ~255ull;                     // partial lists, then |x|^2 of every point (fp32, or fp64 for the cosine)
+    return b + (((uint64_t)n * 8u + 255u) & ~255ull);
 }
 
 // candidates: the first n_base of the n_all points; query rows: any of the n_all points
@@ -455,7 +471,8 @@ static int brute_impl(const float* points_dev, int64_t n_all, int64_t n, int32_t
                       void* workspace_dev, uint64_t workspace_bytes, void* stream)
 {
     if (!points_dev || n < 2 || n > n_all || n_all > 2147483647LL || d < 1 || k < 1 || k > KNNG_MAX_K ||
-        (int64_t)k > n - 1 || nq < 0 || (metric != KNNG_METRIC_L2SQ && metric != KNNG_METRIC_IP_UNIT))
+        (int64_t)k > n - 1 || nq < 0 ||
+        (metric != KNNG_METRIC_L2SQ && metric != KNNG_METRIC_IP_UNIT && metric != KNNG_METRIC_COSINE))
         return KNNG_EINVAL;
     if (nq == 0) return KNNG_OK;
     if (!ids_out_dev || !dists_out_dev) return KNNG_EINVAL;
@@ -472,7 +489,17 @@ static int brute_impl(const float* points_dev, int64_t n_all, int64_t n, int32_t
     u64* part = static_cast<u64*>(workspace_dev);
     hipError_t e;
     const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(points_dev) & 15u) == 0);
-    if (vec) {
+    if (metric == KNNG_METRIC_COSINE) {
+        // every pair in fp64 (the 4x4 register blocks of k_brute), norms from the exact chain
+        const uint64_t part_bytes = ((uint64_t)nq * (uint64_t)nsplit * (uint64_t)k * 8u + 255u) & ~255ull;
+        double* nrm64 = reinterpret_cast<double*>(static_cast<unsigned char*>(workspace_dev) + part_bytes);
+        hipLaunchKernelGGL(k_row_norms_exact, dim3((unsigned)((n_all + 255) / 256)), dim3(256), 0, st, points_dev, n_all, d, nrm64);
+        if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e, "k_row_norms_exact launch");
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_brute<2>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return set_hip_error(e, "hipFuncSetAttribute(k_brute)");
+        hipLaunchKernelGGL(k_brute<2>, dim3(qtiles, (unsigned)nsplit), dim3(256), lds, st, points_dev, n, d, k,
+                           query_rows_dev, nq, chunk, nsplit, part, nrm64);
+    } else if (vec) {
         const uint64_t part_bytes = ((uint64_t)nq * (uint64_t)nsplit * (uint64_t)k * 8u + 255u) & ~255ull;
         float* nrm = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace_dev) + part_bytes);
         hipLaunchKernelGGL(k_row_norms, dim3((unsigned)((n_all * 8 + 255) / 256)), dim3(256), 0, st, points_dev, n_all, d, nrm);
@@ -496,13 +523,13 @@ static int brute_impl(const float* points_dev, int64_t n_all, int64_t n, int32_t
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return set_hip_error(e, "hipFuncSetAttribute(k_brute)");
         hipLaunchKernelGGL(k_brute<0>, dim3(qtiles, (unsigned)nsplit), dim3(256), lds, st, points_dev, n, d, k,
-                           query_rows_dev, nq, chunk, nsplit, part);
+                           query_rows_dev, nq, chunk, nsplit, part, static_cast<const double*>(nullptr));
     } else {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_brute<1>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return set_hip_error(e, "hipFuncSetAttribute(k_brute)");
         hipLaunchKernelGGL(k_brute<1>, dim3(qtiles, (unsigned)nsplit), dim3(256), lds, st, points_dev, n, d, k,
-                           query_rows_dev, nq, chunk, nsplit, part);
+                           query_rows_dev, nq, chunk, nsplit, part, static_cast<const double*>(nullptr));
     }
     if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e, "k_brute launch");
     hipLaunchKernelGGL(k_brute_reduce, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, st, nq, k, nsplit, part,

@@ -1154,6 +1154,7 @@ k_finalize(const float* __restrict__ pts, int64_t n, int dw, int K, int Kp, int 
         KNNG_REP8(KNNG_FIN_LOAD)
     }
     double acc = 0.0;
+    double acc_a = 0.0, acc_b = 0.0;                  // METRIC 2: |a|^2 and |b|^2, chains of the same kind
     uint32_t acc_u = 0u;
     for (int t = 0; t < dw; t += FIN_CH) {
         KNNG_REP8(KNNG_FIN_STORE)
@@ -1192,6 +1193,12 @@ k_finalize(const float* __restrict__ pts, int64_t n, int dw, int K, int Kp, int 
                             acc = exact_step<METRIC>(acc, av[j].y, bv[j].y);
                             acc = exact_step<METRIC>(acc, av[j].z, bv[j].z);
                             acc = exact_step<METRIC>(acc, av[j].w, bv[j].w);
+                            if constexpr (METRIC == 2) {
+                                acc_a = exact_step<2>(acc_a, av[j].x, av[j].x); acc_b = exact_step<2>(acc_b, bv[j].x, bv[j].x);
+                                acc_a = exact_step<2>(acc_a, av[j].y, av[j].y); acc_b = exact_step<2>(acc_b, bv[j].y, bv[j].y);
+                                acc_a = exact_step<2>(acc_a, av[j].z, av[j].z); acc_b = exact_step<2>(acc_b, bv[j].z, bv[j].z);
+                                acc_a = exact_step<2>(acc_a, av[j].w, av[j].w); acc_b = exact_step<2>(acc_b, bv[j].w, bv[j].w);
+                            }
                         }
                     }
                 }
@@ -1203,7 +1210,7 @@ k_finalize(const float* __restrict__ pts, int64_t n, int dw, int K, int Kp, int 
 #undef KNNG_FIN_LOAD
 #undef KNNG_FIN_DECL
 #undef KNNG_REP8
-    const float dist = ELEM == 1 ? (float)acc_u : exact_finish<METRIC>(acc);
+    const float dist = ELEM == 1 ? (float)acc_u : METRIC == 2 ? cosine_finish(acc, acc_a, acc_b) : exact_finish<METRIC>(acc);
     const u64 fk = live ? pack_key(dist, id, 0) : EMPTY_KEY;
     int rank = 0;
     for (int j = 0; j < K; ++j) rank += ((u64)__shfl((unsigned long long)fk, sub * Kp + j) < fk) ? 1 : 0;
@@ -1250,9 +1257,12 @@ k_finalize_scalar(const float* __restrict__ pts, int64_t n, int d, int K, int Kp
     } else {
         const float* __restrict__ a = pts + vv * d;
         const float* __restrict__ b = pts + (int64_t)id * d;
-        double acc = 0.0;
-        for (int t = 0; t < d; ++t) acc = exact_step<METRIC>(acc, a[t], b[t]);
-        dist = exact_finish<METRIC>(acc);
+        double acc = 0.0, acc_a = 0.0, acc_b = 0.0;
+        for (int t = 0; t < d; ++t) {
+            acc = exact_step<METRIC>(acc, a[t], b[t]);
+            if constexpr (METRIC == 2) { acc_a = exact_step<2>(acc_a, a[t], a[t]); acc_b = exact_step<2>(acc_b, b[t], b[t]); }
+        }
+        dist = METRIC == 2 ? cosine_finish(acc, acc_a, acc_b) : exact_finish<METRIC>(acc);
     }
     const u64 fk = live ? pack_key(dist, id, 0) : EMPTY_KEY;
     int rank = 0;
@@ -1261,6 +1271,27 @@ k_finalize_scalar(const float* __restrict__ pts, int64_t n, int d, int K, int Kp
         ids_out[v * k + rank] = id;
         dists_out[v * k + rank] = dist;
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// k_unit_rows (general cosine): out = x / |x| row by row, a zero row stays zero.  The joins of a
+// cosine build work on these unit-length copies with 1 - <a,b> (search-time precision); what is
+// written to the caller is k_finalize's exact cosine of the original rows.  Eight lanes per row.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_unit_rows(const float* __restrict__ pts, int64_t n, int d, float* __restrict__ out)
+{
+    const int sub = threadIdx.x & 7;
+    const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 3;
+    if (row >= n) return;                             // whole groups of 8 lanes leave together
+    const float* x = pts + row * d;
+    float acc = 0.0f;
+    for (int t = sub; t < d; t += 8) acc = fmaf(x[t], x[t], acc);
+    acc += __shfl_xor(acc, 1);
+    acc += __shfl_xor(acc, 2);
+    acc += __shfl_xor(acc, 4);
+    const float inv = acc > 0.0f ? 1.0f / sqrtf(acc) : 0.0f;
+    for (int t = sub; t < d; t += 8) out[row * d + t] = x[t] * inv;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1438,6 +1469,12 @@ static hipError_t launch_join(hipStream_t st, bool vec, int S16, const JoinArgs&
 
 using namespace knng;
 
+extern "C" __attribute__((visibility("default"))) uint64_t knng_build_cosine_extra_bytes(int64_t n, int32_t d)
+{
+    if (n < 2 || n > 2147483647LL || d < 1) return 0;
+    return ((uint64_t)n * (uint64_t)d * 4u + 255u) & ~255ull;
+}
+
 extern "C" __attribute__((visibility("default"))) uint64_t knng_build_workspace_bytes(int64_t n, int32_t d, int32_t k, const knng_params_t* params)
 {
     if (params && params->struct_size != sizeof(knng_params_t)) return 0;
@@ -1460,9 +1497,16 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
     const float* points_dev = static_cast<const float*>(points_void);   // kernels cast back for elem 1
     if (!points_dev || !ids_out_dev || !dists_out_dev || !params) return KNNG_EINVAL;
     if (params->struct_size != sizeof(knng_params_t)) return KNNG_EINVAL;
-    if (metric != KNNG_METRIC_L2SQ && metric != KNNG_METRIC_IP_UNIT) return KNNG_EINVAL;
+    if (metric != KNNG_METRIC_L2SQ && metric != KNNG_METRIC_IP_UNIT && metric != KNNG_METRIC_COSINE) return KNNG_EINVAL;
+    if (metric == KNNG_METRIC_COSINE && elem != 0) return KNNG_EINVAL;
     BuildPlan bp;
     if (!make_plan(n, d, k, params, &bp)) return KNNG_EINVAL;
+    // general cosine: the search runs on unit-length copies of the rows (behind the other arrays of
+    // the workspace) with 1 - <a,b>; only the last step reads the caller's rows
+    const bool cosine = metric == KNNG_METRIC_COSINE;
+    const uint64_t ws_need = bp.total + (cosine ? knng_build_cosine_extra_bytes(n, d) : 0);
+    const float* points_orig = static_cast<const float*>(points_void);
+    if (cosine) metric = KNNG_METRIC_IP_UNIT;
     if (elem == 1) {
         if (metric != KNNG_METRIC_L2SQ || (d & 3) || d > 65536 ||
             (reinterpret_cast<uintptr_t>(points_void) & 3u))
@@ -1472,7 +1516,7 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
         if (metric != KNNG_METRIC_L2SQ || (d & 1) || (reinterpret_cast<uintptr_t>(points_void) & 3u))
             return KNNG_EINVAL;
     }
-    if (!params->workspace_dev || params->workspace_bytes < bp.total ||
+    if (!params->workspace_dev || params->workspace_bytes < ws_need ||
         (reinterpret_cast<uintptr_t>(params->workspace_dev) & 255u))
         return KNNG_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(params->pinned_host) & 7u) return KNNG_EINVAL;
@@ -1536,6 +1580,12 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
         HIPCHK(record(0));
     }
     HIPCHK(hipMemsetAsync(ctr, 0, 256, st));
+    if (cosine) {
+        float* unit = reinterpret_cast<float*>(ws + bp.total);
+        hipLaunchKernelGGL(k_unit_rows, dim3((unsigned)((n * 8 + 255) / 256)), dim3(256), 0, st, points_orig, n, d, unit);
+        HIPCHK(hipGetLastError());
+        points_dev = unit;
+    }
     if (elem == 2)
         hipLaunchKernelGGL((k_init<0, 2>), dim3(row_blocks), dim3(256), 0, st, points_dev, n, d, bp.K, bp.C,
                            params->seed, params->init_ids_dev, G, cand, cnt, worst, rev, bp.B);
@@ -1605,8 +1655,10 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
         else hipLaunchKernelGGL((k_finalize_scalar<M, E>), grid, block, 0, st, points_dev, n, d, bp.K, Kp, k, G, \
                                 ids_out_dev, dists_out_dev);                                                      \
     } while (0)
+        if (cosine) points_dev = points_orig;          // the exact cosine of the caller's rows
         if (elem == 1) KNNG_FIN(0, 1);
         else if (elem == 2) KNNG_FIN(0, 2);
+        else if (cosine) KNNG_FIN(2, 0);
         else if (metric == 0) KNNG_FIN(0, 0);
         else KNNG_FIN(1, 0);
 #undef KNNG_FIN

@@ -85,6 +85,14 @@ template <int METRIC> __device__ __forceinline__ float exact_finish(double acc)
     double r = 1.0 - acc;
     return (float)(r > 0.0 ? r : 0.0);
 }
+// general cosine (METRIC 2): the chain of <a,b> is exact_step<2>; |a|^2 and |b|^2 are chains of the
+// same kind (exact_step<2>(acc, a, a)); a zero vector is at distance 1 from everything
+__device__ __forceinline__ float cosine_finish(double dot, double na, double nb)
+{
+    if (na == 0.0 || nb == 0.0) return 1.0f;
+    const double r = 1.0 - dot / sqrt(na * nb);
+    return (float)(r > 0.0 ? r : 0.0);
+}
 
 // fp16 rows: two halves per 32-bit word
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));

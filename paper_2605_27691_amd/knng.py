@@ -13,7 +13,7 @@ import torch
 
 from . import build as _build
 
-L2SQ, IP_UNIT = 0, 1
+L2SQ, IP_UNIT, COSINE = 0, 1, 2
 MAX_K = 64
 STATS_MAX_ITERS = 128
 
@@ -52,7 +52,7 @@ class Params(ctypes.Structure):
                 ("pinned_host", _P)]
 
 
-EXPORTS = ("knng_build_workspace_bytes", "knng_build_knn_graph", "knng_build_knn_graph_u8", "knng_build_knn_graph_f16",
+EXPORTS = ("knng_build_workspace_bytes", "knng_build_cosine_extra_bytes", "knng_build_knn_graph", "knng_build_knn_graph_u8", "knng_build_knn_graph_f16",
            "knng_brute_workspace_bytes",
            "knng_brute_knn", "knng_brute_knn_base", "knng_graph_recall", "knng_graph_recall_static", "knng_merge_graphs", "knng_optimize_workspace_bytes",
            "knng_optimize_graph", "knng_graph_search", "knng_graph_search_u8", "knng_strerror", "knng_version")
@@ -77,6 +77,8 @@ def load():
     i32, i64, u64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64
     L.knng_build_workspace_bytes.restype = u64
     L.knng_build_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(Params)]
+    L.knng_build_cosine_extra_bytes.restype = u64
+    L.knng_build_cosine_extra_bytes.argtypes = [i64, i32]
     L.knng_build_knn_graph.restype = ctypes.c_int
     L.knng_build_knn_graph.argtypes = [_P, i64, i32, i32, i32, ctypes.POINTER(Params), _P, _P]
     L.knng_build_knn_graph_f16.restype = ctypes.c_int
@@ -175,6 +177,8 @@ def _build_graph(entry, dtype, points, k, metric, k_build, rho, delta, max_iters
     need = int(L.knng_build_workspace_bytes(n, d, k, ctypes.byref(p)))
     if need == 0:
         raise KnngError(-1)
+    if metric == COSINE:
+        need += int(L.knng_build_cosine_extra_bytes(n, d))
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=points.device)
     workspace = _dev(workspace, torch.uint8, "workspace")

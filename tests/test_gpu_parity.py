@@ -369,6 +369,61 @@ def test_build_ordinary_data_is_not_joined_twice():
     assert st["rejoined"] <= 0.02 * st["joined"], (st["rejoined"], st["joined"])
 
 
+# ------------------------------------------------------------------ general cosine (Sec. 2.1)
+def _rows_of_any_length(n, d, seed, zeros=3, repeats=20):
+    """Clustered directions times a row length spread over three decades, a few zero rows, a few
+    rows that point the same way as another (cosine distance 0 between different rows)."""
+    rng = np.random.default_rng(seed)
+    c = rng.standard_normal((12, d))
+    x = c[rng.integers(0, 12, n)] + 0.4 * rng.standard_normal((n, d))
+    x *= np.exp(rng.uniform(np.log(1e-2), np.log(10.0), (n, 1)))
+    src, dst = rng.integers(0, n, repeats), rng.choice(n, repeats, replace=False)
+    x[dst] = x[src] * rng.uniform(0.5, 2.0, (repeats, 1))
+    x[rng.choice(n, zeros, replace=False)] = 0.0
+    return x.astype(np.float32)
+
+
+@pytest.mark.parametrize("n,d,k", [(3000, 32, 10), (1500, 13, 7), (2000, 128, 32), (65, 4, 64)])
+def test_brute_cosine_bit_exact(n, d, k):
+    x = _rows_of_any_length(n, d, seed=n + d)
+    want_i, want_d = oracle.brute_knn(x, k, oracle.COSINE)
+    got_i, got_d = knng.knng_brute_knn(_gpu(x), k, knng.COSINE)
+    assert np.array_equal(got_i.cpu().numpy(), want_i)
+    assert np.array_equal(got_d.cpu().numpy().view(np.uint32), want_d.view(np.uint32))
+    rows = np.array([0, 5, n - 1], np.int32)                 # query rows, candidates restricted to a prefix
+    want_i, want_d = oracle.brute_knn(x, min(k, n // 2 - 1), oracle.COSINE, query_rows=rows, n_base=n // 2)
+    got_i, got_d = knng.knng_brute_knn(_gpu(x), min(k, n // 2 - 1), knng.COSINE, _gpu(rows), n_base=n // 2)
+    assert np.array_equal(got_i.cpu().numpy(), want_i) and np.array_equal(got_d.cpu().numpy(), want_d)
+
+
+@pytest.mark.parametrize("n,d,k,kb,rho", [(5000, 48, 16, 32, 0.5), (3000, 13, 10, 24, 1.0), (4000, 256, 16, 32, 0.5),
+                                          (3000, 64, 16, 64, 0.5)])
+def test_build_cosine_rows_of_any_length(n, d, k, kb, rho):
+    # the joins work on unit-length copies; what is written is the exact cosine of the caller's rows
+    x = _rows_of_any_length(n, d, seed=d + kb)
+    exact = oracle.brute_knn(x, k, oracle.COSINE)
+    ids, dists, st = knng.knng_build_knn_graph(_gpu(x), k, knng.COSINE, k_build=kb, rho=rho, seed=5)
+    # rows of zeros are at distance 1 from everything: any k neighbours are right for them, so
+    # recall is taken over the other rows
+    _check_build(x, k, oracle.COSINE, ids, dists)
+    live = np.flatnonzero(np.abs(x).sum(1) > 0)
+    rec = oracle.graph_recall(ids.cpu().numpy()[live], dists.cpu().numpy()[live], exact[0][live], exact[1][live], k, 0)
+    assert rec >= 0.95, rec
+    # too small a workspace is refused: the cosine build needs room for the unit-length copies
+    ws = torch.empty(knng.knng_build_workspace_bytes(n, d, k, knng.make_params(k_build=kb, rho=rho)), dtype=torch.uint8, device=DEV)
+    with pytest.raises(knng.KnngError) as ei:
+        knng.knng_build_knn_graph(_gpu(x), k, knng.COSINE, k_build=kb, rho=rho, workspace=ws)
+    assert ei.value.code == -2
+
+
+def test_cosine_is_refused_where_it_is_not_defined():
+    x8 = torch.zeros((100, 16), dtype=torch.uint8, device=DEV)
+    with pytest.raises(knng.KnngError):
+        knng.knng_build_knn_graph_u8(x8, 4, knng.COSINE)
+    with pytest.raises(knng.KnngError):
+        knng.knng_build_knn_graph_f16(x8.to(torch.float16), 4, knng.COSINE)
+
+
 def test_build_argument_errors_leave_outputs_untouched():
     x = _gpu(np.random.default_rng(0).standard_normal((100, 8)).astype(np.float32))
     for kw in (dict(k_build=4), dict(rho=1.5), dict(k_build=100), dict(cand_cap=65)):
