@@ -94,7 +94,7 @@ def parse():
     ap.add_argument("--oracle-rows", type=int, default=-1,
                     help="sampled rows the CPU oracle repeats (default 128; 64 above 2M points)")
     ap.add_argument("--cpu-n", type=int, default=-1,
-                    help="points of the CPU-baseline sample (0 = skip; default 250000, 60000 for K > 32)")
+                    help="points of the CPU-baseline sample (0 = skip; default 250000, fewer for K > 32 or long rows)")
     ap.add_argument("--time-to-recall", type=int, default=1,
                     help="also search the smallest iteration cap that reaches recall@k >= 0.95 (0 = skip)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -300,8 +300,8 @@ def main():
     s_size = max(1, min(K, int(np.ceil(np.float32(a.rho or 0.5).astype(np.float64) * K))))
     if a.oracle_rows < 0:
         a.oracle_rows = 128 if n <= 2_000_000 else 64
-    if a.cpu_n < 0:
-        a.cpu_n = 250000 if K <= 32 else 60000
+    if a.cpu_n < 0:                                         # about 10-30 s of oracle work on 16 cores
+        a.cpu_n = int(250000 * (0.5 if K > 32 else 1.0) * (0.4 if d > 384 else 1.0))
     p = knng.make_params(**kw)
     ws = torch.empty(knng.knng_build_workspace_bytes(n, d, k, p), dtype=torch.uint8, device=dev)
     ids = torch.empty((n, k), dtype=torch.int32, device=dev)

@@ -20,7 +20,10 @@
  *
  * Pin status: every function is pinned by tests that do not go through this
  * file (closed forms, exhaustive enumeration in numpy on tiny inputs, integer
- * data where all arithmetic is exact, the K = n-1 special case).  What stays
+ * data where all arithmetic is exact, the K = n-1 special case; for
+ * oracle_nn_descent also a restatement of its sampling, reverse lists,
+ * neighbour check and merge as set statements in Python, checked against the
+ * lists oracle_nn_descent_trace writes out).  What stays
  * "parity unpinned" is agreement with the outputs of the paper's own
  * implementation: the paper prints no worked example or per-dataset numbers
  * for this path.
