@@ -866,6 +866,10 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             }
             if (sm.col_ok) {
                 float* xdst = X + sm.rsub * LD + 4 * sm.c4;
+                // VEC: a piece past the end of the row (loaded from the row's last piece) is zeroed;
+                // only the last slab of a row whose length is no multiple of the slab has such pieces
+                const bool ragged = VEC && k0 + DS > d;             // uniform
+                const bool full = sm.len16 == DS;                   // uniform
                 const bool inb = !VEC || k0 + 4 * sm.c4 < d;
 #pragma unroll
                 for (int i = 0; i < NL; ++i) {
@@ -874,7 +878,7 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                         if (ELEM == 1) x = enc_u8(x, k0 + 4 * sm.c4);
                         else if (ELEM == 2) x = sub_h2x4(x, pv);
                         else { x.x -= pv.x; x.y -= pv.y; x.z -= pv.z; x.w -= pv.w; }
-                        if (!inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
+                        if (ragged && !inb) x = float4{0.0f, 0.0f, 0.0f, 0.0f};
                         if constexpr (SPLIT) {
                             // the piece keeps its place: two words of hi halves, then two of lo halves
                             short4v hi, lo;
@@ -882,7 +886,11 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                             const uint2 h2 = __builtin_bit_cast(uint2, hi), l2 = __builtin_bit_cast(uint2, lo);
                             x = float4{__uint_as_float(h2.x), __uint_as_float(h2.y), __uint_as_float(l2.x), __uint_as_float(l2.y)};
                         }
-                        if (sm.rsub + i * sm.RP < nTot) *reinterpret_cast<float4*>(xdst + i * sm.RP * LD) = x;
+                        // A full-width slab has NCOLS / RP groups of RP rows exactly: the rows of a loaded
+                        // group past the last member (they repeat it) are stored as they are, nobody
+                        // reads them.  A narrower last slab has more rows per group than NCOLS divides
+                        // into, so there the store is per row.
+                        if (full || sm.rsub + i * sm.RP < nTot) *reinterpret_cast<float4*>(xdst + i * sm.RP * LD) = x;
                     }
                 }
                 if (ELEM == 1 && sm.rsub == 0) {                // the pivot's own row
@@ -904,8 +912,6 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 const int n_tot = to_next ? (v_nx >= 0 ? Pn.nTot : 0) : nTot;
                 const int64_t n_piv = to_next ? (v_nx >= 0 ? v_nx : v) : v;
                 issue_slab(nmid, n_tot, n_piv, to_next ? 0 : k0 + DS);
-                if (to_next && v_nx >= 0) issue_members(nmid, n_tot, n_piv);
-                if (to_next && v_nx2 >= 0) { rc_n = plan[v_nx2]; rid_n = load_slot(v_nx2); }
             }
             // ---- C: Gram tiles of this slab
 #pragma unroll
@@ -913,32 +919,36 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
                 if (trow[q] >= 0) {
                     const float* xa = X + (trow[q] * 16 + r16) * LD + 4 * kq;
                     const float* xb = X + (tcol[q] * 16 + r16) * LD + 4 * kq;
-                    for (int kk = 0; kk < sm.len16; kk += 16) {
+                    // one k-step (16 words of the slab) of tile q from operands read as 16-byte pieces
+                    auto mm = [&](uint4 a, uint4 b) {
                         if constexpr (ELEM == 1) {
-                            const intx4 a = *reinterpret_cast<const intx4*>(xa + kk);
-                            const intx4 b = *reinterpret_cast<const intx4*>(xb + kk);
-                            acc[q] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(intx4, a), __builtin_bit_cast(intx4, b), acc[q], 0, 0, 0);
                         } else if constexpr (ELEM == 2) {
-                            const half8v a = *reinterpret_cast<const half8v*>(xa + kk);
-                            const half8v b = *reinterpret_cast<const half8v*>(xb + kk);
-                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a), __builtin_bit_cast(half8v, b), acc[q], 0, 0, 0);
                         } else if constexpr (SPLIT) {
-                            const uint4 a = *reinterpret_cast<const uint4*>(xa + kk);
-                            const uint4 b = *reinterpret_cast<const uint4*>(xb + kk);
                             const short4v ah = __builtin_bit_cast(short4v, uint2{a.x, a.y}), al = __builtin_bit_cast(short4v, uint2{a.z, a.w});
                             const short4v bh = __builtin_bit_cast(short4v, uint2{b.x, b.y}), bl = __builtin_bit_cast(short4v, uint2{b.z, b.w});
                             acc[q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bh, acc[q], 0, 0, 0);
                             acc[q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bl, acc[q], 0, 0, 0);
                             acc[q] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(al, bh, acc[q], 0, 0, 0);
                         } else {
-                            const float4 a = *reinterpret_cast<const float4*>(xa + kk);
-                            const float4 b = *reinterpret_cast<const float4*>(xb + kk);
-                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc[q], 0, 0, 0);
-                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc[q], 0, 0, 0);
-                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc[q], 0, 0, 0);
-                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), acc[q], 0, 0, 0);
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), acc[q], 0, 0, 0);
                         }
+                    };
+                    // two k-steps per round: four operand reads in flight before the first matrix
+                    // instruction waits for them (one step per round leaves every LDS round trip bare)
+                    // (fp32 rows only: the uint8 and fp16 instantiations have no registers to spare)
+                    int kk = 0;
+                    for (; ELEM == 0 && kk + 32 <= sm.len16; kk += 32) {
+                        const uint4 a0 = *reinterpret_cast<const uint4*>(xa + kk), b0 = *reinterpret_cast<const uint4*>(xb + kk);
+                        const uint4 a1 = *reinterpret_cast<const uint4*>(xa + kk + 16), b1 = *reinterpret_cast<const uint4*>(xb + kk + 16);
+                        mm(a0, b0);
+                        mm(a1, b1);
                     }
+                    for (; kk < sm.len16; kk += 16) mm(*reinterpret_cast<const uint4*>(xa + kk), *reinterpret_cast<const uint4*>(xb + kk));
                 }
             }
             if constexpr (ELEM == 1) {
@@ -959,11 +969,16 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             if (last) {
                 // member norms from the diagonal tiles: lane (r16, kq) holds rows 4kq..4kq+3 of
                 // column r16, so the diagonal element sits in lanes with r16 / 4 == kq
+                // (one store per accumulator register, the lane that holds the diagonal element in it
+                // taking part: a select over a register picked by the lane costs the compiler a
+                // chain over every accumulator of the wavefront)
 #pragma unroll
                 for (int q = 0; q < NT; ++q) {
-                    if (trow[q] >= 0 && trow[q] == tcol[q] && (r16 >> 2) == kq) {
-                        const int e = r16 & 3;
-                        nrm[trow[q] * 16 + r16] = acc_bits(e == 0 ? acc[q][0] : e == 1 ? acc[q][1] : e == 2 ? acc[q][2] : acc[q][3]);
+                    if (trow[q] >= 0 && trow[q] == tcol[q]) {   // uniform
+                        uint32_t* dst = nrm + trow[q] * 16 + r16;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (r16 == 4 * kq + e) *dst = acc_bits(acc[q][e]);
                     }
                 }
                 if (ELEM == 1 && w == 0 && lane == 4) thr_v[1] = __uint_as_float((uint32_t)accp[0]);
@@ -971,6 +986,14 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             lds_barrier();                                 // slab consumed by every wavefront
         }
 
+        // After the last Gram pass: the next point's thresholds and signatures and the list record of
+        // the point after next (requested earlier they would hold ten registers through the Gram
+        // passes), then the previous point's offers.  All of it completes under the norm /
+        // distance-block / scan work below, which never waits for memory.
+        if (v_nx >= 0) {
+            issue_members(midbuf + (cur ^ 1) * NCOLS, Pn.nTot, v_nx);
+            if (v_nx2 >= 0) { rc_n = plan[v_nx2]; rid_n = load_slot(v_nx2); }
+        }
         send_offers(untrusted + (cur ^ 1));                // the previous point's
         // The pivot's reverse members hold v in their rows, so |x_m - x_v|^2 is already known:
         // offer them to v itself (closes v<-m edges into v->m without an extra distance).
@@ -1043,30 +1066,47 @@ k_join(const float* __restrict__ pts, int d, int C, int s, uint32_t iter,
             const int m = ps * (256 / LPM) + tid / LPM, sub = tid % LPM;
             if (m >= nTot) continue;
             const int myid = mh[m].x;
-            const uint32_t* msig = sg + m;
             const uint32_t mythr = __float_as_uint(thr[m]);    // non-negative floats order as integers
             uint32_t best_l = mythr, best_j = 0xffffffffu;
             const bool isnew = m < nNew;
             const int jend = isnew ? nTot : nNew;
             // Four partners of the lane's class per step: their distances and records are read
             // together, then their signature words -- two LDS round trips per step instead of
-            // three per partner.  D[m][j] sits at [lower tile][higher tile].
+            // three per partner.  D[m][j] sits at [lower tile][higher tile]; with four classes the
+            // four partners of a step lie in one 16-wide tile, so a step walks either the member's
+            // row (address + 4) or the partners' column (address + 4 LDD).  Index arithmetic in 24
+            // bits: one full-rate instruction per address.
+            const uint32_t um = (uint32_t)m, mrow = __umul24(um, (uint32_t)LDD);
             for (int j0 = sub; j0 < jend; j0 += 4 * LPM) {
                 uint32_t l[4];
                 int2 pj[4];
+                if constexpr (LPM == 4) {
+                    const bool colwalk = !isnew || ((uint32_t)j0 >> 4) < (um >> 4);
+                    const uint32_t a0 = colwalk ? __umul24((uint32_t)j0, (uint32_t)LDD) + um : mrow + (uint32_t)j0;
+                    const uint32_t st = colwalk ? 4u * LDD : 4u;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int j = j0 + u * LPM;
-                    const bool in = j < jend;
-                    const int jj = in ? j : sub;               // any valid partner: its cell is not used
-                    const bool tr = isnew && ((jj >> 4) < (m >> 4));
-                    const uint32_t v = __float_as_uint(tr ? D[jj * LDD + m] : D[(isnew ? m : jj) * LDD + (isnew ? jj : m)]);
-                    l[u] = in ? v : 0xffffffffu;
-                    pj[u] = mh[jj];
+                    for (int u = 0; u < 4; ++u) {
+                        const int j = j0 + 4 * u;
+                        const bool in = j < jend;
+                        const uint32_t v = __float_as_uint(D[in ? a0 + (uint32_t)u * st : a0]);
+                        l[u] = in ? v : 0xffffffffu;
+                        pj[u] = mh[in ? j : j0];
+                    }
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int j = j0 + u * LPM;
+                        const bool in = j < jend;
+                        const int jj = in ? j : sub;           // any valid partner: its cell is not used
+                        const bool tr = isnew && ((jj >> 4) < (m >> 4));
+                        const uint32_t v = __float_as_uint(tr ? D[jj * LDD + m] : D[(isnew ? m : jj) * LDD + (isnew ? jj : m)]);
+                        l[u] = in ? v : 0xffffffffu;
+                        pj[u] = mh[jj];
+                    }
                 }
                 uint32_t wv[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) wv[u] = msig[((uint32_t)pj[u].y >> 5) * SGLD];
+                for (int u = 0; u < 4; ++u) wv[u] = sg[__umul24((uint32_t)pj[u].y >> 5, (uint32_t)SGLD) + um];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const uint32_t known = (wv[u] >> ((uint32_t)pj[u].y & 31u)) & 1u;
