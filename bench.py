@@ -52,13 +52,13 @@ FP16_MFMA_PEAK_TFLOPS = 2500.0   # dense fp16 MFMA (the fp16 build's Gram tiles)
 SIG_BYTES = 32          # row signature read per gathered member
 # HBM-side bytes per join launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each
 # scaled by what a plain 1 GiB device copy reads: 2.0 and 1.0 KiB per count), averaged over the same
-# launch mix as the timed region.  Only measured for the default workload and parameters
-# (profiles/k_join_config1_1m_d128_hbm_traffic.txt: 17.28 GB fetched + 1.47 GB written).
+# launch mix as the timed region.  Only measured for the workloads and parameters listed
+# (profiles/k_join_wave_u8gmm1024_1m_d128_hbm_traffic.txt: 17.28 GB fetched + 1.47 GB written).
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("u8gmm1024_1m_d128_l2", "f32", 32, 0.5): 18.75e9,
-                                     # profiles/k_join_wave_u8_config1_1m_d128.txt: 7.92 GB + 1.47 GB
+                                     # profiles/k_join_wave_u8_u8gmm1024_1m_d128.txt: 7.92 GB + 1.47 GB
                                      ("u8gmm1024_1m_d128_l2", "u8", 32, 0.5): 9.39e9,
-                                     # profiles/k_join_gmm4096_20m_d128_hbm_traffic.txt: 656.9 GB + 48.4 GB
-                                     ("gmm4096_20m_d128_l2", "f32", 64, 0.375): 705.3e9}
+                                     # profiles/k_join_gmm4096_20m_d128_hbm_traffic.txt: 609.6 GB + 48.4 GB
+                                     ("gmm4096_20m_d128_l2", "f32", 64, 0.375): 658.0e9}
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # dense bf16 MFMA (the split Gram pass of long fp32 rows: three per product)
 SPLIT_MIN_D = 256                # fp32 rows from this length on take the bf16-split Gram pass (s <= 16; s > 16: from 64)
 # Parameters a workload runs with when none are given: the cheapest set found that passes
