@@ -11,6 +11,10 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]
+# per-source flags.  knng_brute.hip: accumulators of the matrix instructions in ordinary vector
+# registers; with the accumulator-register form the compiler moves all sixteen in and out around
+# every slab of k_brute_mfma, and the read back waits for the matrix pipe to drain.
+EXTRA_FLAGS = {"knng_brute.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def up_to_date() -> bool:
@@ -34,7 +38,7 @@ def build(force: bool = True, verbose: bool = False, defines=(), lib: str = LIB)
     procs = []
     for src in SOURCES:
         obj = os.path.join(objdir, tag + src.replace(".hip", ".o"))
-        cmd = [HIPCC, *FLAGS, *("-D" + d for d in defines), "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), *("-D" + d for d in defines), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd))
         procs.append((cmd, subprocess.Popen(cmd, stderr=subprocess.PIPE, text=True)))

@@ -186,6 +186,13 @@ k_row_norms(const float* __restrict__ pts, int64_t n, int d, float* __restrict__
     if (row < n && sub == 0) nrm[row] = (float)acc;
 }
 
+__global__ void __launch_bounds__(256)
+k_fill_u32(uint32_t* __restrict__ p, int64_t count, uint32_t value)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) p[i] = value;
+}
+
 // |x_i|^2 of every point as the distance recipe's own chain gives it: fp64, coordinates in index
 // order, fused multiply-add, no rounding to fp32 (general cosine).  One lane per row.
 __global__ void __launch_bounds__(256)
@@ -199,29 +206,42 @@ k_row_norms_exact(const float* __restrict__ pts, int64_t n, int d, double* __res
     nrm64[row] = acc;
 }
 
+// the value of lane - 1 (lane 0: 0), one DPP move per 32-bit half
+__device__ __forceinline__ u64 wave_shr1_64(u64 v)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, 0x138, 0xf, 0xf, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), 0x138, 0xf, 0xf, false);
+    return ((u64)hi << 32) | lo;
+}
+
 constexpr int MLD = BDC + 4;      // row stride of a row-major slab: conflict-free 16-byte reads
 
 constexpr int SQCAP = BT * BT + 256;   // survivor queue: one whole tile on top of what may wait
+constexpr int SQ_BASE_BITS = 26;       // a queue entry: query << 26 | base point - first point of the range
+constexpr int RING = 4;                // slabs in flight from global memory per thread
 
 template <int METRIC>
 __global__ void __launch_bounds__(256)
 k_brute_mfma(const float* __restrict__ pts, const float* __restrict__ nrm, int64_t n, int d, int k,
              const int32_t* __restrict__ query_rows, int64_t nq, int64_t base_chunk, int nsplit,
-             u64* __restrict__ part)
+             u64* __restrict__ part, uint32_t* __restrict__ gthr)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    float* QS = reinterpret_cast<float*>(smem);            // [BT][MLD] query slab
-    float* BS = QS + BT * MLD;                             // [BT][MLD] base slab
-    u64* sq = reinterpret_cast<u64*>(BS + BT * MLD);       // [SQCAP] survivors of the screen: query << 32 | base id
-    u64* list = sq + SQCAP;                                // [BT][k] ascending
+    float* QS = reinterpret_cast<float*>(smem);            // [2][BT][MLD] query slabs
+    float* BS = QS + 2 * BT * MLD;                         // [2][BT][MLD] base slabs
+    uint32_t* sq = reinterpret_cast<uint32_t*>(BS + 2 * BT * MLD);   // [SQCAP] survivors of the screen
+    u64* list = reinterpret_cast<u64*>(sq + SQCAP);        // [BT][k] ascending
     u64* thr = list + BT * k;                              // [BT] current k-th key
     u64* rk = thr + BT;                                    // [256] exact keys of one round (EMPTY: not better)
     int* rq = reinterpret_cast<int*>(rk + 256);            // [256] their queries
     int* qrow = rq + 256;                                  // [BT] source point of each query
     float* qn = reinterpret_cast<float*>(qrow + BT);       // [BT] |q|^2
-    float* bn = qn + BT;                                   // [BT] |b|^2 of the current tile
-    float* thrd = bn + BT;                                 // [BT] k-th distance, +inf while the list is short
-    int* qcount = reinterpret_cast<int*>(thrd + BT);       // survivors waiting in sq
+    float* bn = qn + BT;                                   // [3][256] |b|^2 of the current tile and of the next, a
+                                                           // copy per wavefront; the third: stores nobody reads
+    float* thrd = bn + 3 * 256;                            // [BT] k-th distance, +inf while the list is short
+    float* gthl = thrd + BT;                               // [2][256] the smallest k-th distance any range has
+                                                           // published, a copy per wavefront; the second as above
+    int* qcount = reinterpret_cast<int*>(gthl + 2 * 256);  // survivors waiting in sq
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r16 = lane & 15, kq = lane >> 4;
@@ -240,162 +260,356 @@ k_brute_mfma(const float* __restrict__ pts, const float* __restrict__ nrm, int64
         thr[tid] = EMPTY_KEY;
         thrd[tid] = inf;
     }
+    gthl[tid] = inf;
     if (tid == 0) *qcount = 0;
     for (int i = tid; i < BT * k; i += 256) list[i] = EMPTY_KEY;
     __syncthreads();
 
-    // The slabs are software-pipelined: while the matrix cores work on one slab, the 16-byte
-    // pieces of the next one (the next 32 coordinates, or the first 32 of the next base tile) are
-    // in flight into registers.
-    const int srow = tid >> 3, spc = tid & 7;              // staging: rows srow and srow + 32, piece spc
-    const int sq0 = qrow[srow], sq1 = qrow[srow + 32];
-    float4 pq[2], pb[2];
-    auto issue = [&](int64_t b0, int k0) {
-        const int t = k0 + 4 * spc;
-        pq[0] = pq[1] = pb[0] = pb[1] = float4{0, 0, 0, 0};
-        if (t < d) {
-            if (sq0 >= 0) pq[0] = *reinterpret_cast<const float4*>(pts + (int64_t)sq0 * d + t);
-            if (sq1 >= 0) pq[1] = *reinterpret_cast<const float4*>(pts + (int64_t)sq1 * d + t);
-            if (b0 + srow < b_end) pb[0] = *reinterpret_cast<const float4*>(pts + (b0 + srow) * d + t);
-            if (b0 + srow + 32 < b_end) pb[1] = *reinterpret_cast<const float4*>(pts + (b0 + srow + 32) * d + t);
-        }
-    };
-    if (b_begin < b_end) issue(b_begin, 0);
+    if (b_begin < b_end) {
+        // The walk over (base tile, slab of 32 coordinates) is one sequence of slabs.  Every thread
+        // keeps the 16-byte pieces of the next RING slabs in flight in registers: a load takes
+        // longer than the matrix cores need for one slab, so one slab of look-ahead leaves them idle.
+        // Every load is issued unconditionally from a clamped, valid address (a row past the range
+        // reads the range's last row, a piece past d the row's last piece, an unused query row 0):
+        // such values are zeroed on the way to LDS or belong to pairs the screen never passes.
+        struct Slot { float4 q0, q1, b0, b1; float nb, gt; };   // nb: |b|^2 of the tile's point `lane`; gt: shared bound of query `lane`
+        Slot ring[RING];
+        const int srow = tid >> 3, spc = tid & 7;          // staging: rows srow and srow + 32, piece spc
+        const int sq0 = qrow[srow], sq1 = qrow[srow + 32];
+        const float* qp0 = pts + (int64_t)(sq0 > 0 ? sq0 : 0) * d;
+        const float* qp1 = pts + (int64_t)(sq1 > 0 ? sq1 : 0) * d;
+        // The ranges of one query tile share a bound per query: every range publishes the k-th
+        // distance of its full list (an atomic min on the fp32 bits), and every k-th distance of a
+        // subset of the points is an upper bound of the final one, so a pair above the smallest
+        // published value cannot be in the result.  Without it each of the nsplit ranges would fill
+        // and refine a list of its own: nsplit times the exact evaluations of one pass over all points.
+        // Which pairs are skipped depends on timing; the result, the exact k smallest, does not.
+        const int64_t gq = q0 + lane < nq ? q0 + lane : nq - 1;
+        const int nslab = (d + BDC - 1) / BDC;
+        const int64_t total = ((b_end - b_begin + BT - 1) / BT) * nslab;
+        int64_t ib0 = b_begin;                             // the next slab to issue
+        int ik0 = 0;
+        auto issue = [&](Slot& s) {
+            int t = ik0 + 4 * spc;
+            t = t < d - 4 ? t : d - 4;
+            int64_t r0 = ib0 + srow, r1 = ib0 + srow + 32;
+            r0 = r0 < b_end ? r0 : b_end - 1;
+            r1 = r1 < b_end ? r1 : b_end - 1;
+            s.q0 = *reinterpret_cast<const float4*>(qp0 + t);
+            s.q1 = *reinterpret_cast<const float4*>(qp1 + t);
+            s.b0 = *reinterpret_cast<const float4*>(pts + r0 * d + t);
+            s.b1 = *reinterpret_cast<const float4*>(pts + r1 * d + t);
+            const int64_t rn = ib0 + lane;
+            s.nb = nrm[rn < b_end ? rn : b_end - 1];
+            s.gt = __uint_as_float(__hip_atomic_load(gthr + gq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            ik0 += BDC;
+            if (ik0 >= d) { ik0 = 0; ib0 += BT; }
+            // keep the slots' loads in program order: the waits for a slot count the loads issued after it
+            __builtin_amdgcn_sched_barrier(0);
+        };
+#pragma unroll
+        for (int i = 0; i < RING; ++i) issue(ring[i]);
 
-    for (int64_t b0 = b_begin; b0 < b_end; b0 += BT) {
-        floatx4 acc[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) acc[c] = floatx4{0, 0, 0, 0};
-        for (int k0 = 0; k0 < d; k0 += BDC) {
-            __syncthreads();                               // the previous slab has been multiplied
-            if (k0 == 0 && tid < BT) bn[tid] = (b0 + tid < b_end) ? nrm[b0 + tid] : 0.0f;
-            *reinterpret_cast<float4*>(QS + srow * MLD + 4 * spc) = pq[0];
-            *reinterpret_cast<float4*>(QS + (srow + 32) * MLD + 4 * spc) = pq[1];
-            *reinterpret_cast<float4*>(BS + srow * MLD + 4 * spc) = pb[0];
-            *reinterpret_cast<float4*>(BS + (srow + 32) * MLD + 4 * spc) = pb[1];
-            __syncthreads();
-            if (k0 + BDC < d) issue(b0, k0 + BDC);
-            else if (b0 + BT < b_end) issue(b0 + BT, 0);
-#pragma unroll
-            for (int kk = 0; kk < BDC; kk += 16) {
-                const float4 a = *reinterpret_cast<const float4*>(QS + (16 * w + r16) * MLD + 4 * kq + kk);
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const float4 b = *reinterpret_cast<const float4*>(BS + (16 * c + r16) * MLD + 4 * kq + kk);
-                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc[c], 0, 0, 0);
-                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc[c], 0, 0, 0);
-                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc[c], 0, 0, 0);
-                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc[c], 0, 0, 0);
-                }
-            }
-        }
-        // lane (r16, kq) holds <q, b> for queries 16w + 4kq + r and base points b0 + 16c + r16.
-        // Screen: pairs the bound cannot rule out are queued (one LDS counter bump per vote).
-        {
+        // after the last slab of a tile: lane (r16, kq) holds <q, b> for queries 16w + 4kq + r and
+        // base points b0 + 16c + r16.  Screen: pairs the bound cannot rule out are queued; then,
+        // once enough of them wait (or the range ends), they get their exact distance, 256 at a
+        // time, one per thread, and each wavefront folds the ones of its 16 queries into their lists.
+        auto tile_done = [&](const int64_t b0, const floatx4 (&acc)[4], const int tp) {
             float na[4], td[4];
             int qrr[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int qi = 16 * w + 4 * kq + r;
-                na[r] = qn[qi]; td[r] = thrd[qi] * 1.000001f; qrr[r] = qrow[qi];
+                na[r] = qn[qi]; td[r] = fminf(thrd[qi], gthl[64 * w + qi]) * 1.000001f; qrr[r] = qrow[qi];
             }
+            // one bit per pair of the lane (4c + r); an unused query row never passes
+#pragma unroll
+            for (int r = 0; r < 4; ++r) td[r] = qrr[r] >= 0 ? td[r] : -inf;
+            uint32_t pm = 0;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const int64_t b = b0 + 16 * c + r16;
-                const float nb = bn[16 * c + r16];
+                const int b = (int)b0 + 16 * c + r16;      // ids fit 31 bits
+                const float nb = bn[tp * 256 + 64 * w + 16 * c + r16];
+                uint32_t pc = 0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     float l, e;
                     if (METRIC == 0) { l = na[r] + nb - 2.0f * acc[c][r]; e = epsd * (na[r] + nb); }
                     else { l = 1.0f - acc[c][r]; e = epsd * (0.5f * (na[r] + nb) + 1.0f); }
-                    const bool pass = qrr[r] >= 0 && b < b_end && b != (int64_t)qrr[r] && !(l - e > td[r]);
-                    const u64 m = __ballot(pass);
-                    if (m != 0ull) {
-                        int base = 0;
-                        if (lane == 0) base = atomicAdd(qcount, __popcll(m));
-                        base = (int)bcast32((uint32_t)base, 0);
-                        if (pass)
-                            sq[base + __popcll(m & lanemask_lt())] =
-                                ((u64)(uint32_t)(16 * w + 4 * kq + r) << 32) | (uint32_t)b;
-                    }
+                    pc |= (!(l - e > td[r]) & (b != qrr[r])) ? (1u << r) : 0u;
                 }
+                pm |= (int64_t)b < b_end ? pc << (4 * c) : 0u;
+            }
+            if (__ballot(pm != 0u) != 0ull) {
+                // one reservation in the queue per wavefront: the lanes' counts summed bit by bit,
+                // which also gives every lane the number of entries of the lanes before it
+                const int cnt = __popc(pm);
+                int total = 0, before = 0;
+#pragma unroll
+                for (int bit = 0; bit < 5; ++bit) {
+                    const u64 mb = __ballot(((cnt >> bit) & 1) != 0);
+                    total += __popcll(mb) << bit;
+                    before += __popcll(mb & lanemask_lt()) << bit;
+                }
+                int off = 0;
+                if (lane == 0) off = atomicAdd(qcount, total);
+                off = (int)bcast32((uint32_t)off, 0) + before;
+                const uint32_t ent0 = ((uint32_t)(16 * w + 4 * kq) << SQ_BASE_BITS) | ((uint32_t)(b0 - b_begin) + r16);
+                while (pm != 0u) {
+                    const uint32_t i = (uint32_t)__ffs((int)pm) - 1u;
+                    pm &= pm - 1u;
+                    sq[off++] = ent0 + ((i & 3u) << SQ_BASE_BITS) + 16u * (i >> 2);
+                }
+            }
+            __syncthreads();
+            const int waiting = *qcount;
+            if (waiting > 256 || (waiting > 0 && b0 + BT >= b_end)) {
+                for (int base = 0; base < waiting; base += 256) {
+                    u64 key = EMPTY_KEY;
+                    int qi = -1;
+                    if (base + tid < waiting) {
+                        const uint32_t ent = sq[base + tid];
+                        qi = (int)(ent >> SQ_BASE_BITS);
+                        const int64_t b = b_begin + (int64_t)(ent & ((1u << SQ_BASE_BITS) - 1u));
+                        const float* xq = pts + (int64_t)qrow[qi] * d;
+                        const float* xb = pts + b * d;
+                        double sacc = 0.0;
+                        int t = 0;
+                        for (; t + 16 <= d; t += 16) {
+                            float4 x[4], y[4];
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) {
+                                x[u] = *reinterpret_cast<const float4*>(xq + t + 4 * u);
+                                y[u] = *reinterpret_cast<const float4*>(xb + t + 4 * u);
+                            }
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) {
+                                sacc = exact_step<METRIC>(sacc, x[u].x, y[u].x);
+                                sacc = exact_step<METRIC>(sacc, x[u].y, y[u].y);
+                                sacc = exact_step<METRIC>(sacc, x[u].z, y[u].z);
+                                sacc = exact_step<METRIC>(sacc, x[u].w, y[u].w);
+                            }
+                        }
+                        for (; t < d; t += 4) {
+                            const float4 x = *reinterpret_cast<const float4*>(xq + t);
+                            const float4 y = *reinterpret_cast<const float4*>(xb + t);
+                            sacc = exact_step<METRIC>(sacc, x.x, y.x);
+                            sacc = exact_step<METRIC>(sacc, x.y, y.y);
+                            sacc = exact_step<METRIC>(sacc, x.z, y.z);
+                            sacc = exact_step<METRIC>(sacc, x.w, y.w);
+                        }
+                        const float dist = exact_finish<METRIC>(sacc);
+                        key = pack_key(dist, (int)b, 0);
+                        if (!(key < thr[qi]) || dist > gthl[64 * w + qi]) key = EMPTY_KEY;
+                    }
+                    rk[tid] = key;
+                    rq[tid] = qi;
+                    __syncthreads();
+                    // Wavefront w owns queries 16w .. 16w+15.  It reads the round's 256 keys once, then
+                    // inserts the ones of each of its queries into that query's sorted list, one key at
+                    // a time: the list sits in lanes 0 .. k-1, a key's rank is one vote, and the lanes
+                    // from that rank on take their left neighbour's entry.
+                    u64 rkv[4];
+                    int rqv[4];
+#pragma unroll
+                    for (int ch = 0; ch < 4; ++ch) {
+                        rkv[ch] = rk[64 * ch + lane];
+                        rqv[ch] = rkv[ch] != EMPTY_KEY ? rq[64 * ch + lane] : -1;
+                    }
+                    for (int qq = 0; qq < 16; ++qq) {
+                        const int mq = 16 * w + qq;
+                        u64 cm[4];
+#pragma unroll
+                        for (int ch = 0; ch < 4; ++ch) cm[ch] = __ballot(rqv[ch] == mq);
+                        if ((cm[0] | cm[1] | cm[2] | cm[3]) == 0ull) continue;
+                        u64 lk = lane < k ? list[mq * k + lane] : EMPTY_KEY;
+#pragma unroll
+                        for (int ch = 0; ch < 4; ++ch)
+                            for (u64 mm = cm[ch]; mm; mm &= mm - 1) {
+                                const u64 c = bcast64(rkv[ch], __ffsll((long long)mm) - 1);
+                                const int r = __popcll(__ballot(lk < c));    // lanes >= k hold EMPTY_KEY
+                                if (r < k) {
+                                    const u64 left = wave_shr1_64(lk);
+                                    lk = lane < r ? lk : (lane == r ? c : left);
+                                    if (lane >= k) lk = EMPTY_KEY;
+                                }
+                            }
+                        if (lane < k) list[mq * k + lane] = lk;
+                        if (lane == k - 1) {
+                            thr[mq] = lk;
+                            thrd[mq] = lk == EMPTY_KEY ? inf : key_dist(lk);
+                            if (lk != EMPTY_KEY && q0 + mq < nq) atomicMin(gthr + (q0 + mq), (uint32_t)(lk >> 32));
+                        }
+                    }
+                    __syncthreads();
+                }
+                if (tid == 0) *qcount = 0;
+                __syncthreads();
+            }
+        };
+
+        floatx4 acc[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] = floatx4{0, 0, 0, 0};
+        int64_t b0 = b_begin;                              // the slab being multiplied
+        int k0 = 0, buf = 0, tp = 0;                       // tp: parity of its tile (which half of bn)
+        int64_t b0n = b_begin;                             // the slab being staged: the one after it
+        int k0n = 0, tpn = 0;
+        // One slab ahead of the matrix instructions, a slab goes from the ring to the LDS pair the
+        // previous step read.  The stores stand after the step's matrix instructions in program
+        // order, so they issue in the shadow of those; the barrier that ends the step orders them
+        // before the next step's reads, and this step's reads before the stores of the step after.
+        auto stage = [&](Slot v, const int to) {
+            if (k0n + BDC > d && !(k0n + 4 * spc < d))
+                v.q0 = v.q1 = v.b0 = v.b1 = float4{0, 0, 0, 0};
+            float* qs = QS + to * (BT * MLD);
+            float* bs = BS + to * (BT * MLD);
+            bn[(k0n == 0 ? tpn : 2) * 256 + tid] = v.nb;   // a tile's first slab carries its norms and bounds
+            gthl[(k0n == 0 ? 0 : 1) * 256 + tid] = v.gt;
+            *reinterpret_cast<float4*>(qs + srow * MLD + 4 * spc) = v.q0;
+            *reinterpret_cast<float4*>(qs + (srow + 32) * MLD + 4 * spc) = v.q1;
+            *reinterpret_cast<float4*>(bs + srow * MLD + 4 * spc) = v.b0;
+            *reinterpret_cast<float4*>(bs + (srow + 32) * MLD + 4 * spc) = v.b1;
+            k0n += BDC;
+            if (k0n >= d) { k0n = 0; tpn ^= 1; b0n += BT; }
+        };
+        // the slab in LDS pair `buf` times the accumulators: all operands first (ten 16-byte reads),
+        // then the 32 matrix instructions as four independent chains taken in turn
+        auto multiply = [&]() {
+            const float* qs = QS + buf * (BT * MLD);
+            const float* bs = BS + buf * (BT * MLD);
+            float4 a[2], b[2][4];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                a[h] = *reinterpret_cast<const float4*>(qs + (16 * w + r16) * MLD + 4 * kq + 16 * h);
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    b[h][c] = *reinterpret_cast<const float4*>(bs + (16 * c + r16) * MLD + 4 * kq + 16 * h);
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[h].x, b[h][c].x, acc[c], 0, 0, 0);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[h].y, b[h][c].y, acc[c], 0, 0, 0);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[h].z, b[h][c].z, acc[c], 0, 0, 0);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[h].w, b[h][c].w, acc[c], 0, 0, 0);
+            }
+        };
+        // One step of the steady state: the matrix instructions of the slab in LDS pair `buf`, and
+        // between them, four at a time, the pieces of what the step also has to do: the next slab
+        // from its ring slot to the other LDS pair, then that slot's loads for the slab RING later.
+        // A wavefront issues in order, and four of these matrix instructions keep their pipe busy
+        // for 128 cycles: what stands between two groups issues in their shadow.  The fences keep
+        // the compiler from sorting the groups back together.
+        auto step = [&](Slot& nx) {
+            const float* qs = QS + buf * (BT * MLD);
+            const float* bs = BS + buf * (BT * MLD);
+            float* qd = QS + (buf ^ 1) * (BT * MLD) + srow * MLD + 4 * spc;
+            float* bd = BS + (buf ^ 1) * (BT * MLD) + srow * MLD + 4 * spc;
+            float4 a[2], b[2][4];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                a[h] = *reinterpret_cast<const float4*>(qs + (16 * w + r16) * MLD + 4 * kq + 16 * h);
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    b[h][c] = *reinterpret_cast<const float4*>(bs + (16 * c + r16) * MLD + 4 * kq + 16 * h);
+            }
+            const bool dead = k0n + BDC > d && !(k0n + 4 * spc < d);   // a piece past d of a last slab
+            auto live = [&](float4 x) { return float4{dead ? 0.0f : x.x, dead ? 0.0f : x.y, dead ? 0.0f : x.z, dead ? 0.0f : x.w}; };
+            int t = ik0 + 4 * spc;
+            t = t < d - 4 ? t : d - 4;
+            int64_t r0 = ib0 + srow, r1 = ib0 + srow + 32;
+            r0 = r0 < b_end ? r0 : b_end - 1;
+            r1 = r1 < b_end ? r1 : b_end - 1;
+            const int64_t rn = ib0 + lane;
+#define KNNG_MM(h, e) \
+            _Pragma("unroll") for (int c = 0; c < 4; ++c) \
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[h].e, b[h][c].e, acc[c], 0, 0, 0); \
+            __builtin_amdgcn_sched_barrier(0)
+            __builtin_amdgcn_sched_barrier(0);
+            KNNG_MM(0, x);
+            *reinterpret_cast<float4*>(qd) = live(nx.q0);
+            __builtin_amdgcn_sched_barrier(0);
+            KNNG_MM(0, y);
+            *reinterpret_cast<float4*>(qd + 32 * MLD) = live(nx.q1);
+            __builtin_amdgcn_sched_barrier(0);
+            KNNG_MM(0, z);
+            *reinterpret_cast<float4*>(bd) = live(nx.b0);
+            __builtin_amdgcn_sched_barrier(0);
+            KNNG_MM(0, w);
+            *reinterpret_cast<float4*>(bd + 32 * MLD) = live(nx.b1);
+            bn[(k0n == 0 ? tpn : 2) * 256 + tid] = nx.nb;
+            gthl[(k0n == 0 ? 0 : 1) * 256 + tid] = nx.gt;
+            __builtin_amdgcn_sched_barrier(0);
+            KNNG_MM(1, x);
+            nx.q0 = *reinterpret_cast<const float4*>(qp0 + t);
+            nx.q1 = *reinterpret_cast<const float4*>(qp1 + t);
+            __builtin_amdgcn_sched_barrier(0);
+            KNNG_MM(1, y);
+            nx.b0 = *reinterpret_cast<const float4*>(pts + r0 * d + t);
+            nx.b1 = *reinterpret_cast<const float4*>(pts + r1 * d + t);
+            __builtin_amdgcn_sched_barrier(0);
+            KNNG_MM(1, z);
+            nx.nb = nrm[rn < b_end ? rn : b_end - 1];
+            nx.gt = __uint_as_float(__hip_atomic_load(gthr + gq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            __builtin_amdgcn_sched_barrier(0);
+            KNNG_MM(1, w);
+#undef KNNG_MM
+            k0n += BDC;
+            if (k0n >= d) { k0n = 0; tpn ^= 1; b0n += BT; }
+            ik0 += BDC;
+            if (ik0 >= d) { ik0 = 0; ib0 += BT; }
+        };
+        auto end_step = [&]() {
+            __syncthreads();
+            buf ^= 1;
+            k0 += BDC;
+            if (k0 >= d) {
+                tile_done(b0, acc, tp);
+                k0 = 0;
+                tp ^= 1;
+                b0 += BT;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[c] = floatx4{0, 0, 0, 0};
+            }
+        };
+        stage(ring[0], 0);
+        issue(ring[0]);
+        __syncthreads();
+        // Whole groups of RING slabs run without a condition inside the group: a path on which a
+        // step is skipped and the loop goes round again would make the compiler wait, at the first
+        // step, for every load in flight.  The last total % RING slabs load what they stage
+        // themselves (the ring's loads of those slabs are left to complete unused).
+        const int64_t groups = total / RING;
+        for (int64_t g = 0; g < groups; ++g) {
+#pragma unroll
+            for (int i = 0; i < RING; ++i) {
+                step(ring[(i + 1) % RING]);            // (past the last slab: a clamped copy nobody reads)
+                end_step();
             }
         }
-        __syncthreads();
-        // The queued pairs get their exact distance once enough of them wait (or the range ends):
-        // 256 at a time, one per thread; then each wavefront folds the ones of its 16 queries into
-        // their lists.
-        const int waiting = *qcount;
-        if (waiting > 256 || (waiting > 0 && b0 + BT >= b_end)) {
-            for (int base = 0; base < waiting; base += 256) {
-                u64 key = EMPTY_KEY;
-                int qi = -1;
-                if (base + tid < waiting) {
-                    const u64 ent = sq[base + tid];
-                    qi = (int)(ent >> 32);
-                    const int64_t b = (int64_t)(uint32_t)ent;
-                    const float* xq = pts + (int64_t)qrow[qi] * d;
-                    const float* xb = pts + b * d;
-                    double sacc = 0.0;
-                    int t = 0;
-                    for (; t + 16 <= d; t += 16) {
-                        float4 x[4], y[4];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            x[u] = *reinterpret_cast<const float4*>(xq + t + 4 * u);
-                            y[u] = *reinterpret_cast<const float4*>(xb + t + 4 * u);
-                        }
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            sacc = exact_step<METRIC>(sacc, x[u].x, y[u].x);
-                            sacc = exact_step<METRIC>(sacc, x[u].y, y[u].y);
-                            sacc = exact_step<METRIC>(sacc, x[u].z, y[u].z);
-                            sacc = exact_step<METRIC>(sacc, x[u].w, y[u].w);
-                        }
-                    }
-                    for (; t < d; t += 4) {
-                        const float4 x = *reinterpret_cast<const float4*>(xq + t);
-                        const float4 y = *reinterpret_cast<const float4*>(xb + t);
-                        sacc = exact_step<METRIC>(sacc, x.x, y.x);
-                        sacc = exact_step<METRIC>(sacc, x.y, y.y);
-                        sacc = exact_step<METRIC>(sacc, x.z, y.z);
-                        sacc = exact_step<METRIC>(sacc, x.w, y.w);
-                    }
-                    key = pack_key(exact_finish<METRIC>(sacc), (int)b, 0);
-                    if (!(key < thr[qi])) key = EMPTY_KEY;
-                }
-                rk[tid] = key;
-                rq[tid] = qi;
-                __syncthreads();
-                for (int qq = 0; qq < 16; ++qq) {          // wavefront w owns queries 16w .. 16w+15
-                    const int mq = 16 * w + qq;
-                    for (int ch = 0; ch < 4; ++ch) {       // the round's keys, 64 at a time
-                        const u64 ck = rq[64 * ch + lane] == mq ? rk[64 * ch + lane] : EMPTY_KEY;
-                        const u64 cm = __ballot(ck != EMPTY_KEY);
-                        if (cm == 0ull) continue;
-                        const u64 lk = lane < k ? list[mq * k + lane] : EMPTY_KEY;
-                        int rl = lane, rc = 0;
-                        for (u64 mm = cm; mm; mm &= mm - 1) {
-                            const u64 cj = bcast64(ck, __ffsll((long long)mm) - 1);
-                            rl += (cj < lk) ? 1 : 0;
-                            rc += (cj < ck) ? 1 : 0;
-                        }
-                        for (int i = 0; i < k; ++i) rc += (bcast64(lk, i) < ck) ? 1 : 0;
-                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                        if (lane < k && rl < k) list[mq * k + rl] = lk;
-                        if (ck != EMPTY_KEY && rc < k) list[mq * k + rc] = ck;
-                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                    }
-                    if (lane == 0) {
-                        const u64 t = list[mq * k + (k - 1)];
-                        thr[mq] = t;
-                        thrd[mq] = t == EMPTY_KEY ? inf : key_dist(t);
-                    }
-                }
-                __syncthreads();
+        for (int64_t r = groups * RING; r < total; ++r) {
+            multiply();
+            Slot v;                                        // the staged slab's successor, loaded here
+            {
+                int t = k0n + 4 * spc;
+                t = t < d - 4 ? t : d - 4;
+                int64_t r0 = b0n + srow, r1 = b0n + srow + 32;
+                r0 = r0 < b_end ? r0 : b_end - 1;
+                r1 = r1 < b_end ? r1 : b_end - 1;
+                const int64_t rn = b0n + lane;
+                v.q0 = *reinterpret_cast<const float4*>(qp0 + t);
+                v.q1 = *reinterpret_cast<const float4*>(qp1 + t);
+                v.b0 = *reinterpret_cast<const float4*>(pts + r0 * d + t);
+                v.b1 = *reinterpret_cast<const float4*>(pts + r1 * d + t);
+                v.nb = nrm[rn < b_end ? rn : b_end - 1];
+                v.gt = __uint_as_float(__hip_atomic_load(gthr + gq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
             }
-            if (tid == 0) *qcount = 0;
-            __syncthreads();
+            stage(v, buf ^ 1);
+            end_step();
         }
     }
     __syncthreads();
@@ -450,6 +664,9 @@ static int brute_nsplit(int64_t n, int64_t nq)
     if (want > max_split) want = max_split;
     if (want < 1) want = 1;
     if (want > 1024) want = 1024;
+    // a range's offsets must fit the survivor queue's entries (k_brute_mfma)
+    const int64_t min_split = (n + (1ll << SQ_BASE_BITS) - 1) >> SQ_BASE_BITS;
+    if (want < min_split) want = min_split;
     return (int)want;
 }
 
@@ -461,8 +678,9 @@ extern "C" __attribute__((visibility("default"))) uint64_t knng_brute_workspace_
 {
     if (n < 2 || d < 1 || k < 1 || k > KNNG_MAX_K || (int64_t)k > n - 1 || nq < 0) return 0;
     uint64_t b = (uint64_t)nq * (uint64_t)brute_nsplit(n, nq) * (uint64_t)k * 8u;
-    b = (b + 255u) & ~255ull;                     // partial lists, then |x|^2 of every point (fp32, or fp64 for the cosine)
-    return b + (((uint64_t)n * 8u + 255u) & ~255ull);
+    b = (b + 255u) & ~255ull;                     // partial lists, then |x|^2 of every point (fp32, or fp64 for the cosine),
+    b += ((uint64_t)n * 8u + 255u) & ~255ull;     // then one shared bound per query (k_brute_mfma)
+    return b + (((uint64_t)nq * 4u + 255u) & ~255ull);
 }
 
 // candidates: the first n_base of the n_all points; query rows: any of the n_all points
@@ -504,19 +722,23 @@ static int brute_impl(const float* points_dev, int64_t n_all, int64_t n, int32_t
         float* nrm = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace_dev) + part_bytes);
         hipLaunchKernelGGL(k_row_norms, dim3((unsigned)((n_all * 8 + 255) / 256)), dim3(256), 0, st, points_dev, n_all, d, nrm);
         if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e, "k_row_norms launch");
-        const int mlds = 2 * BT * MLD * 4 + SQCAP * 8 + BT * k * 8 + BT * 8 + 256 * 8 + 256 * 4 + 4 * BT * 4 + 16;
+        uint32_t* gthr = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(workspace_dev) + part_bytes +
+                                                     (((uint64_t)n_all * 8u + 255u) & ~255ull));
+        hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, st, gthr, nq, 0x7f800000u);
+        if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e, "k_fill_u32 launch");
+        const int mlds = 4 * BT * MLD * 4 + SQCAP * 4 + BT * k * 8 + BT * 8 + 256 * 8 + 256 * 4 + (3 * BT + 5 * 256) * 4 + 16;
         if (metric == 0) {
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_brute_mfma<0>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, mlds);
             if (e != hipSuccess) return set_hip_error(e, "hipFuncSetAttribute(k_brute_mfma)");
             hipLaunchKernelGGL(k_brute_mfma<0>, dim3(qtiles, (unsigned)nsplit), dim3(256), mlds, st, points_dev, nrm,
-                               n, d, k, query_rows_dev, nq, chunk, nsplit, part);
+                               n, d, k, query_rows_dev, nq, chunk, nsplit, part, gthr);
         } else {
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_brute_mfma<1>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, mlds);
             if (e != hipSuccess) return set_hip_error(e, "hipFuncSetAttribute(k_brute_mfma)");
             hipLaunchKernelGGL(k_brute_mfma<1>, dim3(qtiles, (unsigned)nsplit), dim3(256), mlds, st, points_dev, nrm,
-                               n, d, k, query_rows_dev, nq, chunk, nsplit, part);
+                               n, d, k, query_rows_dev, nq, chunk, nsplit, part, gthr);
         }
     } else if (metric == 0) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_brute<0>),
