@@ -16,10 +16,18 @@
 // Gram block on the matrix cores (v_mfma_f32_16x16x4_f32: |q|^2 + |b|^2 - 2<q,b>, or 1 - <q,b>).
 // The fp32 value differs from the true distance by at most E = (d + 16) 2^-23 (|q|^2 + |b|^2)
 // (more than twice the textbook bound of a length-d fp32 dot product plus the roundings around
-// it), so a pair whose screened value minus E lies above the query's current k-th distance cannot
-// enter the list and is skipped; every other pair is evaluated in the exact fp64 recipe, and only
-// exact values are ever stored or compared.  The result is the same bit for bit; after the first
-// tiles almost every pair is skipped.
+// it), so a pair whose screened value minus E lies above a bound on the query's final k-th
+// distance cannot be in the result and is skipped; every other pair is evaluated in the exact
+// fp64 recipe, and only exact values are ever stored or compared.  The bound is the smaller of the
+// k-th distance of the workgroup's own list and the smallest k-th distance any base range of the
+// same query has published (one atomic min per query in device memory): with it all ranges
+// together evaluate about as many pairs exactly as one pass over all points would.  The result is
+// the same bit for bit whatever the timing.
+// The walk over (tile, slab of 32 coordinates) is software-pipelined: every thread keeps the
+// pieces of the next four slabs in flight in registers (all loads unconditional, from clamped
+// addresses), a slab goes to one of two LDS buffers one step before it is multiplied, with one
+// barrier per slab, and the stores and the next loads stand between the groups of four matrix
+// instructions of the step.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -218,9 +226,12 @@ constexpr int MLD = BDC + 4;      // row stride of a row-major slab: conflict-fr
 
 constexpr int SQCAP = BT * BT + 256;   // survivor queue: one whole tile on top of what may wait
 constexpr int SQ_BASE_BITS = 26;       // a queue entry: query << 26 | base point - first point of the range
-constexpr int RING = 4;                // slabs in flight from global memory per thread
+#ifndef KNNG_BRUTE_RING
+#define KNNG_BRUTE_RING 4
+#endif
+constexpr int RING = KNNG_BRUTE_RING;  // slabs in flight from global memory per thread
 
-template <int METRIC>
+template <int METRIC, bool RAGGED>
 __global__ void __launch_bounds__(256)
 k_brute_mfma(const float* __restrict__ pts, const float* __restrict__ nrm, int64_t n, int d, int k,
              const int32_t* __restrict__ query_rows, int64_t nq, int64_t base_chunk, int nsplit,
@@ -286,21 +297,22 @@ k_brute_mfma(const float* __restrict__ pts, const float* __restrict__ nrm, int64
         // Which pairs are skipped depends on timing; the result, the exact k smallest, does not.
         const int64_t gq = q0 + lane < nq ? q0 + lane : nq - 1;
         const int nslab = (d + BDC - 1) / BDC;
+        constexpr bool ragged = RAGGED;                    // d % BDC != 0: the last slab of a tile is shorter
         const int64_t total = ((b_end - b_begin + BT - 1) / BT) * nslab;
-        int64_t ib0 = b_begin;                             // the next slab to issue
+        // rows are below 2^31, and the issue position runs at most RING tiles past the range: 32-bit
+        // unsigned row arithmetic, one 32 x 32 -> 64-bit multiply-add per row address
+        uint32_t ib0 = (uint32_t)b_begin;                  // the next slab to issue
         int ik0 = 0;
+        const uint32_t rlast = (uint32_t)(b_end - 1), du = (uint32_t)d;
         auto issue = [&](Slot& s) {
             int t = ik0 + 4 * spc;
             t = t < d - 4 ? t : d - 4;
-            int64_t r0 = ib0 + srow, r1 = ib0 + srow + 32;
-            r0 = r0 < b_end ? r0 : b_end - 1;
-            r1 = r1 < b_end ? r1 : b_end - 1;
+            const uint32_t r0 = min(ib0 + (uint32_t)srow, rlast), r1 = min(ib0 + (uint32_t)srow + 32u, rlast);
             s.q0 = *reinterpret_cast<const float4*>(qp0 + t);
             s.q1 = *reinterpret_cast<const float4*>(qp1 + t);
-            s.b0 = *reinterpret_cast<const float4*>(pts + r0 * d + t);
-            s.b1 = *reinterpret_cast<const float4*>(pts + r1 * d + t);
-            const int64_t rn = ib0 + lane;
-            s.nb = nrm[rn < b_end ? rn : b_end - 1];
+            s.b0 = *reinterpret_cast<const float4*>(pts + ((uint64_t)r0 * du + (uint32_t)t));
+            s.b1 = *reinterpret_cast<const float4*>(pts + ((uint64_t)r1 * du + (uint32_t)t));
+            s.nb = nrm[min(ib0 + (uint32_t)lane, rlast)];
             s.gt = __uint_as_float(__hip_atomic_load(gthr + gq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
             ik0 += BDC;
             if (ik0 >= d) { ik0 = 0; ib0 += BT; }
@@ -315,30 +327,36 @@ k_brute_mfma(const float* __restrict__ pts, const float* __restrict__ nrm, int64
         // once enough of them wait (or the range ends), they get their exact distance, 256 at a
         // time, one per thread, and each wavefront folds the ones of its 16 queries into their lists.
         auto tile_done = [&](const int64_t b0, const floatx4 (&acc)[4], const int tp) {
-            float na[4], td[4];
-            int qrr[4];
+            // The screen, per pair one add and one compare.  With T the smaller of the query's own
+            // k-th distance and the shared bound (+inf while there is none), padded by 2^-20 of itself,
+            // and E = epsd (|q|^2 + |b|^2) (squared L2) or epsd (|q|^2 / 2 + |b|^2 / 2 + 1) (1 - <q,b>)
+            // the bound on the fp32 value's error, a pair can be ruled out if the fp32 distance
+            // minus E lies above T, that is if <q,b> < hq + hb with
+            //   squared L2:  hq = (1 - epsd) |q|^2 / 2 - T / 2,   hb = (1 - epsd) |b|^2 / 2
+            //   1 - <q,b>:   hq = 1 - T - epsd - epsd |q|^2 / 2,  hb = -epsd |b|^2 / 2
+            // (the few roundings of hq + hb are far inside E, which is more than twice the bound of
+            // a length-d fp32 dot product).  A pair whose test is not decidedly "below" (a NaN) stays,
+            // and so does the pair of a query with itself: the exact step drops that one.
+            float hq[4];
+            uint32_t vm = 0;                               // the lane's queries that exist
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int qi = 16 * w + 4 * kq + r;
-                na[r] = qn[qi]; td[r] = fminf(thrd[qi], gthl[64 * w + qi]) * 1.000001f; qrr[r] = qrow[qi];
+                const float t = fminf(thrd[qi], gthl[64 * w + qi]) * 1.000001f;
+                hq[r] = METRIC == 0 ? 0.5f * (1.0f - epsd) * qn[qi] - 0.5f * t : 1.0f - t - epsd - 0.5f * epsd * qn[qi];
+                vm |= qrow[qi] >= 0 ? 1u << r : 0u;
             }
-            // one bit per pair of the lane (4c + r); an unused query row never passes
-#pragma unroll
-            for (int r = 0; r < 4; ++r) td[r] = qrr[r] >= 0 ? td[r] : -inf;
-            uint32_t pm = 0;
+            uint32_t pm = 0;                               // one bit per pair of the lane (4c + r)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int b = (int)b0 + 16 * c + r16;      // ids fit 31 bits
                 const float nb = bn[tp * 256 + 64 * w + 16 * c + r16];
+                const float hb = METRIC == 0 ? 0.5f * (1.0f - epsd) * nb : -0.5f * epsd * nb;
                 uint32_t pc = 0;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float l, e;
-                    if (METRIC == 0) { l = na[r] + nb - 2.0f * acc[c][r]; e = epsd * (na[r] + nb); }
-                    else { l = 1.0f - acc[c][r]; e = epsd * (0.5f * (na[r] + nb) + 1.0f); }
-                    pc |= (!(l - e > td[r]) & (b != qrr[r])) ? (1u << r) : 0u;
-                }
-                pm |= (int64_t)b < b_end ? pc << (4 * c) : 0u;
+                for (int r = 0; r < 4; ++r)
+                    pc |= !(acc[c][r] < hq[r] + hb) ? 1u << r : 0u;
+                pm |= (int64_t)b < b_end ? (pc & vm) << (4 * c) : 0u;
             }
             if (__ballot(pm != 0u) != 0ull) {
                 // one reservation in the queue per wavefront: the lanes' counts summed bit by bit,
@@ -400,7 +418,7 @@ k_brute_mfma(const float* __restrict__ pts, const float* __restrict__ nrm, int64
                         }
                         const float dist = exact_finish<METRIC>(sacc);
                         key = pack_key(dist, (int)b, 0);
-                        if (!(key < thr[qi]) || dist > gthl[64 * w + qi]) key = EMPTY_KEY;
+                        if (!(key < thr[qi]) || dist > gthl[64 * w + qi] || (int)b == qrow[qi]) key = EMPTY_KEY;
                     }
                     rk[tid] = key;
                     rq[tid] = qi;
@@ -518,13 +536,14 @@ k_brute_mfma(const float* __restrict__ pts, const float* __restrict__ nrm, int64
                     b[h][c] = *reinterpret_cast<const float4*>(bs + (16 * c + r16) * MLD + 4 * kq + 16 * h);
             }
             const bool dead = k0n + BDC > d && !(k0n + 4 * spc < d);   // a piece past d of a last slab
-            auto live = [&](float4 x) { return float4{dead ? 0.0f : x.x, dead ? 0.0f : x.y, dead ? 0.0f : x.z, dead ? 0.0f : x.w}; };
+            auto live = [&](float4 x) {
+                if (ragged) x = float4{dead ? 0.0f : x.x, dead ? 0.0f : x.y, dead ? 0.0f : x.z, dead ? 0.0f : x.w};
+                return x;
+            };
             int t = ik0 + 4 * spc;
             t = t < d - 4 ? t : d - 4;
-            int64_t r0 = ib0 + srow, r1 = ib0 + srow + 32;
-            r0 = r0 < b_end ? r0 : b_end - 1;
-            r1 = r1 < b_end ? r1 : b_end - 1;
-            const int64_t rn = ib0 + lane;
+            const uint32_t r0 = min(ib0 + (uint32_t)srow, rlast), r1 = min(ib0 + (uint32_t)srow + 32u, rlast);
+            const uint32_t rn = min(ib0 + (uint32_t)lane, rlast);
 #define KNNG_MM(h, e) \
             _Pragma("unroll") for (int c = 0; c < 4; ++c) \
                 acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[h].e, b[h][c].e, acc[c], 0, 0, 0); \
@@ -549,11 +568,11 @@ k_brute_mfma(const float* __restrict__ pts, const float* __restrict__ nrm, int64
             nx.q1 = *reinterpret_cast<const float4*>(qp1 + t);
             __builtin_amdgcn_sched_barrier(0);
             KNNG_MM(1, y);
-            nx.b0 = *reinterpret_cast<const float4*>(pts + r0 * d + t);
-            nx.b1 = *reinterpret_cast<const float4*>(pts + r1 * d + t);
+            nx.b0 = *reinterpret_cast<const float4*>(pts + ((uint64_t)r0 * du + (uint32_t)t));
+            nx.b1 = *reinterpret_cast<const float4*>(pts + ((uint64_t)r1 * du + (uint32_t)t));
             __builtin_amdgcn_sched_barrier(0);
             KNNG_MM(1, z);
-            nx.nb = nrm[rn < b_end ? rn : b_end - 1];
+            nx.nb = nrm[rn];
             nx.gt = __uint_as_float(__hip_atomic_load(gthr + gq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
             __builtin_amdgcn_sched_barrier(0);
             KNNG_MM(1, w);
@@ -727,19 +746,18 @@ static int brute_impl(const float* points_dev, int64_t n_all, int64_t n, int32_t
         hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, st, gthr, nq, 0x7f800000u);
         if ((e = hipGetLastError()) != hipSuccess) return set_hip_error(e, "k_fill_u32 launch");
         const int mlds = 4 * BT * MLD * 4 + SQCAP * 4 + BT * k * 8 + BT * 8 + 256 * 8 + 256 * 4 + (3 * BT + 5 * 256) * 4 + 16;
-        if (metric == 0) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_brute_mfma<0>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, mlds);
-            if (e != hipSuccess) return set_hip_error(e, "hipFuncSetAttribute(k_brute_mfma)");
-            hipLaunchKernelGGL(k_brute_mfma<0>, dim3(qtiles, (unsigned)nsplit), dim3(256), mlds, st, points_dev, nrm,
+        auto launch = [&](auto kern) -> hipError_t {
+            const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                      hipFuncAttributeMaxDynamicSharedMemorySize, mlds);
+            if (ea != hipSuccess) return ea;
+            hipLaunchKernelGGL(kern, dim3(qtiles, (unsigned)nsplit), dim3(256), mlds, st, points_dev, nrm,
                                n, d, k, query_rows_dev, nq, chunk, nsplit, part, gthr);
-        } else {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_brute_mfma<1>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, mlds);
-            if (e != hipSuccess) return set_hip_error(e, "hipFuncSetAttribute(k_brute_mfma)");
-            hipLaunchKernelGGL(k_brute_mfma<1>, dim3(qtiles, (unsigned)nsplit), dim3(256), mlds, st, points_dev, nrm,
-                               n, d, k, query_rows_dev, nq, chunk, nsplit, part, gthr);
-        }
+            return hipSuccess;
+        };
+        const bool ragged = d % BDC != 0;
+        if (metric == 0) e = ragged ? launch(k_brute_mfma<0, true>) : launch(k_brute_mfma<0, false>);
+        else e = ragged ? launch(k_brute_mfma<1, true>) : launch(k_brute_mfma<1, false>);
+        if (e != hipSuccess) return set_hip_error(e, "hipFuncSetAttribute(k_brute_mfma)");
     } else if (metric == 0) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_brute<0>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
