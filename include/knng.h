@@ -58,7 +58,9 @@ enum {
     KNNG_EINVAL = -1,      /* bad argument (null pointer, n < 2, k < 1, k > n-1, ...) */
     KNNG_EWORKSPACE = -2,  /* workspace missing or smaller than knng_*_workspace_bytes */
     KNNG_EHIP = -3,        /* a HIP call failed; knng_strerror(KNNG_EHIP) has its text */
-    KNNG_ETOOLARGE = -4    /* more input than an entry point with fixed scratch memory takes */
+    KNNG_ETOOLARGE = -4,   /* more input than an entry point with fixed scratch memory takes */
+    KNNG_ECHECK = -5       /* knng_params_t.check_rows: a row broke an invariant (a bug in the
+                              library); the outputs are written all the same                  */
 };
 
 enum { KNNG_METRIC_L2SQ = 0, KNNG_METRIC_IP_UNIT = 1, KNNG_METRIC_COSINE = 2 };
@@ -90,6 +92,7 @@ typedef struct knng_stats {
                                   precision (long fp32 rows, or samples above 16: the Gram
                                   block on bf16 halves) chose a partner far closer to a member
                                   than both are to the point, and was repeated in fp32        */
+    uint64_t row_violations;   /* knng_params_t.check_rows: invariants found broken, whole build */
 } knng_stats_t;
 
 /*
@@ -121,6 +124,16 @@ typedef struct knng_params {
                                  class, 8-byte aligned) for the convergence counter the host
                                  reads once per iteration; NULL = the call allocates and frees
                                  its own, which costs a page-locked allocation per build       */
+    uint32_t check_rows;      /* debug mode, nonzero: after every merge a kernel checks every
+                                 point's state -- row sorted by (distance, id), ids distinct,
+                                 in range and not the point, distances real and >= 0, the
+                                 row's farthest distance as the join will read it, candidate
+                                 slots empty again, sample sizes <= ceil(rho K), sampled ids in
+                                 range, every id of the row in the row's signature (the joins
+                                 rely on it: Sec. 3.1.1's single owner leaves the row itself
+                                 race-free, these are what the lock-free parts must keep).
+                                 A violation makes the call return KNNG_ECHECK.  Slow.          */
+    uint32_t reserved;        /* 0 */
 } knng_params_t;
 
 /* Device scratch needed by knng_build_knn_graph for these sizes (0 on bad arguments).

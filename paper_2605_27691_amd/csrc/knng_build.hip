@@ -405,6 +405,55 @@ k_update(int64_t n, int K, int C, int s, u64 seed, uint32_t iter, int do_sample,
 }
 
 // ------------------------------------------------------------------------------------------
+// k_check_rows (debug mode): one wavefront per point, after k_update; counts broken invariants.
+// sampled: k_update also sampled (lists, counts and signature are current).
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_check_rows(int64_t n, int K, int C, int s, uint32_t iter, int sampled, const u64* __restrict__ G,
+             const u64* __restrict__ cand, const int32_t* __restrict__ newl, const int32_t* __restrict__ oldl,
+             const int32_t* __restrict__ cnt, const uint32_t* __restrict__ sig, const float* __restrict__ worst,
+             u64* __restrict__ violations)
+{
+    const int lane = lane_id();
+    const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= n) return;
+    const bool in = lane < K;
+    const u64 e = in ? G[v * K + lane] : EMPTY_KEY;
+    const int id = key_id(e);
+    const uint32_t db = (uint32_t)(e >> 32);
+    bool bad = false;
+    if (in) {
+        bad |= e == EMPTY_KEY;                                   // rows are full from the start
+        bad |= id < 0 || (int64_t)id >= n || (int64_t)id == v;
+        bad |= (db >> 31) != 0u || db > 0x7f800000u;             // negative, or not a number
+    }
+    // strictly ascending in (distance, id)
+    const u64 nxt = __shfl(key_order(e), lane + 1 < K ? lane + 1 : lane);
+    if (lane + 1 < K) bad |= !(key_order(e) < nxt);
+    // ids pairwise distinct
+    for (int j = 0; j < K; ++j) {
+        const int idj = (int)bcast32((uint32_t)id, j);
+        if (in && lane != j && idj == id) bad = true;
+    }
+    if (lane == K - 1) bad |= __float_as_uint(worst[v]) != db;   // the threshold the join compares against
+    if (lane < C) bad |= cand[v * C + lane] != EMPTY_KEY;        // the merge empties what it used
+    if (sampled) {
+        const int cn = cnt[v * 2 + 0], co = cnt[v * 2 + 1];
+        if (lane == 0) bad |= cn < 0 || cn > s || co < 0 || co > s;
+        if (lane < s) {
+            if (lane < cn) { const int u = newl[v * 2 * (int64_t)s + lane]; bad |= u < 0 || (int64_t)u >= n; }
+            if (lane < co) { const int u = oldl[v * 2 * (int64_t)s + lane]; bad |= u < 0 || (int64_t)u >= n; }
+        }
+        if (in && !(id < 0 || (int64_t)id >= n)) {
+            const uint32_t h = sig_bit(id, iter);
+            bad |= ((sig[v * SIG_WORDS + (h >> 5)] >> (h & 31u)) & 1u) == 0u;
+        }
+    }
+    const u64 m = __ballot(bad);
+    if (lane == 0 && m != 0ull) atomicAdd(violations, (u64)__popcll(m));
+}
+
+// ------------------------------------------------------------------------------------------
 // k_plan: after sampling, turn every point's reverse buckets into its reverse lists (the
 // non-empty buckets in bucket order, decoded, at most s: a random subset, since bucket numbers
 // are hashes), fix the four list lengths for the join, append the points that have anything new
@@ -1574,7 +1623,7 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
     int32_t* redo = reinterpret_cast<int32_t*>(ws + bp.off_redo);
     float* worst = reinterpret_cast<float*>(ws + bp.off_worst);
     uint32_t* sig = reinterpret_cast<uint32_t*>(ws + bp.off_sig);
-    u64* ctr = reinterpret_cast<u64*>(ws + bp.off_ctr);      // [0] updates [1] rows gathered [2] active [3] pairs [4] offers [5] occupied slots [6] points left to the fp32 join
+    u64* ctr = reinterpret_cast<u64*>(ws + bp.off_ctr);      // [0] updates [1] rows gathered [2] active [3] pairs [4] offers [5] occupied slots [6] points left to the fp32 join [7] check_rows: violations
     knng_stats_t* stats = params->stats_host;
     const bool vec = (d % (elem == 1 ? 16 : elem == 2 ? 8 : 4) == 0) && ((reinterpret_cast<uintptr_t>(points_dev) & 15u) == 0);
     const unsigned row_blocks = (unsigned)((n + 3) / 4);
@@ -1591,6 +1640,7 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
     const int n_ev = stats ? 8 + 4 * max_rec : 0;
     hipEvent_t* ev = nullptr;
     int iters = 0, converged = 0;
+    u64 violations = 0;                              // check_rows: broken invariants so far
     if (stats) memset(stats, 0, sizeof(*stats));
     // statistics only: an event per recorded point of the stream, created the first time it is used
     auto record = [&](int i) -> hipError_t {
@@ -1640,6 +1690,11 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
                            params->seed, params->init_ids_dev, G, cand, cnt, worst, rev, bp.B);
     HIPCHK(hipGetLastError());
     if (stats) HIPCHK(record(1));
+    if (params->check_rows) {                        // the start state
+        hipLaunchKernelGGL(k_check_rows, dim3(row_blocks), dim3(256), 0, st, n, bp.K, bp.C, bp.s, 0u, 0, G, cand,
+                           newl, oldl, cnt, sig, worst, ctr + 7);
+        HIPCHK(hipGetLastError());
+    }
 
     // Iteration it: k_update merges what join it-1 offered and samples for join it; the host
     // reads the update count of iteration it-1 (the only device->host crossing of the loop)
@@ -1653,10 +1708,16 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
         HIPCHK(hipGetLastError());
         if (rec) HIPCHK(record(2 + 4 * it));
         if (stats && !more) HIPCHK(record(n_ev - 2));
+        if (params->check_rows) {
+            hipLaunchKernelGGL(k_check_rows, dim3(row_blocks), dim3(256), 0, st, n, bp.K, bp.C, bp.s, (uint32_t)it,
+                               more ? 1 : 0, G, cand, newl, oldl, cnt, sig, worst, ctr + 7);
+            HIPCHK(hipGetLastError());
+        }
         if (it > 0) {
-            HIPCHK(hipMemcpyAsync(host_ctr, ctr, 56, hipMemcpyDeviceToHost, st));
-            HIPCHK(hipMemsetAsync(ctr, 0, 56, st));
+            HIPCHK(hipMemcpyAsync(host_ctr, ctr, 64, hipMemcpyDeviceToHost, st));
+            HIPCHK(hipMemsetAsync(ctr, 0, 64, st));
             HIPCHK(hipStreamSynchronize(st));
+            violations += host_ctr[7];
             if (stats && it - 1 < max_rec) {
                 stats->updates[it - 1] = host_ctr[0];
                 stats->join_rows[it - 1] = host_ctr[1];
@@ -1705,8 +1766,15 @@ static int build_impl(const void* points_void, int elem, int64_t n, int32_t d, i
         HIPCHK(hipGetLastError());
     }
     if (stats) HIPCHK(record(n_ev - 1));
+    if (params->check_rows && bp.max_iters == 0) {   // no iteration read the counter: the start state's check
+        HIPCHK(hipMemcpyAsync(host_ctr, ctr, 64, hipMemcpyDeviceToHost, st));
+        HIPCHK(hipStreamSynchronize(st));
+        violations += host_ctr[7];
+    }
     HIPCHK(hipStreamSynchronize(st));
+    if (violations) rc = KNNG_ECHECK;
     if (stats) {
+        stats->row_violations = violations;
         stats->iterations = iters;
         stats->converged = converged;
         float ms = 0.0f;

@@ -210,6 +210,7 @@ extern "C" __attribute__((visibility("default"))) const char* knng_strerror(int 
     case KNNG_EWORKSPACE: return "workspace missing, misaligned or too small";
     case KNNG_EHIP: return g_hip_msg;
     case KNNG_ETOOLARGE: return "input larger than the fixed scratch of this entry point allows";
+    case KNNG_ECHECK: return "debug check: a row broke an invariant";
     default: return "unknown libknng error code";
     }
 }

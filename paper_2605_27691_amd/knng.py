@@ -33,7 +33,8 @@ class Stats(ctypes.Structure):
                 ("pairs", ctypes.c_uint64),
                 ("cand_kept", ctypes.c_uint64),
                 ("joined", ctypes.c_uint64),
-                ("rejoined", ctypes.c_uint64)]
+                ("rejoined", ctypes.c_uint64),
+                ("row_violations", ctypes.c_uint64)]
 
 
 class Params(ctypes.Structure):
@@ -49,7 +50,9 @@ class Params(ctypes.Structure):
                 ("workspace_dev", _P),
                 ("workspace_bytes", ctypes.c_uint64),
                 ("stats_host", ctypes.POINTER(Stats)),
-                ("pinned_host", _P)]
+                ("pinned_host", _P),
+                ("check_rows", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32)]
 
 
 EXPORTS = ("knng_build_workspace_bytes", "knng_build_cosine_extra_bytes", "knng_build_knn_graph", "knng_build_knn_graph_u8", "knng_build_knn_graph_f16",
@@ -137,6 +140,30 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
+def _shape(t, shape, name):
+    """The library takes sizes as scalars and cannot see how much memory stands behind a pointer:
+    an array of another shape than those scalars say would be read or written past its end."""
+    if t is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t
+
+
+def _room(t, shape, name):
+    """An output array: at least as many elements as the library writes."""
+    need = 1
+    for e in shape:
+        need *= int(e)
+    if t is not None and t.numel() < need:
+        raise ValueError(f"{name}: room for {t.numel()} elements, {need} ({tuple(shape)}) are written")
+    return t
+
+
+def _matrix(t, name):
+    if t is not None and t.dim() != 2:
+        raise ValueError(f"{name}: expected a 2-D tensor, got {tuple(t.shape)}")
+    return t
+
+
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -156,11 +183,12 @@ def knng_version() -> int:
     return int(load().knng_version())
 
 
-def make_params(k_build=0, rho=0.0, delta=0.0, max_iters=0, cand_cap=0, seed=0) -> Params:
+def make_params(k_build=0, rho=0.0, delta=0.0, max_iters=0, cand_cap=0, seed=0, check_rows=False) -> Params:
     p = Params()
     p.struct_size = ctypes.sizeof(Params)
     p.k_build, p.rho, p.delta, p.max_iters, p.cand_cap, p.seed = (
         int(k_build), float(rho), float(delta), int(max_iters), int(cand_cap), int(seed))
+    p.check_rows = 1 if check_rows else 0
     return p
 
 
@@ -169,11 +197,11 @@ def knng_build_workspace_bytes(n, d, k, params=None) -> int:
 
 
 def _build_graph(entry, dtype, points, k, metric, k_build, rho, delta, max_iters, cand_cap, seed,
-                 init_ids, workspace, want_stats, ids_out, dists_out):
+                 init_ids, workspace, want_stats, ids_out, dists_out, check_rows=False):
     L = load()
-    points = _dev(points, dtype, "points")
+    points = _matrix(_dev(points, dtype, "points"), "points")
     n, d = points.shape
-    p = make_params(k_build, rho, delta, max_iters, cand_cap, seed)
+    p = make_params(k_build, rho, delta, max_iters, cand_cap, seed, check_rows)
     need = int(L.knng_build_workspace_bytes(n, d, k, ctypes.byref(p)))
     if need == 0:
         raise KnngError(-1)
@@ -182,13 +210,13 @@ def _build_graph(entry, dtype, points, k, metric, k_build, rho, delta, max_iters
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=points.device)
     workspace = _dev(workspace, torch.uint8, "workspace")
-    init_ids = _dev(init_ids, torch.int32, "init_ids")
+    init_ids = _shape(_dev(init_ids, torch.int32, "init_ids"), (n, int(k_build) or int(k)), "init_ids")   # [n][K]
     if ids_out is None:
         ids_out = torch.empty((n, k), dtype=torch.int32, device=points.device)
     if dists_out is None:
         dists_out = torch.empty((n, k), dtype=torch.float32, device=points.device)
-    ids_out = _dev(ids_out, torch.int32, "ids_out")
-    dists_out = _dev(dists_out, torch.float32, "dists_out")
+    ids_out = _room(_dev(ids_out, torch.int32, "ids_out"), (n, k), "ids_out")
+    dists_out = _room(_dev(dists_out, torch.float32, "dists_out"), (n, k), "dists_out")
     st = Stats() if want_stats else None
     p.init_ids_dev = _ptr(init_ids)
     p.stream = _stream()
@@ -206,13 +234,14 @@ def _build_graph(entry, dtype, points, k, metric, k_build, rho, delta, max_iters
                  "join_rows": list(st.join_rows[:it]), "ms_init": st.ms_init,
                  "ms_sample": st.ms_sample, "ms_join": st.ms_join, "ms_merge": st.ms_merge,
                  "ms_finalize": st.ms_finalize, "ms_total": st.ms_total,
-                 "offers": int(st.offers), "pairs": int(st.pairs), "cand_kept": int(st.cand_kept), "joined": int(st.joined), "rejoined": int(st.rejoined)}
+                 "offers": int(st.offers), "pairs": int(st.pairs), "cand_kept": int(st.cand_kept), "joined": int(st.joined), "rejoined": int(st.rejoined),
+                 "row_violations": int(st.row_violations)}
     return ids_out, dists_out, stats
 
 
 def knng_build_knn_graph(points, k, metric=L2SQ, *, k_build=0, rho=0.0, delta=0.0, max_iters=0,
                          cand_cap=0, seed=0, init_ids=None, workspace=None, want_stats=True,
-                         ids_out=None, dists_out=None):
+                         ids_out=None, dists_out=None, check_rows=False):
     """Approximate k-NN graph of `points` ([n][d] fp32, GPU).  -> (ids, dists, stats | None).
 
     Zero-valued keyword parameters select the library defaults; max_iters=-1 runs
@@ -220,23 +249,23 @@ def knng_build_knn_graph(points, k, metric=L2SQ, *, k_build=0, rho=0.0, delta=0.
     allocated here when not given.
     """
     return _build_graph("knng_build_knn_graph", torch.float32, points, k, metric, k_build, rho, delta,
-                        max_iters, cand_cap, seed, init_ids, workspace, want_stats, ids_out, dists_out)
+                        max_iters, cand_cap, seed, init_ids, workspace, want_stats, ids_out, dists_out, check_rows)
 
 
 def knng_build_knn_graph_u8(points, k, metric=L2SQ, *, k_build=0, rho=0.0, delta=0.0, max_iters=0,
                             cand_cap=0, seed=0, init_ids=None, workspace=None, want_stats=True,
-                            ids_out=None, dists_out=None):
+                            ids_out=None, dists_out=None, check_rows=False):
     """The same for `points` stored as [n][d] uint8 (GPU): squared L2 only, d % 4 == 0."""
     return _build_graph("knng_build_knn_graph_u8", torch.uint8, points, k, metric, k_build, rho, delta,
-                        max_iters, cand_cap, seed, init_ids, workspace, want_stats, ids_out, dists_out)
+                        max_iters, cand_cap, seed, init_ids, workspace, want_stats, ids_out, dists_out, check_rows)
 
 
 def knng_build_knn_graph_f16(points, k, metric=L2SQ, *, k_build=0, rho=0.0, delta=0.0, max_iters=0,
                              cand_cap=0, seed=0, init_ids=None, workspace=None, want_stats=True,
-                             ids_out=None, dists_out=None):
+                             ids_out=None, dists_out=None, check_rows=False):
     """The same for `points` stored as [n][d] float16 (GPU): squared L2 only, d % 2 == 0."""
     return _build_graph("knng_build_knn_graph_f16", torch.float16, points, k, metric, k_build, rho, delta,
-                        max_iters, cand_cap, seed, init_ids, workspace, want_stats, ids_out, dists_out)
+                        max_iters, cand_cap, seed, init_ids, workspace, want_stats, ids_out, dists_out, check_rows)
 
 
 def knng_brute_workspace_bytes(n, d, k, nq) -> int:
@@ -247,10 +276,12 @@ def knng_brute_knn(points, k, metric=L2SQ, query_rows=None, workspace=None, n_ba
     """Exact k-NN rows of all points, or of `query_rows` (int32 GPU tensor), among all points or
     (knng_brute_knn_base) the first `n_base`.  -> (ids, dists)."""
     L = load()
-    points = _dev(points, torch.float32, "points")
+    points = _matrix(_dev(points, torch.float32, "points"), "points")
     n, d = points.shape
     query_rows = _dev(query_rows, torch.int32, "query_rows")
     nq = n if query_rows is None else query_rows.numel()
+    if query_rows is not None and nq > 0 and not (int(query_rows.min()) >= 0 and int(query_rows.max()) < n):
+        raise ValueError("query_rows: row numbers must lie in [0, n)")   # the kernels index the points with them
     need = int(L.knng_brute_workspace_bytes(n, d, k, nq))
     if need == 0:
         raise KnngError(-1)
@@ -277,8 +308,10 @@ def knng_graph_recall(test_ids, test_dists, ref_ids, ref_dists, at_k, mode=0) ->
     ref_dists = _dev(ref_dists, torch.float32, "ref_dists")
     t = test_ids if test_ids is not None else test_dists
     r = ref_ids if ref_ids is not None else ref_dists
-    if t is None or r is None or t.shape[0] != r.shape[0]:
+    if t is None or r is None or t.dim() != 2 or r.dim() != 2 or t.shape[0] != r.shape[0]:
         raise KnngError(-1)
+    _shape(test_dists, t.shape, "test_dists")
+    _shape(ref_dists, r.shape, "ref_dists")
     out = ctypes.c_double(0.0)
     _check(L.knng_graph_recall(_ptr(test_ids), _ptr(test_dists), t.shape[1], _ptr(ref_ids),
                                _ptr(ref_dists), r.shape[1], t.shape[0], at_k, mode,
@@ -296,11 +329,15 @@ def knng_graph_recall_static(test_ids, test_dists, ref_ids, ref_dists, at_k, mod
     ref_dists = _dev(ref_dists, torch.float32, "ref_dists")
     t = test_ids if test_ids is not None else test_dists
     r = ref_ids if ref_ids is not None else ref_dists
-    if t is None or r is None or t.shape[0] != r.shape[0]:
+    if t is None or r is None or t.dim() != 2 or r.dim() != 2 or t.shape[0] != r.shape[0]:
         raise KnngError(-1)
+    _shape(test_dists, t.shape, "test_dists")
+    _shape(ref_dists, r.shape, "ref_dists")
     if out is None:
         out = torch.empty(1, dtype=torch.float64, device=t.device)
     out = _dev(out, torch.float64, "out")
+    if out.numel() < 1:
+        raise ValueError("out: expected one float64 element")
     _check(L.knng_graph_recall_static(_ptr(test_ids), _ptr(test_dists), t.shape[1], _ptr(ref_ids),
                                       _ptr(ref_dists), r.shape[1], t.shape[0], at_k, mode, _ptr(out), _stream()))
     return out
@@ -315,6 +352,8 @@ def knng_merge_graphs(ids_a, dists_a, ids_b, dists_b, k_out, ids_out=None, dists
     dists_b = _dev(dists_b, torch.float32, "dists_b")
     if ids_a is None or ids_b is None or dists_a is None or dists_b is None:
         raise KnngError(-1)
+    if ids_a.dim() != 2 or ids_b.dim() != 2:
+        raise KnngError(-1)
     if ids_a.shape != dists_a.shape or ids_b.shape != dists_b.shape or ids_a.shape[0] != ids_b.shape[0]:
         raise KnngError(-1)
     n = ids_a.shape[0]
@@ -322,9 +361,10 @@ def knng_merge_graphs(ids_a, dists_a, ids_b, dists_b, k_out, ids_out=None, dists
         ids_out = torch.empty((n, k_out), dtype=torch.int32, device=ids_a.device)
     if dists_out is None:
         dists_out = torch.empty((n, k_out), dtype=torch.float32, device=ids_a.device)
+    ids_out = _room(_dev(ids_out, torch.int32, "ids_out"), (n, k_out), "ids_out")
+    dists_out = _room(_dev(dists_out, torch.float32, "dists_out"), (n, k_out), "dists_out")
     _check(L.knng_merge_graphs(_ptr(ids_a), _ptr(dists_a), ids_a.shape[1], _ptr(ids_b), _ptr(dists_b),
-                               ids_b.shape[1], n, k_out, _ptr(_dev(ids_out, torch.int32, "ids_out")),
-                               _ptr(_dev(dists_out, torch.float32, "dists_out")), _stream()))
+                               ids_b.shape[1], n, k_out, _ptr(ids_out), _ptr(dists_out), _stream()))
     return ids_out, dists_out
 
 
@@ -335,7 +375,7 @@ def knng_optimize_workspace_bytes(n, k, d_out) -> int:
 def knng_optimize_graph(ids, d_out, workspace=None, ids_out=None):
     """Search graph of the k-NN graph `ids` ([n][k] int32, GPU, nearest first).  -> ids [n][d_out]."""
     L = load()
-    ids = _dev(ids, torch.int32, "ids")
+    ids = _matrix(_dev(ids, torch.int32, "ids"), "ids")
     n, k = ids.shape
     need = int(L.knng_optimize_workspace_bytes(n, k, d_out))
     if need == 0:
@@ -345,7 +385,7 @@ def knng_optimize_graph(ids, d_out, workspace=None, ids_out=None):
     workspace = _dev(workspace, torch.uint8, "workspace")
     if ids_out is None:
         ids_out = torch.empty((n, d_out), dtype=torch.int32, device=ids.device)
-    ids_out = _dev(ids_out, torch.int32, "ids_out")
+    ids_out = _room(_dev(ids_out, torch.int32, "ids_out"), (n, max(int(d_out), 0)), "ids_out")
     _check(L.knng_optimize_graph(_ptr(ids), n, k, d_out, _ptr(ids_out), _ptr(workspace), workspace.numel(),
                                  _stream()))
     return ids_out
@@ -356,10 +396,10 @@ def _graph_search(entry, dtype, points, graph, queries, starts, k_s, itopk, widt
     ([nq][n_starts] int32); all GPU tensors.
     -> (ids [nq][k_s], dists [nq][k_s][, iterations per query, distance evaluations per query])."""
     L = load()
-    points = _dev(points, dtype, "points")
-    queries = _dev(queries, dtype, "queries")
-    graph = _dev(graph, torch.int32, "graph")
-    starts = _dev(starts, torch.int32, "starts")
+    points = _matrix(_dev(points, dtype, "points"), "points")
+    queries = _matrix(_dev(queries, dtype, "queries"), "queries")
+    graph = _matrix(_dev(graph, torch.int32, "graph"), "graph")
+    starts = _matrix(_dev(starts, torch.int32, "starts"), "starts")
     n, d = points.shape
     nq = queries.shape[0]
     if queries.shape[1] != d or graph.shape[0] != n or starts.shape[0] != nq:

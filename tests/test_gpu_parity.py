@@ -383,6 +383,48 @@ def _rows_of_any_length(n, d, seed, zeros=3, repeats=20):
     return x.astype(np.float32)
 
 
+@pytest.mark.parametrize("elem,idx,n,kb,rho,cap", [
+    ("f32", 2, 20_000, 32, 0.5, 0),       # wavefront join
+    ("f32", 3, 12_000, 32, 0.5, 0),       # 1 - <a,b>
+    ("f32", 4, 5_000, 32, 0.5, 0),        # bf16-split Gram pass, some joins repeated in fp32
+    ("f32", 1, 9_001, 48, 0.5, 0),        # workgroup join, 96 member slots
+    ("f32", 1, 7_003, 64, 0.5, 0),        # 128 member slots
+    ("f32", 1, 3_001, 64, 1.0, 0),        # 256 member slots
+    ("f32", 2, 8_000, 32, 0.5, 8),        # eight candidate slots: heavy contention in the lock-free lists
+    ("u8", 2, 15_000, 32, 0.5, 0),
+    ("f16", 4, 5_000, 32, 0.5, 0),
+    ("f32", 1, 2_500, 24, 0.7, 0)])
+def test_build_debug_mode_finds_no_broken_invariant(elem, idx, n, kb, rho, cap):
+    """check_rows: after the start state and after every merge a kernel looks at every point (row sorted
+    and duplicate-free, threshold, emptied candidate slots, sample sizes, signature holding every id of
+    the row).  The lock-free parts must keep these whatever the interleaving; any violation makes the
+    call fail, and the count comes back in the statistics."""
+    x, w = workloads.make(idx, n=n)
+    k = min(w.k, kb)
+    xg = _gpu(x)
+    if elem == "u8":
+        fn, xg = knng.knng_build_knn_graph_u8, xg.to(torch.uint8)
+    elif elem == "f16":
+        fn, xg = knng.knng_build_knn_graph_f16, xg.to(torch.float16)
+    else:
+        fn = knng.knng_build_knn_graph
+    metric = w.metric if elem == "f32" else 0
+    ids, dists, st = fn(xg, k, metric, k_build=kb, rho=rho, cand_cap=cap, seed=11, check_rows=True)
+    assert st["row_violations"] == 0 and st["iterations"] >= 3
+    ids2, dists2, st2 = fn(xg, k, metric, k_build=kb, rho=rho, cand_cap=cap, seed=11)
+    assert torch.equal(ids, ids2) and torch.equal(dists, dists2)      # looking does not change the build
+    # the start state alone (no iteration), and a warm start from the result
+    _, _, st0 = fn(xg, k, metric, k_build=kb, rho=rho, seed=11, max_iters=-1, check_rows=True)
+    assert st0["row_violations"] == 0 and st0["iterations"] == 0
+    if elem == "f32":
+        init = torch.full((n, kb), -1, dtype=torch.int32, device=DEV)     # [n][K]: the rest is redrawn
+        init[:, :k] = ids
+        _, _, st3 = fn(xg, k, metric, k_build=kb, rho=rho, seed=12, init_ids=init, check_rows=True)
+        assert st3["row_violations"] == 0
+        with pytest.raises(ValueError):                                   # [n][k] where [n][K] is read
+            fn(xg, k, metric, k_build=kb + 1 if kb < 64 else 63, rho=rho, init_ids=init)
+
+
 @pytest.mark.parametrize("n,d,k", [(3000, 32, 10), (1500, 13, 7), (2000, 128, 32), (65, 4, 64)])
 def test_brute_cosine_bit_exact(n, d, k):
     x = _rows_of_any_length(n, d, seed=n + d)

@@ -30,9 +30,9 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layouts_match_the_header_sizes():
     # params: u32 i32 f32 f32 i32 i32 u64 ptr ptr ptr u64 ptr ptr = 80 bytes on LP64
-    assert ctypes.sizeof(knng.Params) == 80
+    assert ctypes.sizeof(knng.Params) == 88
     # stats: 2*i32 + 128*u64 + 128*f32 + 128*u64 + 6*f32 + 5*u64 (8-byte aligned)
-    assert ctypes.sizeof(knng.Stats) == 8 + 1024 + 512 + 1024 + 24 + 8 + 8 + 8 + 8 + 8
+    assert ctypes.sizeof(knng.Stats) == 8 + 1024 + 512 + 1024 + 24 + 8 + 8 + 8 + 8 + 8 + 8
 
 
 def test_workspace_queries_are_host_only_and_validate():
