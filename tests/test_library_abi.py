@@ -57,11 +57,37 @@ def test_workspace_queries_are_host_only_and_validate():
     assert knng.knng_brute_workspace_bytes(1000, 16, 8, -1) == 0
 
 
+def test_brute_force_ranges_fit_the_survivor_queue_entries():
+    """knng_brute_knn splits the base points into ranges; a survivor of the fp32 screen waits in a 32-bit
+    queue entry that holds its offset in the range in 26 bits.  The number of ranges can be read off
+    the workspace size (partial lists of nq x ranges x k keys, then 8 bytes per point, then 4 per
+    query): whatever n and nq, a range, rounded up to whole tiles of 64, has at most 2^26 points."""
+    def al(x):
+        return (x + 255) & ~255
+    k = 8
+    for n in (2, 65, 4096, 4097, 1_000_000, 20_000_000, (1 << 26) - 1, 1 << 26, (1 << 26) + 1,
+              3 * (1 << 26) + 5, (1 << 30) + 7, (1 << 31) - 1):
+        for nq in (1, 63, 64, 65, 5000, 20_000, 300_000):
+            if k > n - 1:
+                continue
+            b = knng.knng_brute_workspace_bytes(n, 16, k, nq)
+            assert b > 0 and b % 256 == 0
+            part = b - al(n * 8) - al(nq * 4)
+            # nq * nsplit * k * 8 rounded up to 256: the number of ranges is the largest that fits
+            nsplit = part // (nq * k * 8)
+            assert nsplit >= 1 and al(nq * nsplit * k * 8) == part
+            chunk = -(-n // nsplit)
+            chunk = -(-chunk // 64) * 64
+            assert chunk <= 1 << 26, (n, nq, nsplit, chunk)
+            assert nsplit <= 1024
+
+
 def test_error_text():
     lib = knng.load()
     assert lib.knng_strerror(0) == b"success"
     assert b"invalid" in lib.knng_strerror(-1)
     assert b"workspace" in lib.knng_strerror(-2)
+    assert b"invariant" in lib.knng_strerror(-5)
     assert lib.knng_strerror(-99) is not None
 
 
